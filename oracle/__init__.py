@@ -1,0 +1,29 @@
+"""CPU oracle for the batched-verify path.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, by-eye-checkable numpy implementation of what the HIP path
+computes: a Llama-style decoder forward over offloaded draft chunks against a
+paged KV cache, the per-token confidence statistics, and the greedy
+accept-prefix rule.  It exists so the tests can compare the GPU results with an
+independent implementation.  Only tests, the smoke check and the benchmark's
+CPU-baseline leg may import it; the product package never does, and this
+package never imports the product package.  It shares no code with the HIP
+path: only the seeded input draws (package `workloads`) serve both.
+
+Precision: every function takes a working dtype, float64 by default; the
+8B/70B-shaped parity runs use float32, the precision the benchmark spec fixes
+for the oracle.  Parameters and the KV cache hold bf16 values (the cache format
+is part of the method's state), widened exactly.
+
+Pins (tests/test_oracle_*.py): chunked == sequential == full prefill, paging and
+batch invariance, accept-rule properties and brute force, softmax/entropy closed
+forms, attention/RoPE/RMSNorm special cases, an independently written dense
+float64 decoder on the tiny config, and the capped-geometric expected accept
+length.  No function here is "parity unpinned".
+"""
+from .numerics import bf16_round, bf16_bits, bf16_from_bits  # noqa: F401
+from .confidence import confidence_row, confidence  # noqa: F401
+from .decoder import (  # noqa: F401
+    OracleModel, PagedKV, rmsnorm, rope, attention_one_query, decode_token, forward_tokens,
+    lm_head,
+)
+from .verify import accept_prefix, verify_chunks, draft_chain, prefill_context  # noqa: F401
