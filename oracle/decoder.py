@@ -83,6 +83,19 @@ class PagedKV:
         self.k[layer, b, :, s, :] = bf16_bits(k_row)
         self.v[layer, b, :, :, s] = bf16_bits(v_row)
 
+    def append_many(self, layer, block_table_row, start, k_rows, v_rows):
+        """Store K and V of positions start..start+n-1 ([n, kv_head, dim] each), page by page."""
+        n = len(k_rows)
+        kb, vb = bf16_bits(k_rows), bf16_bits(v_rows)
+        t = start
+        while t < start + n:
+            b = self._backing(block_table_row[t // PAGE])
+            s = t % PAGE
+            m = min(PAGE - s, start + n - t)
+            self.k[layer, b, :, s:s + m, :] = kb[t - start:t - start + m].transpose(1, 0, 2)
+            self.v[layer, b, :, :, s:s + m] = vb[t - start:t - start + m].transpose(1, 2, 0)
+            t += m
+
     def gather(self, layer, block_table_row, n):
         """K and V of positions 0..n-1, widened to float32: [n, kv_head, dim] each."""
         K = np.empty((n, self.n_kv_heads, self.head_dim), np.float32)

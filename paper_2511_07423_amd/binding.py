@@ -1,0 +1,221 @@
+"""ctypes binding with the same entry points as include/synera.h (marshalling only)."""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+OK, EINVAL, ERANGE, ENOSPC, EUNSUP, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6
+PAGE_SIZE = 16
+MAX_CHUNK = 32
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsynera.so")
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+if not os.path.exists(_LIB_PATH):
+    raise ImportError(
+        f"{_LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()'). "
+        "There is no CPU fallback.")
+_lib = C.CDLL(_LIB_PATH)
+
+_i32p = C.POINTER(C.c_int32)
+_vp = C.c_void_p
+
+
+class _ModelDesc(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_q_heads", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("d_ffn", C.c_int32),
+                ("vocab", C.c_int32), ("rope_base", C.c_float), ("rms_eps", C.c_float)]
+
+
+_LAYER_FIELDS = ("attn_norm", "wq", "wk", "wv", "wo", "mlp_norm", "w_gate", "w_up", "w_down")
+
+
+class _LayerWeights(C.Structure):
+    _fields_ = [(n, _vp) for n in _LAYER_FIELDS]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("embed", _vp), ("layers", C.POINTER(_LayerWeights)), ("final_norm", _vp), ("lm_head", _vp)]
+
+
+_lib.synera_version.restype = C.c_int32
+_lib.synera_strerror.restype = C.c_char_p
+_lib.synera_strerror.argtypes = [C.c_int32]
+_lib.synera_create.restype = C.c_int32
+_lib.synera_create.argtypes = [C.POINTER(_vp), C.POINTER(_ModelDesc), C.POINTER(_Weights), C.c_int32, C.c_int32,
+                               C.c_int32]
+_lib.synera_destroy.restype = C.c_int32
+_lib.synera_destroy.argtypes = [_vp]
+_lib.synera_validate_batch.restype = C.c_int32
+_lib.synera_validate_batch.argtypes = [C.c_int32, _i32p, _i32p, _i32p, _i32p, C.c_int32, C.c_int32, C.c_int32,
+                                       C.c_int64, C.c_int32]
+_lib.synera_verify.restype = C.c_int32
+_lib.synera_verify.argtypes = [_vp, C.c_int32, _i32p, _i32p, _i32p, _vp, _vp, _i32p, C.c_int32, C.c_int32, _vp, _vp,
+                               _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.synera_confidence.restype = C.c_int32
+_lib.synera_confidence.argtypes = [_vp, C.c_int32, C.c_int64, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp]
+_lib.synera_kv_append.restype = C.c_int32
+_lib.synera_kv_append.argtypes = [_vp, C.c_int32, C.c_int32, _i32p, _i32p, _vp, _vp, _i32p, C.c_int32, C.c_int32,
+                                  _vp, _vp, _vp]
+_lib.synera_gemm_bf16.restype = C.c_int32
+_lib.synera_gemm_bf16.argtypes = [_vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
+
+
+class SyneraError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {_lib.synera_strerror(status).decode()} ({status})")
+
+
+def _check(status, where):
+    if status != OK:
+        raise SyneraError(status, where)
+
+
+def version():
+    return _lib.synera_version()
+
+
+def _host_i32(a):
+    """contiguous int32 numpy array + its ctypes pointer (None passes NULL)."""
+    if a is None:
+        return None, None
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data_as(_i32p)
+
+
+def _dev(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("device tensors must be contiguous and on the GPU")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def validate_batch(ctx_len, n_first, n_second, block_table, n_pages_in_pool, max_batch, max_tokens,
+                   chunk_limit=MAX_CHUNK):
+    """Host-only check of a batch description; returns the status code (no GPU needed)."""
+    bt = np.ascontiguousarray(block_table, dtype=np.int32)
+    _, p_ctx = _host_i32(ctx_len)
+    _, p_a = _host_i32(n_first)
+    keep = [_host_i32(x) for x in (ctx_len, n_first, n_second)]
+    B = len(keep[0][0]) if keep[0][0] is not None else 0
+    max_pages = bt.shape[1] if bt.ndim == 2 else 0
+    return _lib.synera_validate_batch(B, keep[0][1], keep[1][1], keep[2][1], bt.ctypes.data_as(_i32p), max_pages,
+                                      n_pages_in_pool, max_batch, max_tokens, chunk_limit)
+
+
+def confidence(logits, want_prob=True, want_entropy=True):
+    """Per row: (argmax id int32, top-1 probability f32, entropy f32) of a 2-D f32 or bf16 GPU tensor."""
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be 2-D with unit column stride")
+    dt = {torch.float32: 0, torch.bfloat16: 1}[logits.dtype]
+    rows, vocab = logits.shape
+    dev = logits.device
+    ids = torch.empty(rows, dtype=torch.int32, device=dev)
+    p = torch.empty(rows, dtype=torch.float32, device=dev) if want_prob else None
+    h = torch.empty(rows, dtype=torch.float32, device=dev) if want_entropy else None
+    st = _lib.synera_confidence(logits.data_ptr(), dt, rows, vocab, logits.stride(0) if rows > 1 else vocab,
+                                ids.data_ptr(), _dev(p), _dev(h), _stream())
+    _check(st, "synera_confidence")
+    return ids, p, h
+
+
+def gemm_bf16(a, w):
+    """C = A W^T on the matrix cores; a bf16 [M,K], w bf16 [N,K] -> f32 [M,N]."""
+    M, K = a.shape
+    N = w.shape[0]
+    c = torch.empty((M, N), dtype=torch.float32, device=a.device)
+    st = _lib.synera_gemm_bf16(_dev(a, torch.bfloat16), _dev(w, torch.bfloat16), c.data_ptr(), M, N, K, _stream())
+    _check(st, "synera_gemm_bf16")
+    return c
+
+
+class Verifier:
+    """Owns a synera_ctx for one model.  `head` and `layers` are the bf16 GPU weight
+    tensors (dict / list of dicts with the field names of synera_layer_weights);
+    they are kept alive here because the context records their addresses."""
+
+    def __init__(self, shape, head, layers, max_batch, max_tokens, max_pages):
+        self.shape = shape
+        self._keep = (head, layers)
+        desc = _ModelDesc(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                          shape.d_ffn, shape.vocab, shape.rope_base, shape.rms_eps)
+        arr = (_LayerWeights * shape.n_layers)()
+        for l, lw in enumerate(layers):
+            for n in _LAYER_FIELDS:
+                setattr(arr[l], n, _dev(lw[n], torch.bfloat16))
+        w = _Weights(_dev(head["embed"], torch.bfloat16), arr, _dev(head["final_norm"], torch.bfloat16),
+                     _dev(head["lm_head"], torch.bfloat16))
+        self._ctx = _vp()
+        self.max_batch, self.max_tokens, self.max_pages = max_batch, max_tokens, max_pages
+        _check(_lib.synera_create(C.byref(self._ctx), C.byref(desc), C.byref(w), max_batch, max_tokens, max_pages),
+               "synera_create")
+
+    def close(self):
+        if self._ctx:
+            _lib.synera_destroy(self._ctx)
+            self._ctx = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def verify(self, ctx_len, n_uncached, n_draft, tokens, anchor, block_table, n_pages_in_pool, k_pool, v_pool,
+               want_logits=True, want_prob=True, want_entropy=True):
+        """One flattened ragged verify.  Host: ctx_len, n_uncached, n_draft, block_table (numpy int32).
+        Device: tokens int32 [T], anchor int32 [B], pools bf16.  Returns a dict of GPU tensors."""
+        a_ctx, p_ctx = _host_i32(ctx_len)
+        a_u, p_u = _host_i32(n_uncached)
+        a_k, p_k = _host_i32(n_draft)
+        bt = np.ascontiguousarray(block_table, dtype=np.int32)
+        B = len(a_ctx)
+        R = int(a_k.sum())
+        dev = tokens.device
+        V = self.shape.vocab
+        out = {
+            "logits": torch.empty((R, V), dtype=torch.float32, device=dev) if want_logits else None,
+            "argmax": torch.empty(R, dtype=torch.int32, device=dev),
+            "top1_prob": torch.empty(R, dtype=torch.float32, device=dev) if want_prob else None,
+            "entropy": torch.empty(R, dtype=torch.float32, device=dev) if want_entropy else None,
+            "accept_len": torch.empty(B, dtype=torch.int32, device=dev),
+            "correction": torch.empty(B, dtype=torch.int32, device=dev),
+        }
+        self.verify_into(a_ctx, a_u, a_k, tokens, anchor, bt, n_pages_in_pool, k_pool, v_pool, out)
+        return out
+
+    def verify_into(self, ctx_len, n_uncached, n_draft, tokens, anchor, block_table, n_pages_in_pool, k_pool, v_pool,
+                    out):
+        """Same call with caller-provided output tensors (int32 numpy metadata, no allocation here)."""
+        st = _lib.synera_verify(
+            self._ctx, len(ctx_len), ctx_len.ctypes.data_as(_i32p), n_uncached.ctypes.data_as(_i32p),
+            n_draft.ctypes.data_as(_i32p), _dev(tokens, torch.int32), _dev(anchor, torch.int32),
+            block_table.ctypes.data_as(_i32p), block_table.shape[1], n_pages_in_pool,
+            _dev(k_pool, torch.bfloat16), _dev(v_pool, torch.bfloat16), _dev(out["logits"]), _dev(out["argmax"]),
+            _dev(out["top1_prob"]), _dev(out["entropy"]), _dev(out["accept_len"]), _dev(out["correction"]),
+            _stream())
+        _check(st, "synera_verify")
+
+    def kv_append(self, layer, ctx_len, n_new, k, v, block_table, n_pages_in_pool, k_pool, v_pool):
+        """Scatter bf16 rows k, v [sum n_new, Hkv, hd] of one layer into the paged pools."""
+        a_ctx, p_ctx = _host_i32(ctx_len)
+        a_n, p_n = _host_i32(n_new)
+        bt = np.ascontiguousarray(block_table, dtype=np.int32)
+        st = _lib.synera_kv_append(self._ctx, layer, len(a_ctx), p_ctx, p_n, _dev(k, torch.bfloat16),
+                                   _dev(v, torch.bfloat16), bt.ctypes.data_as(_i32p), bt.shape[1], n_pages_in_pool,
+                                   _dev(k_pool, torch.bfloat16), _dev(v_pool, torch.bfloat16), _stream())
+        _check(st, "synera_kv_append")

@@ -1,0 +1,515 @@
+// Host side of the C ABI declared in include/synera.h: validation of the batch
+// description, the context with its device scratch, the per-call plan (flattening
+// of the ragged batch, attention work items) and the launch sequence of one verify.
+// No arithmetic of the method happens on the host.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/synera.h"
+#include "common.h"
+
+#define SY_VERSION 100
+#define N_STAGE 4              // metadata staging slots (calls may run this far ahead of the GPU)
+#define ATTN_TARGET_BLOCKS 1536
+
+#define HIP_TRY(expr)                       \
+  do {                                      \
+    if ((expr) != hipSuccess) {             \
+      (void)hipGetLastError();              \
+      return SYNERA_EHIP;                   \
+    }                                       \
+  } while (0)
+
+extern "C" int32_t synera_version(void) { return SY_VERSION; }
+
+extern "C" const char* synera_strerror(int32_t st) {
+  switch (st) {
+    case SYNERA_OK: return "ok";
+    case SYNERA_EINVAL: return "invalid argument";
+    case SYNERA_ERANGE: return "length or page id out of range, or page used twice";
+    case SYNERA_ENOSPC: return "capacity (batch, tokens, block table) too small";
+    case SYNERA_EUNSUP: return "unsupported shape or chunk length";
+    case SYNERA_EHIP: return "HIP runtime error or no usable device";
+    case SYNERA_ENOMEM: return "out of device memory";
+    default: return "unknown status";
+  }
+}
+
+// ------------------------------------------------------------------------------------ validation
+extern "C" int32_t synera_validate_batch(int32_t B, const int32_t* h_ctx_len, const int32_t* h_n_first,
+                                         const int32_t* h_n_second, const int32_t* h_block_table,
+                                         int32_t max_pages, int32_t n_pages_in_pool, int32_t max_batch,
+                                         int64_t max_tokens, int32_t chunk_limit) {
+  if (!h_ctx_len || !h_n_first || !h_block_table) return SYNERA_EINVAL;
+  if (B < 1 || max_pages < 1 || n_pages_in_pool < 1) return SYNERA_EINVAL;
+  if (B > max_batch) return SYNERA_ENOSPC;
+  int64_t total = 0;
+  for (int i = 0; i < B; ++i) {
+    const int32_t second = h_n_second ? h_n_second[i] : 0;
+    if (h_n_first[i] < 1 || second < 0) return SYNERA_EINVAL;
+    if (h_ctx_len[i] < 0) return SYNERA_ERANGE;
+    const int64_t chunk = (int64_t)h_n_first[i] + second;
+    if (chunk_limit > 0 && chunk > chunk_limit) return SYNERA_EUNSUP;
+    total += chunk;
+    const int64_t need = ((int64_t)h_ctx_len[i] + chunk + SYNERA_PAGE_SIZE - 1) / SYNERA_PAGE_SIZE;
+    if (need > max_pages) return SYNERA_ENOSPC;
+  }
+  if (total > max_tokens) return SYNERA_ENOSPC;
+  std::vector<uint8_t> used((size_t)n_pages_in_pool, 0);
+  for (int i = 0; i < B; ++i) {
+    const int64_t chunk = (int64_t)h_n_first[i] + (h_n_second ? h_n_second[i] : 0);
+    const int64_t need = ((int64_t)h_ctx_len[i] + chunk + SYNERA_PAGE_SIZE - 1) / SYNERA_PAGE_SIZE;
+    for (int64_t p = 0; p < need; ++p) {
+      const int32_t id = h_block_table[(size_t)i * max_pages + p];
+      if (id < 0 || id >= n_pages_in_pool) return SYNERA_ERANGE;
+      if (used[id]) return SYNERA_ERANGE;
+      used[id] = 1;
+    }
+  }
+  return SYNERA_OK;
+}
+
+// ------------------------------------------------------------------------------------ context
+struct synera_ctx {
+  synera_model_desc desc;
+  std::vector<synera_layer_weights> layers;
+  const void* embed;
+  const void* final_norm;
+  const void* lm_head;
+  int32_t max_batch, max_tokens, max_pages, max_rows, items_cap, rows_per_group_tokens;
+  int device;
+  // device scratch (one allocation)
+  char* arena;
+  float* x;
+  bf16_t* y;
+  float* qkv;
+  bf16_t* q;
+  bf16_t* o;
+  bf16_t* act;
+  bf16_t* ysel;
+  float* logits;
+  int32_t* lm_ids;
+  float* lm_p;
+  float* lm_h;
+  float2* cs;
+  float* part_o;
+  float* part_ml;
+  // metadata staging ring
+  size_t meta_cap;             // bytes per slot
+  int32_t* h_meta[N_STAGE];    // pinned host
+  int32_t* d_meta[N_STAGE];
+  hipEvent_t done[N_STAGE];
+  bool pending[N_STAGE];
+  uint64_t calls;
+};
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc, const synera_weights* w,
+                                 int32_t max_batch, int32_t max_tokens, int32_t max_pages) {
+  if (!out) return SYNERA_EINVAL;
+  *out = nullptr;
+  if (!desc || !w || !w->layers || !w->embed || !w->final_norm || !w->lm_head) return SYNERA_EINVAL;
+  if (max_batch < 1 || max_tokens < 1 || max_pages < 1) return SYNERA_EINVAL;
+  const synera_model_desc& m = *desc;
+  if (m.n_layers < 1 || m.d_model < 1 || m.n_q_heads < 1 || m.n_kv_heads < 1 || m.d_ffn < 1 || m.vocab < 1)
+    return SYNERA_EINVAL;
+  if (!(m.rope_base > 1.0f) || !(m.rms_eps >= 0.0f)) return SYNERA_EINVAL;
+  if (m.head_dim != 64 && m.head_dim != 128) return SYNERA_EUNSUP;
+  if (m.n_q_heads % m.n_kv_heads != 0 || m.n_q_heads / m.n_kv_heads > 16) return SYNERA_EUNSUP;
+  const int64_t qd = (int64_t)m.n_q_heads * m.head_dim, kd = (int64_t)m.n_kv_heads * m.head_dim;
+  // GEMM tiles are 128 output columns by 64 of K; Wq | Wk | Wv are segments of one launch.
+  if (m.d_model % 128 || m.d_ffn % 64 || m.vocab % 128 || qd % 128 || kd % 128) return SYNERA_EUNSUP;
+  for (int l = 0; l < m.n_layers; ++l) {
+    const synera_layer_weights& lw = w->layers[l];
+    if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.mlp_norm || !lw.w_gate || !lw.w_up ||
+        !lw.w_down)
+      return SYNERA_EINVAL;
+  }
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+
+  synera_ctx* c = new (std::nothrow) synera_ctx();
+  if (!c) return SYNERA_ENOMEM;
+  c->desc = m;
+  c->layers.assign(w->layers, w->layers + m.n_layers);
+  c->embed = w->embed;
+  c->final_norm = w->final_norm;
+  c->lm_head = w->lm_head;
+  c->max_batch = max_batch;
+  c->max_tokens = max_tokens;
+  c->max_pages = max_pages;
+  c->max_rows = max_tokens + max_batch;
+  c->device = dev;
+  const int G = m.n_q_heads / m.n_kv_heads;
+  c->rows_per_group_tokens = std::max(1, 64 / G);
+  const int rg_max = (SYNERA_MAX_CHUNK + c->rows_per_group_tokens - 1) / c->rows_per_group_tokens;
+  c->items_cap = ATTN_TARGET_BLOCKS + max_batch * rg_max;
+
+  const size_t T = (size_t)max_tokens, R = (size_t)c->max_rows;
+  const size_t qkv_dim = (size_t)(qd + 2 * kd);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+  const size_t o_x = take(T * m.d_model * 4), o_y = take(T * m.d_model * 2), o_qkv = take(T * qkv_dim * 4);
+  const size_t o_q = take(T * qd * 2), o_o = take(T * qd * 2), o_act = take(T * (size_t)m.d_ffn * 2);
+  const size_t o_ysel = take(R * m.d_model * 2), o_logits = take(R * (size_t)m.vocab * 4);
+  const size_t o_ids = take(R * 4), o_p = take(R * 4), o_h = take(R * 4);
+  const size_t o_cs = take(T * (m.head_dim / 2) * 8);
+  const size_t o_po = take((size_t)c->items_cap * m.n_kv_heads * 64 * m.head_dim * 4);
+  const size_t o_pml = take((size_t)c->items_cap * m.n_kv_heads * 64 * 2 * 4);
+  if (hipMalloc(reinterpret_cast<void**>(&c->arena), off) != hipSuccess) {
+    (void)hipGetLastError();
+    delete c;
+    return SYNERA_ENOMEM;
+  }
+  c->x = reinterpret_cast<float*>(c->arena + o_x);
+  c->y = reinterpret_cast<bf16_t*>(c->arena + o_y);
+  c->qkv = reinterpret_cast<float*>(c->arena + o_qkv);
+  c->q = reinterpret_cast<bf16_t*>(c->arena + o_q);
+  c->o = reinterpret_cast<bf16_t*>(c->arena + o_o);
+  c->act = reinterpret_cast<bf16_t*>(c->arena + o_act);
+  c->ysel = reinterpret_cast<bf16_t*>(c->arena + o_ysel);
+  c->logits = reinterpret_cast<float*>(c->arena + o_logits);
+  c->lm_ids = reinterpret_cast<int32_t*>(c->arena + o_ids);
+  c->lm_p = reinterpret_cast<float*>(c->arena + o_p);
+  c->lm_h = reinterpret_cast<float*>(c->arena + o_h);
+  c->cs = reinterpret_cast<float2*>(c->arena + o_cs);
+  c->part_o = reinterpret_cast<float*>(c->arena + o_po);
+  c->part_ml = reinterpret_cast<float*>(c->arena + o_pml);
+
+  const size_t meta_ints = (size_t)max_batch * 5 + 2 + (size_t)max_tokens + (size_t)c->max_rows +
+                           (size_t)max_batch * max_pages + (size_t)max_tokens * 4 + (size_t)c->items_cap * 8 + 64;
+  c->meta_cap = align_up(meta_ints * 4, 256);
+  for (int s = 0; s < N_STAGE; ++s) {
+    c->h_meta[s] = nullptr;
+    c->d_meta[s] = nullptr;
+    c->done[s] = nullptr;
+    c->pending[s] = false;
+  }
+  bool ok = true;
+  for (int s = 0; s < N_STAGE && ok; ++s) {
+    ok = hipHostMalloc(reinterpret_cast<void**>(&c->h_meta[s]), c->meta_cap, hipHostMallocDefault) == hipSuccess &&
+         hipMalloc(reinterpret_cast<void**>(&c->d_meta[s]), c->meta_cap) == hipSuccess &&
+         hipEventCreateWithFlags(&c->done[s], hipEventDisableTiming) == hipSuccess;
+  }
+  if (!ok) {
+    (void)hipGetLastError();
+    synera_destroy(c);
+    return SYNERA_ENOMEM;
+  }
+  c->calls = 0;
+  *out = c;
+  return SYNERA_OK;
+}
+
+extern "C" int32_t synera_destroy(synera_ctx* c) {
+  if (!c) return SYNERA_OK;
+  (void)hipDeviceSynchronize();
+  for (int s = 0; s < N_STAGE; ++s) {
+    if (c->done[s]) (void)hipEventDestroy(c->done[s]);
+    if (c->h_meta[s]) (void)hipHostFree(c->h_meta[s]);
+    if (c->d_meta[s]) (void)hipFree(c->d_meta[s]);
+  }
+  if (c->arena) (void)hipFree(c->arena);
+  delete c;
+  return SYNERA_OK;
+}
+
+// ------------------------------------------------------------------------------------ per-call plan
+struct Plan {
+  BatchMeta meta;
+  const AttnItem* d_items;
+  const AttnCombine* d_comb;
+  int32_t class_begin[4];
+  int32_t T, R, R_all;      // chunk tokens, draft rows, LM-head rows (drafts + last-uncached rows)
+  bool any_split;
+  int slot;
+};
+
+// Lays the metadata out in the staging slot, uploads it, and returns device pointers.
+// n_second == nullptr means "append only": no LM rows, no attention items.
+static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, const int32_t* n_unc,
+                          const int32_t* n_draft, const int32_t* block_table, int32_t max_pages, bool with_attention,
+                          hipStream_t stream, Plan& p) {
+  const int slot = (int)(c->calls % N_STAGE);
+  if (c->pending[slot]) {
+    HIP_TRY(hipEventSynchronize(c->done[slot]));
+    c->pending[slot] = false;
+  }
+  int32_t* h = c->h_meta[slot];
+  int32_t* d = c->d_meta[slot];
+  size_t at = 0;
+  auto region = [&](size_t n) { size_t r = at; at += n; return r; };
+  const size_t o_ctx = region(B), o_cu = region(B + 1), o_cud = region(B + 1), o_first = region(B), o_unc = region(B);
+  int32_t T = 0, R = 0;
+  for (int i = 0; i < B; ++i) {
+    const int u = n_unc ? n_unc[i] : 0;
+    h[o_ctx + i] = ctx_len[i];
+    h[o_cu + i] = T;
+    h[o_cud + i] = R;
+    h[o_unc + i] = u;
+    T += u + n_draft[i];
+    R += n_draft[i];
+  }
+  h[o_cu + B] = T;
+  h[o_cud + B] = R;
+  const size_t o_bt = region((size_t)B * max_pages);
+  std::memcpy(h + o_bt, block_table, (size_t)B * max_pages * sizeof(int32_t));
+  size_t o_req = 0, o_sel = 0, o_comb = 0, o_items = 0;
+  int32_t R_all = R;
+  p.any_split = false;
+  p.class_begin[0] = p.class_begin[1] = p.class_begin[2] = p.class_begin[3] = 0;
+  if (with_attention) {
+    o_req = region(T);
+    o_sel = region((size_t)R + B);
+    for (int i = 0; i < B; ++i) {
+      const int u = n_unc[i], base = h[o_cu + i];
+      for (int j = 0; j < u + n_draft[i]; ++j) h[o_req + base + j] = i;
+      for (int j = 0; j < n_draft[i]; ++j) h[o_sel + h[o_cud + i] + j] = base + u + j;
+    }
+    for (int i = 0; i < B; ++i) {           // rows of the last uncached tokens follow the draft rows
+      if (n_unc[i] > 0) {
+        h[o_first + i] = R_all;
+        h[o_sel + R_all] = h[o_cu + i] + n_unc[i] - 1;
+        ++R_all;
+      } else {
+        h[o_first + i] = -1;
+      }
+    }
+    at = (at + 3) & ~(size_t)3;             // 16-byte alignment for the structs
+    o_comb = region((size_t)T * 4);
+    o_items = region((size_t)c->items_cap * 8);
+
+    // Attention work items.  A row group is up to `tg` chunk tokens (x G heads <= 64 rows);
+    // its keys 0 .. L+j_last are cut into ranges of `chunk` keys (a multiple of 128).
+    const int G = c->desc.n_q_heads / c->desc.n_kv_heads;
+    const int tg = c->rows_per_group_tokens;
+    int64_t key_work = 0;
+    for (int i = 0; i < B; ++i) {
+      const int qn = n_unc[i] + n_draft[i];
+      for (int j0 = 0; j0 < qn; j0 += tg) key_work += (int64_t)ctx_len[i] + std::min(qn, j0 + tg);
+    }
+    int64_t chunk = (key_work * c->desc.n_kv_heads + ATTN_TARGET_BLOCKS - 1) / ATTN_TARGET_BLOCKS;
+    chunk = std::max<int64_t>(256, (chunk + 127) / 128 * 128);
+    std::vector<AttnItem> items[3];
+    AttnCombine* comb = reinterpret_cast<AttnCombine*>(h + o_comb);
+    int32_t n_part = 0;
+    for (int i = 0; i < B; ++i) {
+      const int qn = n_unc[i] + n_draft[i];
+      for (int j0 = 0; j0 < qn; j0 += tg) {
+        const int ntok = std::min(tg, qn - j0);
+        const int keys = ctx_len[i] + j0 + ntok;
+        const int nsplit = (int)((keys + chunk - 1) / chunk);
+        const int rows = ntok * G;
+        const int cls = rows <= 16 ? 0 : (rows <= 32 ? 1 : 2);
+        const int part0 = nsplit > 1 ? n_part : -1;
+        for (int s = 0; s < nsplit; ++s) {
+          AttnItem it;
+          it.req = i;
+          it.tok0 = h[o_cu + i] + j0;
+          it.j0 = j0;
+          it.ntok = ntok;
+          it.ctx_len = ctx_len[i];
+          it.key_begin = (int32_t)(s * chunk);
+          it.key_end = (int32_t)std::min<int64_t>(keys, (s + 1) * chunk);
+          it.part = nsplit > 1 ? n_part++ : -1;
+          items[cls].push_back(it);
+        }
+        for (int j = 0; j < ntok; ++j) {
+          AttnCombine& cb = comb[h[o_cu + i] + j0 + j];
+          cb.part0 = part0;
+          cb.nsplit = nsplit;
+          cb.row0 = j * G;
+          cb.pad = 0;
+        }
+        if (nsplit > 1) p.any_split = true;
+      }
+    }
+    const size_t n_items = items[0].size() + items[1].size() + items[2].size();
+    if (n_items > (size_t)c->items_cap) return SYNERA_ENOSPC;   // cannot happen by construction of `chunk`
+    AttnItem* hi = reinterpret_cast<AttnItem*>(h + o_items);
+    size_t w = 0;
+    for (int cls = 0; cls < 3; ++cls) {
+      p.class_begin[cls] = (int32_t)w;
+      for (const AttnItem& it : items[cls]) hi[w++] = it;
+    }
+    p.class_begin[3] = (int32_t)w;
+    at = o_items + w * 8;
+  }
+  if (at * 4 > c->meta_cap) return SYNERA_ENOSPC;
+  HIP_TRY(hipMemcpyAsync(d, h, at * 4, hipMemcpyHostToDevice, stream));
+  p.meta.ctx_len = d + o_ctx;
+  p.meta.cu_tok = d + o_cu;
+  p.meta.cu_draft = d + o_cud;
+  p.meta.first_row = d + o_first;
+  p.meta.n_unc = d + o_unc;
+  p.meta.block_table = d + o_bt;
+  p.meta.tok_req = d + o_req;
+  p.meta.sel_rows = d + o_sel;
+  p.meta.max_pages = max_pages;
+  p.d_comb = reinterpret_cast<const AttnCombine*>(d + o_comb);
+  p.d_items = reinterpret_cast<const AttnItem*>(d + o_items);
+  p.T = T;
+  p.R = R;
+  p.R_all = R_all;
+  p.slot = slot;
+  return SYNERA_OK;
+}
+
+static int32_t finish_call(synera_ctx* c, const Plan& p, hipStream_t stream) {
+  HIP_TRY(hipEventRecord(c->done[p.slot], stream));
+  c->pending[p.slot] = true;
+  c->calls++;
+  return SYNERA_OK;
+}
+
+static int32_t run_gemm(const bf16_t* a, const void* w0, int r0, const void* w1, int r1, const void* w2, int r2,
+                        void* cbuf, int M, int N, int K, int epi, hipStream_t s) {
+  GemmArgs g;
+  g.a = a;
+  g.w[0] = static_cast<const bf16_t*>(w0);
+  g.w[1] = static_cast<const bf16_t*>(w1);
+  g.w[2] = static_cast<const bf16_t*>(w2);
+  g.w_rows[0] = r0;
+  g.w_rows[1] = r1;
+  g.w_rows[2] = r2;
+  g.c = cbuf;
+  g.M = M;
+  g.N = N;
+  g.K = K;
+  g.epilogue = epi;
+  g.split_k = (epi == GEMM_SWIGLU_BF16) ? 1 : gemm_pick_split(M, N, K);
+  if (epi == GEMM_STORE_F32 && g.split_k > 1) HIP_TRY(launch_fill_zero(static_cast<float*>(cbuf), (size_t)M * N, s));
+  HIP_TRY(launch_gemm(g, s));
+  return SYNERA_OK;
+}
+
+// ------------------------------------------------------------------------------------ verify
+extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_len, const int32_t* h_n_uncached,
+                                 const int32_t* h_n_draft, const int32_t* d_tokens, const int32_t* d_anchor,
+                                 const int32_t* h_block_table, int32_t max_pages, int32_t n_pages_in_pool,
+                                 void* d_k_pool, void* d_v_pool, float* d_logits, int32_t* d_argmax,
+                                 float* d_top1_prob, float* d_entropy, int32_t* d_accept_len,
+                                 int32_t* d_correction, void* stream_) {
+  if (!c || !h_n_uncached || !d_tokens || !d_anchor || !d_k_pool || !d_v_pool || !d_argmax || !d_accept_len ||
+      !d_correction)
+    return SYNERA_EINVAL;
+  if (max_pages > c->max_pages) return SYNERA_ENOSPC;
+  int32_t st = synera_validate_batch(B, h_ctx_len, h_n_draft, h_n_uncached, h_block_table, max_pages,
+                                     n_pages_in_pool, c->max_batch, c->max_tokens, SYNERA_MAX_CHUNK);
+  if (st != SYNERA_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream_);
+  const synera_model_desc& m = c->desc;
+  Plan p;
+  st = build_plan(c, B, h_ctx_len, h_n_uncached, h_n_draft, h_block_table, max_pages, true, s, p);
+  if (st != SYNERA_OK) return st;
+
+  const int T = p.T, d = m.d_model, Hq = m.n_q_heads, Hkv = m.n_kv_heads, hd = m.head_dim;
+  const int qd = Hq * hd, kd = Hkv * hd;
+  const size_t layer_elems = (size_t)n_pages_in_pool * Hkv * SY_PAGE * hd;
+  HIP_TRY(launch_embed(static_cast<const bf16_t*>(c->embed), d_tokens, c->x, T, d, s));
+  HIP_TRY(launch_rope_table(p.meta, c->cs, T, hd, m.rope_base, s));
+
+  AttnLaunch al;
+  al.q = c->q;
+  al.block_table = p.meta.block_table;
+  al.max_pages = max_pages;
+  al.items = p.d_items;
+  for (int i = 0; i < 4; ++i) al.class_begin[i] = p.class_begin[i];
+  al.comb = p.d_comb;
+  al.part_o = c->part_o;
+  al.part_ml = c->part_ml;
+  al.o = c->o;
+  al.T = T;
+  al.Hq = Hq;
+  al.Hkv = Hkv;
+  al.hd = hd;
+  al.any_split = p.any_split ? 1 : 0;
+
+  for (int l = 0; l < m.n_layers; ++l) {
+    const synera_layer_weights& w = c->layers[l];
+    bf16_t* k_layer = static_cast<bf16_t*>(d_k_pool) + (size_t)l * layer_elems;
+    bf16_t* v_layer = static_cast<bf16_t*>(d_v_pool) + (size_t)l * layer_elems;
+    HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.attn_norm), nullptr, c->y, T, d, m.rms_eps, s));
+    if ((st = run_gemm(c->y, w.wq, qd, w.wk, kd, w.wv, kd, c->qkv, T, qd + 2 * kd, d, GEMM_STORE_F32, s))) return st;
+    HIP_TRY(launch_rope_append(c->qkv, c->cs, p.meta, c->q, k_layer, v_layer, T, Hq, Hkv, hd, s));
+    al.k_layer = k_layer;
+    al.v_layer = v_layer;
+    HIP_TRY(launch_attention(al, s));
+    if ((st = run_gemm(c->o, w.wo, d, nullptr, 0, nullptr, 0, c->x, T, d, qd, GEMM_ADD_F32, s))) return st;
+    HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.mlp_norm), nullptr, c->y, T, d, m.rms_eps, s));
+    if ((st = run_gemm(c->y, w.w_gate, 0, w.w_up, 0, nullptr, 0, c->act, T, 2 * m.d_ffn, d, GEMM_SWIGLU_BF16, s)))
+      return st;
+    if ((st = run_gemm(c->act, w.w_down, d, nullptr, 0, nullptr, 0, c->x, T, d, m.d_ffn, GEMM_ADD_F32, s))) return st;
+  }
+
+  // LM head over the draft rows (plus the last uncached row of requests that have one).
+  const bool extra = p.R_all > p.R;
+  HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(c->final_norm), p.meta.sel_rows, c->ysel, p.R_all, d,
+                         m.rms_eps, s));
+  float* logits = (d_logits && !extra) ? d_logits : c->logits;
+  if ((st = run_gemm(c->ysel, c->lm_head, m.vocab, nullptr, 0, nullptr, 0, logits, p.R_all, m.vocab, d,
+                     GEMM_STORE_F32, s)))
+    return st;
+  float* p_out = (d_top1_prob && !extra) ? d_top1_prob : c->lm_p;
+  float* h_out = (d_entropy && !extra) ? d_entropy : c->lm_h;
+  HIP_TRY(launch_confidence(logits, 0, p.R_all, m.vocab, m.vocab, c->lm_ids, p_out, h_out, s));
+  if (extra) {
+    if (d_logits)
+      HIP_TRY(hipMemcpyAsync(d_logits, c->logits, (size_t)p.R * m.vocab * 4, hipMemcpyDeviceToDevice, s));
+    if (d_top1_prob) HIP_TRY(hipMemcpyAsync(d_top1_prob, c->lm_p, (size_t)p.R * 4, hipMemcpyDeviceToDevice, s));
+    if (d_entropy) HIP_TRY(hipMemcpyAsync(d_entropy, c->lm_h, (size_t)p.R * 4, hipMemcpyDeviceToDevice, s));
+  }
+  HIP_TRY(launch_accept(d_tokens, d_anchor, c->lm_ids, p.meta, B, p.R, d_argmax, d_accept_len, d_correction, s));
+  return finish_call(c, p, s);
+}
+
+// ------------------------------------------------------------------------------------ confidence
+extern "C" int32_t synera_confidence(const void* d_logits, int32_t dtype, int64_t rows, int64_t vocab,
+                                     int64_t row_stride_elems, int32_t* d_top1_id, float* d_top1_prob,
+                                     float* d_entropy, void* stream) {
+  if (rows < 0 || vocab < 1 || (dtype != 0 && dtype != 1)) return SYNERA_EINVAL;
+  if (rows == 0) return SYNERA_OK;
+  if (!d_logits || !d_top1_id || row_stride_elems < vocab) return SYNERA_EINVAL;
+  if (rows > 0x7FFFFFFF || vocab > 0x7FFFFFFF) return SYNERA_EINVAL;
+  const int64_t align = dtype == 1 ? 8 : 4;
+  if (row_stride_elems % align != 0 || (reinterpret_cast<uintptr_t>(d_logits) & 15) != 0) return SYNERA_EINVAL;
+  HIP_TRY(launch_confidence(d_logits, dtype, rows, vocab, row_stride_elems, d_top1_id, d_top1_prob, d_entropy,
+                            static_cast<hipStream_t>(stream)));
+  return SYNERA_OK;
+}
+
+// ------------------------------------------------------------------------------------ kv append
+extern "C" int32_t synera_kv_append(synera_ctx* c, int32_t layer, int32_t B, const int32_t* h_ctx_len,
+                                    const int32_t* h_n_new, const void* d_k, const void* d_v,
+                                    const int32_t* h_block_table, int32_t max_pages, int32_t n_pages_in_pool,
+                                    void* d_k_pool, void* d_v_pool, void* stream_) {
+  if (!c || !d_k || !d_v || !d_k_pool || !d_v_pool) return SYNERA_EINVAL;
+  if (layer < 0 || layer >= c->desc.n_layers) return SYNERA_EINVAL;
+  if (max_pages > c->max_pages) return SYNERA_ENOSPC;
+  int32_t st = synera_validate_batch(B, h_ctx_len, h_n_new, nullptr, h_block_table, max_pages, n_pages_in_pool,
+                                     c->max_batch, INT64_MAX, 0);
+  if (st != SYNERA_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream_);
+  Plan p;
+  st = build_plan(c, B, h_ctx_len, nullptr, h_n_new, h_block_table, max_pages, false, s, p);
+  if (st != SYNERA_OK) return st;
+  const int Hkv = c->desc.n_kv_heads, hd = c->desc.head_dim;
+  const size_t layer_elems = (size_t)n_pages_in_pool * Hkv * SY_PAGE * hd;
+  HIP_TRY(launch_kv_append(static_cast<const bf16_t*>(d_k), static_cast<const bf16_t*>(d_v), p.meta, B,
+                           static_cast<bf16_t*>(d_k_pool) + (size_t)layer * layer_elems,
+                           static_cast<bf16_t*>(d_v_pool) + (size_t)layer * layer_elems, p.T, Hkv, hd, s));
+  return finish_call(c, p, s);
+}
+
+// ------------------------------------------------------------------------------------ plain GEMM
+extern "C" int32_t synera_gemm_bf16(const void* d_a, const void* d_w, float* d_c, int32_t M, int32_t N, int32_t K,
+                                    void* stream) {
+  if (!d_a || !d_w || !d_c || M < 1 || N < 1 || K < 1) return SYNERA_EINVAL;
+  if (N % 128 != 0 || K % 64 != 0) return SYNERA_EUNSUP;
+  return run_gemm(static_cast<const bf16_t*>(d_a), d_w, N, nullptr, 0, nullptr, 0, d_c, M, N, K, GEMM_STORE_F32,
+                  static_cast<hipStream_t>(stream));
+}

@@ -1,0 +1,99 @@
+// Shared declarations of the HIP sources: vector types for the gfx950 matrix
+// cores, launch helpers, and the host-side launchers each .hip file exports to
+// the orchestration code in synera.cpp.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint16_t bf16_t;  // raw bf16 bits in memory
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+#define SY_PAGE 16
+
+// Round-to-nearest-even fp32 -> bf16 bits (finite inputs).
+__device__ __forceinline__ uint32_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) { return f2bf(lo) | (f2bf(hi) << 16); }
+
+// ---------------------------------------------------------------- elementwise.hip
+struct BatchMeta {        // device pointers into one uploaded metadata blob (all int32)
+  const int32_t* ctx_len;      // [B]
+  const int32_t* cu_tok;       // [B+1] prefix sums of chunk lengths (u_i + k_i)
+  const int32_t* block_table;  // [B][max_pages]
+  const int32_t* tok_req;      // [T] request of each flattened chunk token
+  const int32_t* sel_rows;     // [R'] chunk-token index feeding LM-head row r
+  const int32_t* cu_draft;     // [B+1] prefix sums of k_i (output row offsets)
+  const int32_t* first_row;    // [B] LM-head row of the last uncached token, or -1
+  const int32_t* n_unc;        // [B]
+  int32_t max_pages;
+};
+
+hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, int T, int d, hipStream_t s);
+hipError_t launch_rmsnorm(const float* x, const bf16_t* gain, const int32_t* rows, bf16_t* y, int n_rows, int d,
+                          float eps, hipStream_t s);
+hipError_t launch_rope_table(const BatchMeta& m, float2* cs, int T, int head_dim, float base, hipStream_t s);
+hipError_t launch_rope_append(const float* qkv, const float2* cs, const BatchMeta& m, bf16_t* q, bf16_t* k_layer,
+                              bf16_t* v_layer, int T, int Hq, int Hkv, int hd, hipStream_t s);
+hipError_t launch_kv_append(const bf16_t* k, const bf16_t* v, const BatchMeta& m, int B, bf16_t* k_layer,
+                            bf16_t* v_layer, int T, int Hkv, int hd, hipStream_t s);
+hipError_t launch_accept(const int32_t* tokens, const int32_t* anchor, const int32_t* lm_argmax, const BatchMeta& m,
+                         int B, int R, int32_t* out_argmax, int32_t* accept_len, int32_t* correction,
+                         hipStream_t s);
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
+
+// ---------------------------------------------------------------- confidence.hip
+hipError_t launch_confidence(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride,
+                             int32_t* ids, float* p1, float* H, hipStream_t s);
+
+// ---------------------------------------------------------------- attention.hip
+struct AttnItem {      // one (request, row group, key range); uploaded with the metadata
+  int32_t req;         // request index
+  int32_t tok0;        // flattened index of the group's first chunk token
+  int32_t j0;          // its index inside the request's chunk
+  int32_t ntok;        // chunk tokens in the group (rows = ntok * G <= 64)
+  int32_t ctx_len;     // L_i
+  int32_t key_begin;   // multiple of 32
+  int32_t key_end;     // exclusive, <= L_i + j0 + ntok
+  int32_t part;        // partial-result slot, or -1: this item is the only split and writes o
+};
+struct AttnCombine {   // per chunk token: where its partials live
+  int32_t part0;       // first partial slot of its row group, -1 if written directly
+  int32_t nsplit;
+  int32_t row0;        // (j - j0) * G: first row of this token inside the group
+  int32_t pad;
+};
+struct AttnLaunch {
+  const bf16_t* q;           // [T][Hq][hd]
+  const bf16_t* k_layer;     // pool of this layer
+  const bf16_t* v_layer;
+  const int32_t* block_table;
+  int32_t max_pages;
+  const AttnItem* items;     // device; items of row-block class c are items[class_begin[c] .. class_begin[c+1])
+  int32_t class_begin[4];    // classes: rows <= 16, <= 32, <= 64
+  const AttnCombine* comb;   // [T]
+  float* part_o;             // [slots][Hkv][64][hd]
+  float* part_ml;            // [slots][Hkv][64][2]
+  bf16_t* o;                 // [T][Hq][hd]
+  int32_t T, Hq, Hkv, hd;
+  int32_t any_split;
+};
+hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
+
+// ---------------------------------------------------------------- gemm.hip
+enum GemmEpilogue { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };
+struct GemmArgs {
+  const bf16_t* a;       // [M][K]
+  const bf16_t* w[3];    // up to three row segments of the weight (each [rows][K])
+  int32_t w_rows[3];     // rows per segment (multiples of the N tile); unused = 0
+  void* c;               // f32 [M][N] (STORE/ADD) or bf16 [M][N/2] (SWIGLU: w[0] = gate, w[1] = up)
+  int32_t M, N, K;       // N = total output columns of the contraction (gate + up for SWIGLU)
+  int32_t epilogue;
+  int32_t split_k;       // >= 1; > 1 only with STORE (pre-zeroed C) or ADD: partial sums are added atomically
+};
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
+int gemm_pick_split(int M, int N, int K);

@@ -1,0 +1,152 @@
+"""GPU parity of the stand-alone entry points (confidence, KV append, GEMM) through the C ABI."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _synera():
+    import paper_2511_07423_amd as synera
+    return synera
+
+
+def _check_conf(logits_t, name):
+    synera = _synera()
+    ids, p, H = synera.confidence(logits_t)
+    torch.cuda.synchronize()
+    x = logits_t.detach().to("cpu", torch.float32).numpy().astype(np.float64)
+    wi, wp, wH, mg = oracle.confidence(x)
+    ids, p, H = ids.cpu().numpy(), p.cpu().numpy(), H.cpu().numpy()
+    assert np.array_equal(ids, wi), f"{name}: argmax differs at rows {np.nonzero(ids != wi)[0][:8]}"
+    assert np.all(np.abs(p - wp) <= 1e-4 * wp + 1e-12), f"{name}: prob rel err {np.max(np.abs(p - wp) / wp):.3e}"
+    assert np.all(np.abs(H - wH) <= 1e-3 * wH + 1e-6), f"{name}: entropy err {np.max(np.abs(H - wH)):.3e}"
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("rows,vocab", [(1, 8), (3, 40), (5, 1000), (7, 4096), (4, 32000), (2, 128256), (9, 1037)])
+def test_confidence_matches_oracle(dtype, rows, vocab):
+    g = torch.Generator(device=DEV).manual_seed(rows * 100003 + vocab)
+    wide = (vocab + 7) // 8 * 8                      # rows must start 16-byte aligned; the tail may be ragged
+    x = (torch.randn((rows, wide), generator=g, device=DEV) * 3).to(dtype)[:, :vocab]
+    _check_conf(x, f"{rows}x{vocab}")
+
+
+def test_confidence_workload_recipe_strided_and_ties():
+    synera = _synera()
+    x = wl.draw_confidence_logits(64, 128256, 3.0, 10.0, 42, DEV, torch.bfloat16)
+    _check_conf(x, "c5b recipe")
+    # rows taken from a wider buffer (stride > vocab), f32
+    wide = torch.randn((6, 2048), device=DEV)
+    _check_conf(wide[:, :1000], "strided")
+    # exact ties: lowest id wins, also across threads / wavefronts / vector lanes
+    t = torch.zeros((4, 5000), device=DEV)
+    t[0, [4097, 13, 4999]] = 2.0
+    t[1, [4999]] = 1.0
+    t[2, :] = -7.5
+    t[3, [1027, 1026]] = 0.5
+    ids, p, H = synera.confidence(t)
+    assert ids.cpu().tolist() == [13, 4999, 0, 1026]
+    assert p[2].item() == pytest.approx(1 / 5000, rel=1e-5) and H[2].item() == pytest.approx(math.log(5000), rel=1e-5)
+    # peaked rows: p -> 1, H -> 0
+    t = torch.full((2, 4096), -50.0, device=DEV)
+    t[0, 7] = 50.0
+    t[1, 4095] = 0.0
+    ids, p, H = synera.confidence(t)
+    assert ids.cpu().tolist() == [7, 4095] and p[0].item() == 1.0 and abs(H[0].item()) < 1e-6
+    # empty input is a no-op
+    ids, _, _ = synera.confidence(torch.empty((0, 128), device=DEV))
+    assert ids.numel() == 0
+
+
+def test_confidence_rejects_bad_arguments():
+    synera = _synera()
+    x = torch.zeros((4, 1001), device=DEV, dtype=torch.bfloat16)   # row stride not 16-byte aligned
+    with pytest.raises(synera.SyneraError) as e:
+        synera.confidence(x)
+    assert e.value.status == synera.EINVAL
+
+
+def _mini_shape():
+    return wl.ModelShape("mini", 2, 128, 4, 2, 64, 256, 256)
+
+
+def test_kv_append_is_bit_exact_and_touches_nothing_else():
+    synera = _synera()
+    shape = _mini_shape()
+    head = wl.draw_head_weights(shape, 9, DEV)
+    layers = [wl.draw_layer_weights(shape, 9, l, DEV) for l in range(shape.n_layers)]
+    rng = np.random.default_rng(3)
+    B, n_pages, max_pages = 5, 40, 6
+    perm = rng.permutation(n_pages)
+    bt = perm[: B * max_pages].reshape(B, max_pages).astype(np.int32)
+    start = np.array([0, 3, 16, 31, 40], np.int32)
+    n_new = np.array([33, 1, 16, 2, 50], np.int32)
+    ver = synera.Verifier(shape, head, layers, max_batch=B, max_tokens=64, max_pages=max_pages)
+    kp = torch.full((2, n_pages, 2, 16, 64), float("nan"), dtype=torch.bfloat16, device=DEV)
+    vp = torch.full((2, n_pages, 2, 64, 16), float("nan"), dtype=torch.bfloat16, device=DEV)
+    okv = oracle.PagedKV(2, n_pages, 2, 64)
+    nan_bits = int(torch.tensor(float("nan"), dtype=torch.bfloat16).view(torch.int16).item()) & 0xFFFF
+    okv.k[:] = nan_bits
+    okv.v[:] = nan_bits
+    for layer in range(2):
+        k = wl.draw_normal_bf16((int(n_new.sum()), 2, 64), 1.0, 100 + layer, DEV)
+        v = wl.draw_normal_bf16((int(n_new.sum()), 2, 64), 1.0, 200 + layer, DEV)
+        ver.kv_append(layer, start, n_new, k, v, bt, n_pages, kp, vp)
+        at = 0
+        for i in range(B):
+            rows = slice(at, at + int(n_new[i]))
+            okv.append_many(layer, bt[i], int(start[i]), k[rows].float().cpu().numpy(), v[rows].float().cpu().numpy())
+            at += int(n_new[i])
+    torch.cuda.synchronize()
+    assert np.array_equal(kp.view(torch.int16).cpu().numpy().view(np.uint16), okv.k)
+    assert np.array_equal(vp.view(torch.int16).cpu().numpy().view(np.uint16), okv.v)
+    # error paths: nothing is launched, the pools stay as they were
+    before = kp.clone()
+    bad = bt.copy()
+    bad[1, 0] = bt[0, 0]
+    for kwargs, code in ((dict(block_table=bad), synera.ERANGE), (dict(layer=2), synera.EINVAL),
+                         (dict(n_new=np.array([33, 1, 16, 2, 57], np.int32)), synera.ENOSPC)):
+        args = dict(layer=0, ctx_len=start, n_new=n_new, k=k, v=v, block_table=bt, n_pages_in_pool=n_pages,
+                    k_pool=kp, v_pool=vp)
+        args.update(kwargs)
+        with pytest.raises(synera.SyneraError) as e:
+            ver.kv_append(**args)
+        assert e.value.status == code
+    torch.cuda.synchronize()
+    assert torch.equal(before.view(torch.int16), kp.view(torch.int16))
+    ver.close()
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 128, 64), (16, 256, 256), (130, 384, 512), (128, 4096, 4096),
+                                   (544, 1024, 14336), (257, 32000, 256)])
+def test_gemm_matches_float64(M, N, K):
+    synera = _synera()
+    a = wl.draw_normal_bf16((M, K), 1.0, 11 * M + K, DEV)
+    w = wl.draw_normal_bf16((N, K), 0.02, 13 * N + K, DEV)
+    c = synera.gemm_bf16(a, w)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, M - 1], np.random.default_rng(M).integers(0, M, 6)]))
+    want = a[rows].double().cpu() @ w.double().cpu().T
+    got = c[rows].double().cpu()
+    scale = 0.02 * math.sqrt(K)
+    assert torch.isfinite(c).all()
+    assert (got - want).abs().max().item() < 2e-5 * scale * math.sqrt(K) + 1e-6
+    # full comparison against the fp32 library product on the device (looser: its own rounding)
+    ref = a.float() @ w.float().T
+    assert (c - ref).abs().max().item() < 1e-3 * scale + 1e-5
+
+
+def test_gemm_rejects_unsupported_shapes():
+    synera = _synera()
+    a = torch.zeros((4, 96), dtype=torch.bfloat16, device=DEV)
+    w = torch.zeros((128, 96), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(synera.SyneraError) as e:
+        synera.gemm_bf16(a, w)
+    assert e.value.status == synera.EUNSUP

@@ -1,0 +1,148 @@
+"""GPU parity of synera_verify against the CPU oracle, through the C ABI.
+
+Tolerances are the benchmark spec's: logits max |delta| <= 2e-2, token ids / accept lengths /
+corrections exact except where the oracle's top-2 logit margin is below 1e-2, entropy within
+1e-3 relative; KV page indexing bit-exact (slots that must not be written keep their NaN fill).
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_harness as gh
+import oracle
+import workloads as wl
+from helpers import oracle_model
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _report(name, rep, kv=None):
+    print(f"\n[{name}] rows={rep['rows_checked']} requests={rep['requests_checked']} "
+          f"max|dlogit|={rep['max_logit_err']:.3e} max rel dH={rep['max_entropy_rel']:.3e} "
+          f"max rel dp={rep['max_prob_rel']:.3e} exempt rows/requests={rep['exempt_rows']}/{rep['exempt_requests']}"
+          + (f" max|dKV|={kv['max_kv_err']:.3e}" if kv else ""), flush=True)
+
+
+def test_config1_tiny_decoder_verify():
+    case = gh.build_case(wl.config(1), DEV)
+    out = gh.run_verify(case)
+    rep = gh.compare_with_oracle(case, out)
+    kv = gh.compare_kv(case)
+    _report("c1", rep, kv)
+    assert rep["ok"], rep["fail"]
+    assert kv["ok"], kv["fail"]
+    assert rep["rows_checked"] == 16 and rep["requests_checked"] == 4
+
+
+def _mini_shape():
+    return wl.ModelShape("mini_gqa", 3, 128, 4, 2, 64, 256, 256)
+
+
+def test_ragged_chunks_with_uncached_tokens_and_edge_lengths():
+    """Requests carrying u >= 0 uncached accepted tokens plus k drafts, chunk lengths 1..32, contexts
+    from empty to several key ranges, pages permuted; compared request by request with the oracle."""
+    import paper_2511_07423_amd as synera
+    shape = _mini_shape()
+    head = wl.draw_head_weights(shape, 21, DEV)
+    layers = [wl.draw_layer_weights(shape, 21, l, DEV) for l in range(shape.n_layers)]
+    model = oracle_model(shape, head, layers, np.float64)
+    rng = np.random.default_rng(22)
+    ctx = np.array([0, 1, 15, 16, 17, 100, 255, 256, 257, 700, 1500, 33], np.int32)
+    unc = np.array([1, 0, 3, 0, 31, 0, 5, 16, 0, 2, 0, 0], np.int32)
+    k = np.array([4, 1, 2, 32, 1, 7, 9, 16, 3, 8, 11, 5], np.int32)
+    B = len(ctx)
+    need = (ctx + unc + k + 15) // 16
+    n_pages = int(need.sum()) + 7
+    perm = rng.permutation(n_pages)
+    max_pages = int(need.max()) + 1
+    bt = np.full((B, max_pages), -1, np.int32)
+    at = 0
+    for i in range(B):
+        bt[i, :need[i]] = perm[at:at + need[i]]
+        at += int(need[i])
+    okv = oracle.PagedKV(shape.n_layers, n_pages, shape.n_kv_heads, shape.head_dim)
+    anchors = np.zeros(B, np.int32)
+    toks, reqs = [], []
+    for i in range(B):
+        c = rng.integers(0, shape.vocab, int(ctx[i]))
+        anchors[i] = oracle.prefill_context(model, okv, bt[i], c) if ctx[i] > 0 else int(rng.integers(0, shape.vocab))
+        u = rng.integers(0, shape.vocab, int(unc[i]))
+        d = rng.integers(0, shape.vocab, int(k[i]))
+        if unc[i] == 0:
+            d[0] = anchors[i]                                   # at least one draft can be accepted
+        reqs.append({"block_table": bt[i], "ctx_len": int(ctx[i]), "uncached": u, "drafts": d, "anchor": int(anchors[i])})
+        toks += [u, d]
+    kp = gh.nan_pool(shape, n_pages, DEV, False)
+    vp = gh.nan_pool(shape, n_pages, DEV, True)
+    kd, vd = gh._oracle_pool_to_device(okv, DEV)
+    for i in range(B):
+        for t0 in range(0, int(ctx[i]), 16):
+            m = min(16, int(ctx[i]) - t0)
+            kp[:, bt[i, t0 // 16], :, :m, :] = kd[:, bt[i, t0 // 16], :, :m, :]
+            vp[:, bt[i, t0 // 16], :, :, :m] = vd[:, bt[i, t0 // 16], :, :, :m]
+    want = oracle.verify_chunks(model, okv, reqs)
+    ver = synera.Verifier(shape, head, layers, max_batch=B, max_tokens=int((unc + k).sum()), max_pages=max_pages)
+    tokens = torch.from_numpy(np.concatenate(toks).astype(np.int32)).to(DEV)
+    out = ver.verify(ctx, unc, k, tokens, torch.from_numpy(anchors).to(DEV), bt, n_pages, kp, vp)
+    torch.cuda.synchronize()
+    got = {n: v.cpu().numpy() for n, v in out.items()}
+    err = np.abs(got["logits"].astype(np.float64) - want["logits"]).max()
+    print(f"\n[ragged+uncached] max|dlogit|={err:.3e}", flush=True)
+    assert np.isfinite(got["logits"]).all() and err <= gh.LOGIT_TOL
+    safe = want["margin"] >= gh.MARGIN
+    assert np.array_equal(got["argmax"][safe], want["argmax"][safe])
+    assert np.all(np.abs(got["entropy"] - want["entropy"]) <= gh.ENTROPY_RTOL * want["entropy"])
+    assert np.all(np.abs(got["top1_prob"] - want["top1_prob"]) <= 2.5e-2 * want["top1_prob"] + 1e-6)
+    cu = np.concatenate([[0], np.cumsum(k)])
+    n_exact = 0
+    for i in range(B):
+        n = int(want["accept_len"][i])
+        rows_ok = np.all(want["margin"][cu[i]:cu[i] + min(n + 1, int(k[i]))] >= gh.MARGIN)
+        if rows_ok and want["first_margin"][i] >= gh.MARGIN:
+            assert got["accept_len"][i] == n and got["correction"][i] == want["correction"][i], i
+            n_exact += 1
+    assert n_exact >= B - 2
+    # appended K/V (uncached and draft positions) land where the oracle put them; nothing else is written
+    gk = kp.view(torch.int16).cpu().numpy().view(np.uint16)
+    gv = vp.view(torch.int16).cpu().numpy().view(np.uint16)
+    live_k = np.zeros(gk.shape, bool)                           # slots that hold a position < L + u + k
+    live_v = np.zeros(gv.shape, bool)
+    for i in range(B):
+        for t in range(int(ctx[i] + unc[i] + k[i])):
+            live_k[:, bt[i, t // 16], :, t % 16, :] = True
+            live_v[:, bt[i, t // 16], :, :, t % 16] = True
+    assert np.array_equal(gk != gh.NAN_BITS, live_k) and np.array_equal(gv != gh.NAN_BITS, live_v)
+    dk = np.abs(oracle.bf16_from_bits(gk) - oracle.bf16_from_bits(okv.k))[live_k]
+    dv = np.abs(oracle.bf16_from_bits(gv) - oracle.bf16_from_bits(okv.v))[live_v]
+    assert dk.max() <= 0.05 and dv.max() <= 0.05
+    # error paths launch nothing
+    with pytest.raises(synera.SyneraError) as e:
+        ver.verify(ctx, unc, np.where(k == 32, 33, k).astype(np.int32), tokens, torch.from_numpy(anchors).to(DEV), bt,
+                   n_pages, kp, vp)
+    assert e.value.status == synera.EUNSUP
+    ver.close()
+
+
+def test_chunked_verify_equals_sequential_decodes_on_gpu():
+    """The method's own invariant on the HIP path: verifying a k-token chunk gives the rows of k
+    single-token verifies with the context length advanced by one each time."""
+    import paper_2511_07423_amd as synera
+    case = gh.build_case(wl.config(1), DEV)
+    chunk = gh.run_verify(case)
+    b = case.batch
+    B = len(b["ctx_len"])
+    kmax = int(b["n_draft"].max())
+    rows = [[] for _ in range(B)]
+    for j in range(kmax):
+        live = [i for i in range(B) if b["n_draft"][i] > j]
+        toks = torch.tensor([int(case.drafts[i][j]) for i in live], dtype=torch.int32, device=DEV)
+        out = case.verifier.verify((b["ctx_len"][live] + j).astype(np.int32), np.zeros(len(live), np.int32),
+                                   np.ones(len(live), np.int32), toks,
+                                   torch.zeros(len(live), dtype=torch.int32, device=DEV), b["block_table"][live],
+                                   b["n_pages"], case.k_pool, case.v_pool)
+        lg = out["logits"].cpu().numpy()
+        for n, i in enumerate(live):
+            rows[i].append(lg[n])
+    seq = np.concatenate([np.stack(r) for r in rows])
+    assert np.abs(seq - chunk["logits"]).max() < 2e-3

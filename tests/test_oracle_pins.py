@@ -396,3 +396,15 @@ def test_float32_mode_tracks_float64():
         outs.append(oracle.lm_head(m, oracle.forward_tokens(m, kv, [([0, 1], 0, toks)])))
     assert outs[1].dtype == np.float32
     assert np.abs(outs[0] - outs[1]).max() < 2e-3          # bf16 rounding of K/V can differ by one ulp
+
+
+def test_append_many_equals_single_appends():
+    rng = np.random.default_rng(13)
+    bt = [3, 0, 2, 1]
+    K, V = rng.normal(size=(41, 2, 4)), rng.normal(size=(41, 2, 4))
+    a = oracle.PagedKV(1, 4, 2, 4)
+    b = oracle.PagedKV(1, 4, 2, 4)
+    for t in range(41):
+        a.append(0, bt, 5 + t, K[t], V[t])
+    b.append_many(0, bt, 5, K, V)
+    assert np.array_equal(a.k, b.k) and np.array_equal(a.v, b.v)
