@@ -98,13 +98,12 @@ class PagedKV:
 
     def gather(self, layer, block_table_row, n):
         """K and V of positions 0..n-1, widened to float32: [n, kv_head, dim] each."""
-        K = np.empty((n, self.n_kv_heads, self.head_dim), np.float32)
-        V = np.empty((n, self.n_kv_heads, self.head_dim), np.float32)
-        for p0 in range(0, n, PAGE):
-            b = self._backing(block_table_row[p0 // PAGE])
-            m = min(PAGE, n - p0)
-            K[p0:p0 + m] = bf16_from_bits(self.k[layer, b, :, :m, :]).transpose(1, 0, 2)
-            V[p0:p0 + m] = bf16_from_bits(self.v[layer, b, :, :, :m]).transpose(2, 0, 1)
+        n_pg = (n + PAGE - 1) // PAGE
+        b = [self._backing(block_table_row[p]) for p in range(n_pg)]
+        # [pages, kv_head, slot, dim] -> [pages*slot, kv_head, dim]; V pages are [kv_head, dim, slot]
+        K = bf16_from_bits(self.k[layer, b]).transpose(0, 2, 1, 3).reshape(n_pg * PAGE, self.n_kv_heads, self.head_dim)
+        V = bf16_from_bits(self.v[layer, b]).transpose(0, 3, 1, 2).reshape(n_pg * PAGE, self.n_kv_heads, self.head_dim)
+        K, V = K[:n], V[:n]
         return K, V
 
 

@@ -84,12 +84,17 @@ struct synera_ctx {
   // device scratch (one allocation)
   char* arena;
   float* x;
-  bf16_t* y;
+  bf16_t* y;        // activations travel as bf16 (hi, lo) pairs: *_lo is the low part
+  bf16_t* y_lo;
   float* qkv;
   bf16_t* q;
+  bf16_t* q_lo;
   bf16_t* o;
+  bf16_t* o_lo;
   bf16_t* act;
+  bf16_t* act_lo;
   bf16_t* ysel;
+  bf16_t* ysel_lo;
   float* logits;
   int32_t* lm_ids;
   float* lm_p;
@@ -153,9 +158,12 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   const size_t qkv_dim = (size_t)(qd + 2 * kd);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
-  const size_t o_x = take(T * m.d_model * 4), o_y = take(T * m.d_model * 2), o_qkv = take(T * qkv_dim * 4);
-  const size_t o_q = take(T * qd * 2), o_o = take(T * qd * 2), o_act = take(T * (size_t)m.d_ffn * 2);
-  const size_t o_ysel = take(R * m.d_model * 2), o_logits = take(R * (size_t)m.vocab * 4);
+  const size_t o_x = take(T * m.d_model * 4), o_y = take(T * m.d_model * 2), o_yl = take(T * m.d_model * 2);
+  const size_t o_qkv = take(T * qkv_dim * 4);
+  const size_t o_q = take(T * qd * 2), o_ql = take(T * qd * 2), o_o = take(T * qd * 2), o_ol = take(T * qd * 2);
+  const size_t o_act = take(T * (size_t)m.d_ffn * 2), o_actl = take(T * (size_t)m.d_ffn * 2);
+  const size_t o_ysel = take(R * m.d_model * 2), o_ysell = take(R * m.d_model * 2);
+  const size_t o_logits = take(R * (size_t)m.vocab * 4);
   const size_t o_ids = take(R * 4), o_p = take(R * 4), o_h = take(R * 4);
   const size_t o_cs = take(T * (m.head_dim / 2) * 8);
   const size_t o_po = take((size_t)c->items_cap * m.n_kv_heads * 64 * m.head_dim * 4);
@@ -167,6 +175,11 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   }
   c->x = reinterpret_cast<float*>(c->arena + o_x);
   c->y = reinterpret_cast<bf16_t*>(c->arena + o_y);
+  c->y_lo = reinterpret_cast<bf16_t*>(c->arena + o_yl);
+  c->q_lo = reinterpret_cast<bf16_t*>(c->arena + o_ql);
+  c->o_lo = reinterpret_cast<bf16_t*>(c->arena + o_ol);
+  c->act_lo = reinterpret_cast<bf16_t*>(c->arena + o_actl);
+  c->ysel_lo = reinterpret_cast<bf16_t*>(c->arena + o_ysell);
   c->qkv = reinterpret_cast<float*>(c->arena + o_qkv);
   c->q = reinterpret_cast<bf16_t*>(c->arena + o_q);
   c->o = reinterpret_cast<bf16_t*>(c->arena + o_o);
@@ -366,10 +379,13 @@ static int32_t finish_call(synera_ctx* c, const Plan& p, hipStream_t stream) {
   return SYNERA_OK;
 }
 
-static int32_t run_gemm(const bf16_t* a, const void* w0, int r0, const void* w1, int r1, const void* w2, int r2,
-                        void* cbuf, int M, int N, int K, int epi, hipStream_t s) {
+static int32_t run_gemm(const bf16_t* a, const bf16_t* a_lo, const void* w0, int r0, const void* w1, int r1,
+                        const void* w2, int r2, void* cbuf, void* cbuf_lo, int M, int N, int K, int epi,
+                        hipStream_t s) {
   GemmArgs g;
   g.a = a;
+  g.a_lo = a_lo;
+  g.c_lo = cbuf_lo;
   g.w[0] = static_cast<const bf16_t*>(w0);
   g.w[1] = static_cast<const bf16_t*>(w1);
   g.w[2] = static_cast<const bf16_t*>(w2);
@@ -381,7 +397,8 @@ static int32_t run_gemm(const bf16_t* a, const void* w0, int r0, const void* w1,
   g.N = N;
   g.K = K;
   g.epilogue = epi;
-  g.split_k = (epi == GEMM_SWIGLU_BF16) ? 1 : gemm_pick_split(M, N, K);
+  g.split_k = 1;
+  g.split_k = gemm_pick_split(g);
   if (epi == GEMM_STORE_F32 && g.split_k > 1) HIP_TRY(launch_fill_zero(static_cast<float*>(cbuf), (size_t)M * N, s));
   HIP_TRY(launch_gemm(g, s));
   return SYNERA_OK;
@@ -415,6 +432,8 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
 
   AttnLaunch al;
   al.q = c->q;
+  al.q_lo = c->q_lo;
+  al.o_lo = c->o_lo;
   al.block_table = p.meta.block_table;
   al.max_pages = max_pages;
   al.items = p.d_items;
@@ -433,26 +452,33 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
     const synera_layer_weights& w = c->layers[l];
     bf16_t* k_layer = static_cast<bf16_t*>(d_k_pool) + (size_t)l * layer_elems;
     bf16_t* v_layer = static_cast<bf16_t*>(d_v_pool) + (size_t)l * layer_elems;
-    HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.attn_norm), nullptr, c->y, T, d, m.rms_eps, s));
-    if ((st = run_gemm(c->y, w.wq, qd, w.wk, kd, w.wv, kd, c->qkv, T, qd + 2 * kd, d, GEMM_STORE_F32, s))) return st;
-    HIP_TRY(launch_rope_append(c->qkv, c->cs, p.meta, c->q, k_layer, v_layer, T, Hq, Hkv, hd, s));
+    HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.attn_norm), nullptr, c->y, c->y_lo, T, d, m.rms_eps,
+                           s));
+    if ((st = run_gemm(c->y, c->y_lo, w.wq, qd, w.wk, kd, w.wv, kd, c->qkv, nullptr, T, qd + 2 * kd, d,
+                       GEMM_STORE_F32, s)))
+      return st;
+    HIP_TRY(launch_rope_append(c->qkv, c->cs, p.meta, c->q, c->q_lo, k_layer, v_layer, T, Hq, Hkv, hd, s));
     al.k_layer = k_layer;
     al.v_layer = v_layer;
     HIP_TRY(launch_attention(al, s));
-    if ((st = run_gemm(c->o, w.wo, d, nullptr, 0, nullptr, 0, c->x, T, d, qd, GEMM_ADD_F32, s))) return st;
-    HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.mlp_norm), nullptr, c->y, T, d, m.rms_eps, s));
-    if ((st = run_gemm(c->y, w.w_gate, 0, w.w_up, 0, nullptr, 0, c->act, T, 2 * m.d_ffn, d, GEMM_SWIGLU_BF16, s)))
+    if ((st = run_gemm(c->o, c->o_lo, w.wo, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, qd, GEMM_ADD_F32, s)))
       return st;
-    if ((st = run_gemm(c->act, w.w_down, d, nullptr, 0, nullptr, 0, c->x, T, d, m.d_ffn, GEMM_ADD_F32, s))) return st;
+    HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.mlp_norm), nullptr, c->y, c->y_lo, T, d, m.rms_eps, s));
+    if ((st = run_gemm(c->y, c->y_lo, w.w_gate, 0, w.w_up, 0, nullptr, 0, c->act, c->act_lo, T, 2 * m.d_ffn, d,
+                       GEMM_SWIGLU_BF16, s)))
+      return st;
+    if ((st = run_gemm(c->act, c->act_lo, w.w_down, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, m.d_ffn,
+                       GEMM_ADD_F32, s)))
+      return st;
   }
 
   // LM head over the draft rows (plus the last uncached row of requests that have one).
   const bool extra = p.R_all > p.R;
-  HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(c->final_norm), p.meta.sel_rows, c->ysel, p.R_all, d,
-                         m.rms_eps, s));
+  HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(c->final_norm), p.meta.sel_rows, c->ysel, c->ysel_lo,
+                         p.R_all, d, m.rms_eps, s));
   float* logits = (d_logits && !extra) ? d_logits : c->logits;
-  if ((st = run_gemm(c->ysel, c->lm_head, m.vocab, nullptr, 0, nullptr, 0, logits, p.R_all, m.vocab, d,
-                     GEMM_STORE_F32, s)))
+  if ((st = run_gemm(c->ysel, c->ysel_lo, c->lm_head, m.vocab, nullptr, 0, nullptr, 0, logits, nullptr, p.R_all,
+                     m.vocab, d, GEMM_STORE_F32, s)))
     return st;
   float* p_out = (d_top1_prob && !extra) ? d_top1_prob : c->lm_p;
   float* h_out = (d_entropy && !extra) ? d_entropy : c->lm_h;
@@ -510,6 +536,6 @@ extern "C" int32_t synera_gemm_bf16(const void* d_a, const void* d_w, float* d_c
                                     void* stream) {
   if (!d_a || !d_w || !d_c || M < 1 || N < 1 || K < 1) return SYNERA_EINVAL;
   if (N % 128 != 0 || K % 64 != 0) return SYNERA_EUNSUP;
-  return run_gemm(static_cast<const bf16_t*>(d_a), d_w, N, nullptr, 0, nullptr, 0, d_c, M, N, K, GEMM_STORE_F32,
-                  static_cast<hipStream_t>(stream));
+  return run_gemm(static_cast<const bf16_t*>(d_a), nullptr, d_w, N, nullptr, 0, nullptr, 0, d_c, nullptr, M, N, K,
+                  GEMM_STORE_F32, static_cast<hipStream_t>(stream));
 }

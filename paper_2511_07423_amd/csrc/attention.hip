@@ -17,6 +17,10 @@
 //     cross-lane exchanges, and the probabilities are already laid out as the B
 //     operand of O^T = V^T P^T.  V pages are stored dim-major ([dim][slot]), which
 //     makes the A operand of that product two plain 8-byte loads per lane.
+//   * q and the probabilities enter the matrix cores as bf16 (hi, lo) pairs (two MFMAs per
+//     product, K/V fragments reused), and o leaves as a pair: single bf16 terms here cost the
+//     logits of a deep decoder an order of magnitude in accuracy.  The Q pairs of the row
+//     group sit in LDS in fragment order (each lane re-reads its own 16 bytes per tile).
 //   * Every K/V byte of the key range is read once per KV head and shared by the
 //     G x k_i query rows.  Ranges are split across blocks for occupancy; partial
 //     (m, l, O) results are merged by attn_combine_kernel.
@@ -52,6 +56,17 @@ __device__ __forceinline__ void load_tile(KVTile<HD>& t, const bf16_t* __restric
 
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Four consecutive outputs as a bf16 (hi, lo) pair: 8 bytes to each array.
+__device__ __forceinline__ void store_pair(bf16_t* hi, bf16_t* lo, float a, float b, float c, float d) {
+  uint2 h, l;
+  h.x = pack_bf2(a, b);
+  h.y = pack_bf2(c, d);
+  l.x = pack_bf2(a - bf2f(h.x & 0xFFFF), b - bf2f(h.x >> 16));
+  l.y = pack_bf2(c - bf2f(h.y & 0xFFFF), d - bf2f(h.y >> 16));
+  *reinterpret_cast<uint2*>(hi) = h;
+  *reinterpret_cast<uint2*>(lo) = l;
+}
+
 template <int HD, int RB>
 __global__ __launch_bounds__(256) void attn_kernel(AttnLaunch a, int item_base, float scale_log2) {
   constexpr int KS = HD / 32;
@@ -74,23 +89,27 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnLaunch a, int item_base, 
   const int nrows = it.ntok * G;
   const int32_t* bt = a.block_table + (size_t)it.req * a.max_pages;
 
-  // Q fragments (B operand: lane = (row n16, dim chunk g)); rows past the group are zero.
-  bf16x8 qf[RB][KS];
+  // Q fragments (B operand: lane = (row n16, dim chunk g)) as (hi, lo) pairs, parked in LDS in
+  // fragment order: fragment f = (rb * KS + s) * 2 + part, 64 lanes x 16 bytes each.  Rows past the
+  // group are zero.  The region is reused by the merge at the end.
+  bf16x8* s_q = reinterpret_cast<bf16x8*>(lds);
   int lim[RB];                                    // last key this lane's row may see
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     const int row = rb * 16 + n16;
-    if (row < nrows) {
-      const bf16_t* qp = a.q + ((size_t)(it.tok0 + row / G) * Hq + kh * G + row % G) * HD + 8 * g;
-#pragma unroll
-      for (int s = 0; s < KS; ++s) qf[rb][s] = *reinterpret_cast<const bf16x8*>(qp + 32 * s);
-      lim[rb] = it.ctx_len + it.j0 + row / G;
-    } else {
-#pragma unroll
-      for (int s = 0; s < KS; ++s) qf[rb][s] = bf16x8{};
-      lim[rb] = 0x7FFFFFFF;
-    }
+    lim[rb] = row < nrows ? it.ctx_len + it.j0 + row / G : 0x7FFFFFFF;
   }
+  for (int f = wave; f < RB * KS * 2; f += 4) {
+    const int part = f & 1, s = (f >> 1) % KS, rb = (f >> 1) / KS;
+    const int row = rb * 16 + n16;
+    bf16x8 v = bf16x8{};
+    if (row < nrows) {
+      const bf16_t* qp = (part ? a.q_lo : a.q) + ((size_t)(it.tok0 + row / G) * Hq + kh * G + row % G) * HD;
+      v = *reinterpret_cast<const bf16x8*>(qp + 32 * s + 8 * g);
+    }
+    s_q[f * 64 + lane] = v;
+  }
+  __syncthreads();
 
   float m_run[RB], l_run[RB];
   f32x4 acc[RB][DB];
@@ -146,8 +165,12 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnLaunch a, int item_base, 
       f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
-        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[0][s], qf[rb][s], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[1][s], qf[rb][s], s1, 0, 0, 0);
+        const bf16x8 qh = s_q[((rb * KS + s) * 2 + 0) * 64 + lane];
+        const bf16x8 ql = s_q[((rb * KS + s) * 2 + 1) * 64 + lane];
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[0][s], qh, s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[1][s], qh, s1, 0, 0, 0);
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[0][s], ql, s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[1][s], ql, s1, 0, 0, 0);
       }
       float sv[8];
 #pragma unroll
@@ -181,27 +204,35 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnLaunch a, int item_base, 
         psum += p[r];
       }
       l_run[rb] = l_run[rb] * alpha + psum;
-      uint4 pk;
+      uint4 pk, pl;
       pk.x = pack_bf2(p[0], p[1]);
       pk.y = pack_bf2(p[2], p[3]);
       pk.z = pack_bf2(p[4], p[5]);
       pk.w = pack_bf2(p[6], p[7]);
+      pl.x = pack_bf2(p[0] - bf2f(pk.x & 0xFFFF), p[1] - bf2f(pk.x >> 16));
+      pl.y = pack_bf2(p[2] - bf2f(pk.y & 0xFFFF), p[3] - bf2f(pk.y >> 16));
+      pl.z = pack_bf2(p[4] - bf2f(pk.z & 0xFFFF), p[5] - bf2f(pk.z >> 16));
+      pl.w = pack_bf2(p[6] - bf2f(pk.w & 0xFFFF), p[7] - bf2f(pk.w >> 16));
       const bf16x8 pf = __builtin_bit_cast(bf16x8, pk);
+      const bf16x8 pfl = __builtin_bit_cast(bf16x8, pl);
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         uint4 vv;
         vv.x = cur.v[db][0].x; vv.y = cur.v[db][0].y;
         vv.z = cur.v[db][1].x; vv.w = cur.v[db][1].y;
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
         f32x4 o = acc[rb][db];
         o[0] *= alpha; o[1] *= alpha; o[2] *= alpha; o[3] *= alpha;
-        acc[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vv), pf, o, 0, 0, 0);
+        o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o, 0, 0, 0);
+        acc[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pfl, o, 0, 0, 0);
       }
     }
     cur = nxt;
     kb = kb_next;
   }
 
-  // ---- merge the four wavefronts' (m, l, O) through LDS
+  // ---- merge the four wavefronts' (m, l, O) through LDS (which held Q until now)
+  __syncthreads();
 #pragma unroll
   for (int rb = 0; rb < RB; ++rb) {
     float l = l_run[rb];
@@ -242,10 +273,8 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnLaunch a, int item_base, 
     }
     if (it.part < 0) {
       const float inv = 1.0f / s_ls[row];
-      uint2 out;
-      out.x = pack_bf2(sum.x * inv, sum.y * inv);
-      out.y = pack_bf2(sum.z * inv, sum.w * inv);
-      *reinterpret_cast<uint2*>(a.o + ((size_t)(it.tok0 + row / G) * Hq + kh * G + row % G) * HD + d4) = out;
+      const size_t at = ((size_t)(it.tok0 + row / G) * Hq + kh * G + row % G) * HD + d4;
+      store_pair(a.o + at, a.o_lo + at, sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
     } else {
       *reinterpret_cast<float4*>(a.part_o + (((size_t)it.part * Hkv + kh) * 64 + row) * HD + d4) = sum;
     }
@@ -279,10 +308,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnLaunch a) {
       l += w * ml.y;
     }
     const float inv = 1.0f / l;
-    uint2 out;
-    out.x = pack_bf2(sum.x * inv, sum.y * inv);
-    out.y = pack_bf2(sum.z * inv, sum.w * inv);
-    *reinterpret_cast<uint2*>(a.o + ((size_t)t * Hq + hq) * HD + d4) = out;
+    const size_t at = ((size_t)t * Hq + hq) * HD + d4;
+    store_pair(a.o + at, a.o_lo + at, sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
   }
 }
 
@@ -291,7 +318,9 @@ static hipError_t launch_class(const AttnLaunch& a, int cls, float scale_log2, h
   const int n = a.class_begin[cls + 1] - a.class_begin[cls];
   if (n <= 0) return hipSuccess;
   constexpr int ROWS = RB * 16;
-  const size_t lds = (size_t)(4 * ROWS * (HD + 4) + 8 * ROWS + 2 * ROWS) * sizeof(float);
+  const size_t lds_merge = (size_t)(4 * ROWS * (HD + 4) + 8 * ROWS + 2 * ROWS) * sizeof(float);
+  const size_t lds_q = (size_t)RB * (HD / 32) * 2 * 64 * 16;
+  const size_t lds = lds_merge > lds_q ? lds_merge : lds_q;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<HD, RB>),

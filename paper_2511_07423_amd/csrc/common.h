@@ -12,6 +12,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 #define SY_PAGE 16
 
+// Activations travel between kernels as a bf16 pair (hi, lo): hi = bf16(v), lo = bf16(v - hi), which keeps
+// about 16 mantissa bits while every matrix-core operand stays bf16.
 // Round-to-nearest-even fp32 -> bf16 bits (finite inputs).
 __device__ __forceinline__ uint32_t f2bf(float f) {
   uint32_t u = __float_as_uint(f);
@@ -34,11 +36,11 @@ struct BatchMeta {        // device pointers into one uploaded metadata blob (al
 };
 
 hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, int T, int d, hipStream_t s);
-hipError_t launch_rmsnorm(const float* x, const bf16_t* gain, const int32_t* rows, bf16_t* y, int n_rows, int d,
-                          float eps, hipStream_t s);
+hipError_t launch_rmsnorm(const float* x, const bf16_t* gain, const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo,
+                          int n_rows, int d, float eps, hipStream_t s);
 hipError_t launch_rope_table(const BatchMeta& m, float2* cs, int T, int head_dim, float base, hipStream_t s);
-hipError_t launch_rope_append(const float* qkv, const float2* cs, const BatchMeta& m, bf16_t* q, bf16_t* k_layer,
-                              bf16_t* v_layer, int T, int Hq, int Hkv, int hd, hipStream_t s);
+hipError_t launch_rope_append(const float* qkv, const float2* cs, const BatchMeta& m, bf16_t* q_hi, bf16_t* q_lo,
+                              bf16_t* k_layer, bf16_t* v_layer, int T, int Hq, int Hkv, int hd, hipStream_t s);
 hipError_t launch_kv_append(const bf16_t* k, const bf16_t* v, const BatchMeta& m, int B, bf16_t* k_layer,
                             bf16_t* v_layer, int T, int Hkv, int hd, hipStream_t s);
 hipError_t launch_accept(const int32_t* tokens, const int32_t* anchor, const int32_t* lm_argmax, const BatchMeta& m,
@@ -68,7 +70,8 @@ struct AttnCombine {   // per chunk token: where its partials live
   int32_t pad;
 };
 struct AttnLaunch {
-  const bf16_t* q;           // [T][Hq][hd]
+  const bf16_t* q;           // [T][Hq][hd], high part of the (hi, lo) bf16 pair
+  const bf16_t* q_lo;        // low part
   const bf16_t* k_layer;     // pool of this layer
   const bf16_t* v_layer;
   const int32_t* block_table;
@@ -78,7 +81,8 @@ struct AttnLaunch {
   const AttnCombine* comb;   // [T]
   float* part_o;             // [slots][Hkv][64][hd]
   float* part_ml;            // [slots][Hkv][64][2]
-  bf16_t* o;                 // [T][Hq][hd]
+  bf16_t* o;                 // [T][Hq][hd], high part of the output pair
+  bf16_t* o_lo;              // low part
   int32_t T, Hq, Hkv, hd;
   int32_t any_split;
 };
@@ -87,13 +91,16 @@ hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 // ---------------------------------------------------------------- gemm.hip
 enum GemmEpilogue { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };
 struct GemmArgs {
-  const bf16_t* a;       // [M][K]
+  const bf16_t* a;       // [M][K], high part of the activation pair
+  const bf16_t* a_lo;    // [M][K], low part (nullptr: single-term activations)
   const bf16_t* w[3];    // up to three row segments of the weight (each [rows][K])
   int32_t w_rows[3];     // rows per segment (multiples of the N tile); unused = 0
   void* c;               // f32 [M][N] (STORE/ADD) or bf16 [M][N/2] (SWIGLU: w[0] = gate, w[1] = up)
+  void* c_lo;            // SWIGLU only: low part of the bf16 output pair
   int32_t M, N, K;       // N = total output columns of the contraction (gate + up for SWIGLU)
   int32_t epilogue;
   int32_t split_k;       // >= 1; > 1 only with STORE (pre-zeroed C) or ADD: partial sums are added atomically
 };
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
-int gemm_pick_split(int M, int N, int K);
+int gemm_pick_split(const GemmArgs& g);
+void gemm_force_variant(int v);   // tuning hook: -1 automatic, else a tile configuration index

@@ -28,12 +28,13 @@ hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, in
 }
 
 // ------------------------------------------------------------------ RMSNorm
-// y = x * rsqrt(mean(x^2) + eps) * g, fp32 in, bf16 out.  One block per output
-// row; `rows` (optional) selects which input row feeds output row r.
+// y = x * rsqrt(mean(x^2) + eps) * g, fp32 in, bf16 (hi, lo) pair out.  One block per
+// output row; `rows` (optional) selects which input row feeds output row r.
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x,
                                                       const bf16_t* __restrict__ gain,
                                                       const int32_t* __restrict__ rows,
-                                                      bf16_t* __restrict__ y, int d, float eps) {
+                                                      bf16_t* __restrict__ y, bf16_t* __restrict__ y_lo, int d,
+                                                      float eps) {
   const int r = blockIdx.x;
   const float* src = x + (size_t)(rows ? rows[r] : r) * d;
   float ss = 0.f;
@@ -47,20 +48,26 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   __syncthreads();
   const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
   bf16_t* dst = y + (size_t)r * d;
+  bf16_t* dst_lo = y_lo + (size_t)r * d;
   for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
     float4 v = *reinterpret_cast<const float4*>(src + c);
     uint2 g = *reinterpret_cast<const uint2*>(gain + c);
-    uint2 out;
-    out.x = pack_bf2(v.x * inv * bf2f(g.x & 0xFFFF), v.y * inv * bf2f(g.x >> 16));
-    out.y = pack_bf2(v.z * inv * bf2f(g.y & 0xFFFF), v.w * inv * bf2f(g.y >> 16));
-    *reinterpret_cast<uint2*>(dst + c) = out;
+    const float o0 = v.x * inv * bf2f(g.x & 0xFFFF), o1 = v.y * inv * bf2f(g.x >> 16);
+    const float o2 = v.z * inv * bf2f(g.y & 0xFFFF), o3 = v.w * inv * bf2f(g.y >> 16);
+    uint2 hi, lo;
+    hi.x = pack_bf2(o0, o1);
+    hi.y = pack_bf2(o2, o3);
+    lo.x = pack_bf2(o0 - bf2f(hi.x & 0xFFFF), o1 - bf2f(hi.x >> 16));
+    lo.y = pack_bf2(o2 - bf2f(hi.y & 0xFFFF), o3 - bf2f(hi.y >> 16));
+    *reinterpret_cast<uint2*>(dst + c) = hi;
+    *reinterpret_cast<uint2*>(dst_lo + c) = lo;
   }
 }
 
-hipError_t launch_rmsnorm(const float* x, const bf16_t* gain, const int32_t* rows, bf16_t* y, int n_rows, int d,
-                          float eps, hipStream_t s) {
+hipError_t launch_rmsnorm(const float* x, const bf16_t* gain, const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo,
+                          int n_rows, int d, float eps, hipStream_t s) {
   if (n_rows <= 0) return hipSuccess;
-  rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, gain, rows, y, d, eps);
+  rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, gain, rows, y_hi, y_lo, d, eps);
   return hipGetLastError();
 }
 
@@ -87,13 +94,14 @@ hipError_t launch_rope_table(const BatchMeta& m, float2* cs, int T, int head_dim
 
 // ------------------------------------------------------------------ rotary + append
 // One block per chunk token.  Input row: fp32 [q heads | k heads | v heads] x hd.
-// q and k are rotated on adjacent pairs; q goes to bf16 [T][Hq][hd]; k and v go to
+// q and k are rotated on adjacent pairs; q goes to a bf16 (hi, lo) pair [T][Hq][hd]; k and v go to
 // the token's page (position t lives in page block_table[t/16], slot t%16):
 // K page [kv_head][slot][dim], V page [kv_head][dim][slot].
 __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restrict__ qkv,
                                                           const float2* __restrict__ cs, BatchMeta m,
-                                                          bf16_t* __restrict__ q, bf16_t* __restrict__ k_layer,
-                                                          bf16_t* __restrict__ v_layer, int Hq, int Hkv, int hd) {
+                                                          bf16_t* __restrict__ q, bf16_t* __restrict__ q_lo,
+                                                          bf16_t* __restrict__ k_layer, bf16_t* __restrict__ v_layer,
+                                                          int Hq, int Hkv, int hd) {
   const int t = blockIdx.x;
   const int r = m.tok_req[t];
   const int pos = m.ctx_len[r] + (t - m.cu_tok[r]);
@@ -110,7 +118,10 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
       const float r0 = v.x * c.x - v.y * c.y;
       const float r1 = v.x * c.y + v.y * c.x;
       if (head < Hq) {
-        *reinterpret_cast<uint32_t*>(q + ((size_t)t * Hq + head) * hd + 2 * i) = pack_bf2(r0, r1);
+        const uint32_t hi = pack_bf2(r0, r1);
+        const size_t at = ((size_t)t * Hq + head) * hd + 2 * i;
+        *reinterpret_cast<uint32_t*>(q + at) = hi;
+        *reinterpret_cast<uint32_t*>(q_lo + at) = pack_bf2(r0 - bf2f(hi & 0xFFFF), r1 - bf2f(hi >> 16));
       } else {
         const int kh = head - Hq;
         bf16_t* dst = k_layer + (((size_t)page * Hkv + kh) * SY_PAGE + slot) * hd + 2 * i;
@@ -125,10 +136,10 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
   }
 }
 
-hipError_t launch_rope_append(const float* qkv, const float2* cs, const BatchMeta& m, bf16_t* q, bf16_t* k_layer,
-                              bf16_t* v_layer, int T, int Hq, int Hkv, int hd, hipStream_t s) {
+hipError_t launch_rope_append(const float* qkv, const float2* cs, const BatchMeta& m, bf16_t* q_hi, bf16_t* q_lo,
+                              bf16_t* k_layer, bf16_t* v_layer, int T, int Hq, int Hkv, int hd, hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  rope_append_kernel<<<T, 256, 0, s>>>(qkv, cs, m, q, k_layer, v_layer, Hq, Hkv, hd);
+  rope_append_kernel<<<T, 256, 0, s>>>(qkv, cs, m, q_hi, q_lo, k_layer, v_layer, Hq, Hkv, hd);
   return hipGetLastError();
 }
 

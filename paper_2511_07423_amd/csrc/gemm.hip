@@ -2,49 +2,71 @@
 // with fp32 accumulation (v_mfma_f32_32x32x16_bf16).  Both operands are K-major, so
 // an MFMA operand fragment (8 consecutive k of one row) is one 16-byte read.
 //
-// Tiling: a 256-thread block (4 wavefronts, 2x2) owns a BM x BN = 128 x 128 output
-// tile; each wavefront a 64 x 64 sub-tile (2x2 MFMA blocks, 64 fp32 accumulators per
-// lane).  K advances in steps of 64 through double-buffered LDS tiles whose 16-byte
-// chunks are XOR-swizzled by row so fragment reads are bank-conflict free.  Global
-// loads of step i+1 are issued before the MFMAs of step i.
+// Activations arrive as a bf16 pair (hi, lo) with hi + lo equal to the fp32 value to
+// about 16 mantissa bits; the kernel accumulates A_hi*W and A_lo*W into the same
+// accumulators.  (bf16 weights are exact; a single bf16 activation term leaves the
+// logits of a 32-layer decoder an order of magnitude outside the parity tolerance.)
+// The lo term reuses the weight fragments already in registers, so it costs MFMA
+// issue slots but no extra weight traffic from HBM, L2 or LDS.
+//
+// Tiling: a block of WGM x WGN wavefronts owns a BM x BN output tile; each wavefront
+// a (BM/WGM) x (BN/WGN) sub-tile made of 32x32 MFMA blocks.  K advances in steps of BK
+// through double-buffered LDS tiles whose 16-byte chunks are XOR-swizzled by row, so
+// fragment reads are bank-conflict free.  Global loads of step i+1 are issued before
+// the MFMAs of step i and parked in registers.
 //
 // The weight may be given as up to three row segments (Wq | Wk | Wv share one
 // launch).  Epilogues: store fp32; add into fp32 (residual stream); SwiGLU, where the
 // tile's even 32-column blocks come from W_gate and the odd ones from W_up at the same
 // rows, so one lane holds gate and up of the same output and writes
-// silu(gate) * up as bf16.  split_k > 1 spreads K over blockIdx.z and adds the
-// partial sums with hardware fp32 atomics (the order of those adds is not fixed).
+// silu(gate) * up as a bf16 (hi, lo) pair.  split_k > 1 spreads K over blockIdx.z and
+// adds the partial sums with hardware fp32 atomics (the order of those adds is not fixed).
 #include "common.h"
 
-#define BM 128
-#define BN 128
-#define BK 64
+template <int CPR>
+__device__ __forceinline__ int swz(int row, int chunk) {
+  // element offset of 16-byte chunk `chunk` of `row` in a tile with CPR chunks per row
+  return (row * CPR + (chunk ^ ((row / (8 / CPR)) % CPR))) * 8;
+}
 
-__device__ __forceinline__ int swz(int row, int chunk) { return row * BK + ((chunk ^ (row & 7)) << 3); }
-
-template <int EPI>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
-  __shared__ __attribute__((aligned(16))) bf16_t sA[2][BM * BK];
-  __shared__ __attribute__((aligned(16))) bf16_t sB[2][BN * BK];
+template <int BM, int BN, int BK, int WGM, int WGN, bool SPLIT, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NJ = WN / 32;
+  constexpr int CPR = BK / 8;
+  constexpr int A_CH = BM * CPR / NT, B_CH = BN * CPR / NT;
+  constexpr int NA = SPLIT ? 2 : 1;
+  constexpr int A_ELEMS = BM * BK, B_ELEMS = BN * BK;
+  constexpr int STAGE = NA * A_ELEMS + B_ELEMS;
+  static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile / thread mismatch");
+  static_assert(EPI != GEMM_SWIGLU_BF16 || NJ % 2 == 0, "SwiGLU needs gate/up column-block pairs per wavefront");
+  extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int K = g.K, M = g.M;
   const int k_per = K / g.split_k;                 // multiple of BK (checked by the launcher)
   const int k_begin = blockIdx.z * k_per;
   const int n_steps = k_per / BK;
 
-  // Each thread moves four 16-byte chunks of A and four of B per K step.
-  const bf16_t* a_src[4];
-  const bf16_t* b_src[4];
-  int lds_off[4];
+  const bf16_t* a_src[A_CH];
+  int a_off[A_CH];
+  size_t lo_delta = 0;
+  if (SPLIT) lo_delta = (size_t)(g.a_lo - g.a);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int id = tid + i * 256, row = id >> 3, ch = id & 7;
+  for (int i = 0; i < A_CH; ++i) {
+    const int id = tid + i * NT, row = id / CPR, ch = id % CPR;
     int am = m0 + row;
     am = am < M ? am : M - 1;                      // rows past M are loaded (clamped) and never stored
     a_src[i] = g.a + (size_t)am * K + k_begin + ch * 8;
+    a_off[i] = swz<CPR>(row, ch);
+  }
+  const bf16_t* b_src[B_CH];
+  int b_off[B_CH];
+#pragma unroll
+  for (int i = 0; i < B_CH; ++i) {
+    const int id = tid + i * NT, row = id / CPR, ch = id % CPR;
     int wrow;                                      // weight row feeding tile column `row`
     const bf16_t* wbase;
     if (EPI == GEMM_SWIGLU_BF16) {
@@ -63,83 +85,95 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
       }
     }
     b_src[i] = wbase + (size_t)wrow * K + k_begin + ch * 8;
-    lds_off[i] = swz(row, ch);
+    b_off[i] = swz<CPR>(row, ch);
   }
 
-  f32x16 acc[2][2];
+  f32x16 acc[MI][NJ];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 ra[4], rb[4];
+  uint4 ra[NA][A_CH], rb[B_CH];
+  auto fetch = [&](int step) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    ra[i] = *reinterpret_cast<const uint4*>(a_src[i]);
-    rb[i] = *reinterpret_cast<const uint4*>(b_src[i]);
-  }
+    for (int i = 0; i < A_CH; ++i) {
+      ra[0][i] = *reinterpret_cast<const uint4*>(a_src[i] + (size_t)step * BK);
+      if (SPLIT) ra[NA - 1][i] = *reinterpret_cast<const uint4*>(a_src[i] + lo_delta + (size_t)step * BK);
+    }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    *reinterpret_cast<uint4*>(&sA[0][lds_off[i]]) = ra[i];
-    *reinterpret_cast<uint4*>(&sB[0][lds_off[i]]) = rb[i];
-  }
+    for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_src[i] + (size_t)step * BK);
+  };
+  auto park = [&](int buf) {
+    bf16_t* s = smem + buf * STAGE;
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+      *reinterpret_cast<uint4*>(s + a_off[i]) = ra[0][i];
+      if (SPLIT) *reinterpret_cast<uint4*>(s + A_ELEMS + a_off[i]) = ra[NA - 1][i];
+    }
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(s + NA * A_ELEMS + b_off[i]) = rb[i];
+  };
+
+  fetch(0);
+  park(0);
   __syncthreads();
 
   const int l32 = lane & 31, kb = lane >> 5;
   for (int step = 0; step < n_steps; ++step) {
     const int buf = step & 1;
-    if (step + 1 < n_steps) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        ra[i] = *reinterpret_cast<const uint4*>(a_src[i] + (size_t)(step + 1) * BK);
-        rb[i] = *reinterpret_cast<const uint4*>(b_src[i] + (size_t)(step + 1) * BK);
-      }
-    }
+    if (step + 1 < n_steps) fetch(step + 1);
+    const bf16_t* sA = smem + buf * STAGE;
+    const bf16_t* sB = sA + NA * A_ELEMS;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[2], fb[2];
+      bf16x8 fb[NJ];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int ar = wm * 64 + i * 32 + l32;
-        fa[i] = *reinterpret_cast<const bf16x8*>(&sA[buf][swz(ar, ks * 2 + kb)]);
-        const int br = wn * 64 + i * 32 + l32;
-        fb[i] = *reinterpret_cast<const bf16x8*>(&sB[buf][swz(br, ks * 2 + kb)]);
-      }
+      for (int j = 0; j < NJ; ++j)
+        fb[j] = *reinterpret_cast<const bf16x8*>(sB + swz<CPR>(wn * WN + j * 32 + l32, ks * 2 + kb));
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MI; ++i) {
+        const int ar = wm * WM + i * 32 + l32;
+        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(sA + swz<CPR>(ar, ks * 2 + kb));
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (step + 1 < n_steps) {
+        for (int j = 0; j < NJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[i][j], 0, 0, 0);
+        if (SPLIT) {
+          const bf16x8 fl = *reinterpret_cast<const bf16x8*>(sA + A_ELEMS + swz<CPR>(ar, ks * 2 + kb));
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        *reinterpret_cast<uint4*>(&sA[buf ^ 1][lds_off[i]]) = ra[i];
-        *reinterpret_cast<uint4*>(&sB[buf ^ 1][lds_off[i]]) = rb[i];
+          for (int j = 0; j < NJ; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl, fb[j], acc[i][j], 0, 0, 0);
+        }
       }
     }
+    if (step + 1 < n_steps) park(buf ^ 1);
     __syncthreads();
   }
 
   // Epilogue.  A 32x32 accumulator block leaves lane (l32, kb) with column l32 and rows
   // 8*(r/4) + 4*kb + r%4, r = 0..15.
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < MI; ++i) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int m = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
+      const int m = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
       if (m >= M) continue;
       if (EPI == GEMM_SWIGLU_BF16) {
-        const float gate = acc[i][0][r], up = acc[i][1][r];
-        const float v = gate / (1.0f + __expf(-gate)) * up;
-        bf16_t* c = reinterpret_cast<bf16_t*>(g.c);
-        c[(size_t)m * (g.N >> 1) + (n0 >> 1) + wn * 32 + l32] = (bf16_t)f2bf(v);
-      } else {
-        float* c = reinterpret_cast<float*>(g.c) + (size_t)m * g.N + n0 + wn * 64 + l32;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < NJ; j += 2) {
+          const float gate = acc[i][j][r], up = acc[i][j + 1][r];
+          const float v = gate / (1.0f + __expf(-gate)) * up;
+          const size_t at = (size_t)m * (g.N >> 1) + (n0 >> 1) + ((wn * WN + j * 32) >> 1) + l32;
+          const uint32_t hi = f2bf(v);
+          reinterpret_cast<bf16_t*>(g.c)[at] = (bf16_t)hi;
+          reinterpret_cast<bf16_t*>(g.c_lo)[at] = (bf16_t)f2bf(v - bf2f(hi));
+        }
+      } else {
+        float* c = reinterpret_cast<float*>(g.c) + (size_t)m * g.N + n0 + wn * WN + l32;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
           const float v = acc[i][j][r];
           if (g.split_k > 1) {
             unsafeAtomicAdd(c + j * 32, v);
@@ -154,33 +188,82 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   }
 }
 
-int gemm_pick_split(int M, int N, int K) {
+// ---------------------------------------------------------------------------------------------
+// Tile configurations.  N tile 256 halves the weight re-reads from L2 per MFMA; the 128-wide
+// one serves outputs whose N is not a multiple of 256 and small problems.
+struct TileCfg { int bm, bn; };
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool SPLIT>
+static hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
+  constexpr int NA = SPLIT ? 2 : 1;
+  const size_t lds = (size_t)2 * (NA * BM * BK + BN * BK) * sizeof(bf16_t);
+  const dim3 grid(g.N / BN, (g.M + BM - 1) / BM, g.split_k);
+  const dim3 block(64 * WGM * WGN);
+#define SY_LAUNCH(EPI)                                                                                      \
+  do {                                                                                                      \
+    static bool attr_done = false;                                                                          \
+    if (!attr_done) {                                                                                       \
+      hipError_t e = hipFuncSetAttribute(                                                                   \
+          reinterpret_cast<const void*>(&gemm_kernel<BM, BN, BK, WGM, WGN, SPLIT, EPI>),                    \
+          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                                            \
+      if (e != hipSuccess) return e;                                                                        \
+      attr_done = true;                                                                                     \
+    }                                                                                                       \
+    gemm_kernel<BM, BN, BK, WGM, WGN, SPLIT, EPI><<<grid, block, lds, s>>>(g);                              \
+  } while (0)
+  switch (g.epilogue) {
+    case GEMM_STORE_F32: SY_LAUNCH(GEMM_STORE_F32); break;
+    case GEMM_ADD_F32: SY_LAUNCH(GEMM_ADD_F32); break;
+    case GEMM_SWIGLU_BF16: SY_LAUNCH(GEMM_SWIGLU_BF16); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef SY_LAUNCH
+  return hipGetLastError();
+}
+
+static int g_gemm_variant = -1;   // test / tuning hook: force a tile configuration (-1 = automatic)
+void gemm_force_variant(int v) { g_gemm_variant = v; }
+
+static int pick_variant(const GemmArgs& g) {
+  if (g_gemm_variant >= 0) return g_gemm_variant;
+  bool wide_ok = g.N % 256 == 0;
+  if (g.epilogue != GEMM_SWIGLU_BF16)
+    for (int i = 0; i < 3; ++i) wide_ok = wide_ok && g.w_rows[i] % 256 == 0;
+  return (wide_ok && g.M > 64) ? 1 : 0;
+}
+
+static int variant_bn(int v) { return v == 0 ? 128 : 256; }
+static int variant_bm(int v) { return 128; }
+
+int gemm_pick_split(const GemmArgs& g) {
+  if (g.epilogue == GEMM_SWIGLU_BF16) return 1;
   // Enough blocks to cover the 256 compute units about twice; K slices stay >= 512.
-  const long tiles = (long)((M + BM - 1) / BM) * (N / BN);
+  const int v = pick_variant(g);
+  const long tiles = (long)((g.M + variant_bm(v) - 1) / variant_bm(v)) * (g.N / variant_bn(v));
   int split = 1;
-  while (tiles * split < 512 && K % (split * 2 * BK) == 0 && K / (split * 2) >= 512) split *= 2;
+  while (tiles * split < 512 && g.K % (split * 2 * 64) == 0 && g.K / (split * 2) >= 512) split *= 2;
   return split;
 }
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0) return hipSuccess;
-  if (g.N % BN != 0 || g.K % BK != 0 || g.split_k < 1 || g.K % (g.split_k * BK) != 0) return hipErrorInvalidValue;
+  const int v = pick_variant(g);
+  const int bn = variant_bn(v);
+  if (g.N % bn != 0 || g.K % 64 != 0 || g.split_k < 1 || g.K % (g.split_k * 64) != 0) return hipErrorInvalidValue;
   if (g.epilogue == GEMM_SWIGLU_BF16) {
-    if (g.split_k != 1) return hipErrorInvalidValue;
+    if (g.split_k != 1 || !g.c_lo) return hipErrorInvalidValue;
   } else {
     long rows = 0;
     for (int i = 0; i < 3; ++i) {
-      if (g.w_rows[i] % BN != 0) return hipErrorInvalidValue;
+      if (g.w_rows[i] % bn != 0) return hipErrorInvalidValue;
       rows += g.w_rows[i];
     }
     if (rows != g.N) return hipErrorInvalidValue;
   }
-  const dim3 grid(g.N / BN, (g.M + BM - 1) / BM, g.split_k);
-  switch (g.epilogue) {
-    case GEMM_STORE_F32: gemm_kernel<GEMM_STORE_F32><<<grid, 256, 0, s>>>(g); break;
-    case GEMM_ADD_F32: gemm_kernel<GEMM_ADD_F32><<<grid, 256, 0, s>>>(g); break;
-    case GEMM_SWIGLU_BF16: gemm_kernel<GEMM_SWIGLU_BF16><<<grid, 256, 0, s>>>(g); break;
+  const bool split = g.a_lo != nullptr;
+  switch (v) {
+    case 0: return split ? launch_cfg<128, 128, 64, 2, 2, true>(g, s) : launch_cfg<128, 128, 64, 2, 2, false>(g, s);
+    case 1: return split ? launch_cfg<128, 256, 32, 2, 2, true>(g, s) : launch_cfg<128, 256, 32, 2, 2, false>(g, s);
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
 }

@@ -102,25 +102,34 @@ def gpu_chain(case, reqs, anchors):
     return {i: np.asarray(d, np.int32) for i, d in drafts.items()}
 
 
-def build_case(recipe, device="cuda:0", n_oracle=None, batch_size=None, oracle_dtype=None, verbose=False):
+def draw_weights(shape, seed, device, oracle_dtype=None):
+    """Weights on the device plus the oracle's widened host copy of the same bytes.  Tests of several
+    configs with one model shape may share the result."""
+    if oracle_dtype is None:
+        oracle_dtype = np.float64 if shape.d_model <= 512 else np.float32
+    head = wl.draw_head_weights(shape, seed, device)
+    layers = [wl.draw_layer_weights(shape, seed, l, device) for l in range(shape.n_layers)]
+    return {"head": head, "layers": layers, "model": oracle_model(shape, head, layers, oracle_dtype)}
+
+
+def build_case(recipe, device="cuda:0", n_oracle=None, batch_size=None, oracle_dtype=None, verbose=False,
+               weights=None):
     shape = recipe.shape
     t0 = time.time()
     say = (lambda *a: print("[case]", *a, f"(+{time.time() - t0:.1f}s)", flush=True)) if verbose else (lambda *a: None)
     b = wl.draw_batch(recipe, batch_size)
     B = len(b["ctx_len"])
     rnd = wl.draw_draft_randoms(recipe, B)
-    head = wl.draw_head_weights(shape, recipe.seed, device)
-    layers = [wl.draw_layer_weights(shape, recipe.seed, l, device) for l in range(shape.n_layers)]
+    if weights is None:
+        weights = draw_weights(shape, recipe.seed, device, oracle_dtype)
+    head, layers = weights["head"], weights["layers"]
     say("weights drawn")
     k_pool = nan_pool(shape, b["n_pages"], device, False)
     v_pool = nan_pool(shape, b["n_pages"], device, True)
     ver = synera.Verifier(shape, head, layers, max_batch=B, max_tokens=int(b["n_draft"].sum()) + B,
                           max_pages=b["max_pages"])
     sampled = pick_sample(b, B if n_oracle is None else n_oracle)
-    if oracle_dtype is None:
-        oracle_dtype = np.float64 if shape.d_model <= 512 else np.float32
-    model = oracle_model(shape, head, layers, oracle_dtype)
-    say("oracle weights on host")
+    model = weights["model"]
     pages = [p for i in sampled for p in b["block_table"][i] if p >= 0]
     okv = oracle.PagedKV(shape.n_layers, b["n_pages"], shape.n_kv_heads, shape.head_dim,
                          pages=None if len(sampled) == B and shape.d_model <= 512 else pages)
@@ -275,9 +284,11 @@ def compare_with_oracle(case, out):
     return rep
 
 
-def compare_kv(case, atol=0.0):
+def compare_kv(case, atol=0.02):
     """KV pool after the verify, sampled requests: context positions bit-identical to the oracle's,
-    chunk positions within bf16 rounding of it, every other slot of their pages still untouched."""
+    chunk positions within a few bf16 roundings of it (|d| <= atol + 2^-6 |value|: the HIP path rounds
+    the normalised activations to bf16 before the projection, the oracle does not), every other slot
+    of their pages still untouched."""
     b = case.batch
     rep = {"ok": True, "fail": [], "max_kv_err": 0.0}
     kp = case.k_pool.view(torch.int16)
@@ -300,8 +311,8 @@ def compare_kv(case, atol=0.0):
                 elif t < L + kk:
                     ek = np.abs(oracle.bf16_from_bits(gk[:, :, s, :]) - oracle.bf16_from_bits(wk))
                     ev = np.abs(oracle.bf16_from_bits(gv[:, :, :, s]) - oracle.bf16_from_bits(wv))
-                    tol_k = atol + 2.0 ** -7 * np.abs(oracle.bf16_from_bits(wk))
-                    tol_v = atol + 2.0 ** -7 * np.abs(oracle.bf16_from_bits(wv))
+                    tol_k = atol + 2.0 ** -6 * np.abs(oracle.bf16_from_bits(wk))
+                    tol_v = atol + 2.0 ** -6 * np.abs(oracle.bf16_from_bits(wv))
                     rep["max_kv_err"] = max(rep["max_kv_err"], float(ek.max()), float(ev.max()))
                     if not (np.all(np.isfinite(ek)) and np.all(ek <= tol_k) and np.all(ev <= tol_v)):
                         rep["ok"] = False
