@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the batched-verify hot path on one MI355X.
+
+A step is one synera_verify call over the whole batch of the headline workload (the ragged
+selective-offload batch on the 8B shape: 64 requests, contexts log-uniform in [128, 4096], chunk
+lengths uniform in 1..16, bf16 weights).  Everything is synthetic and seeded; weights, KV pools,
+block tables, tokens and drafts are resident in HBM before the timed region starts (the call's
+own small metadata upload is part of the step).  Drafts come from the library's own greedy chain
+(draft j is the current greedy token with the config's match probability, else a random token).
+
+Prints ONE JSON line: verified draft tokens/s, plus
+  roofline     - the dominant kernel (gate/up projection + SiLU*mul) timed with HIP events inside
+                 the timed region, its algorithmic FLOPs against the dense bf16 MFMA peak;
+  cpu_baseline - the CPU oracle timed on a bounded sample of the same workload (this leg is the
+                 only place the benchmark touches the oracle).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def build_workload(cfg_no, device):
+    import numpy as np
+    import torch
+    import paper_2511_07423_amd as synera
+    import workloads as wl
+
+    rec = wl.config(cfg_no)
+    shape = rec.shape
+    b = wl.draw_batch(rec)
+    B = len(b["ctx_len"])
+    rnd = wl.draw_draft_randoms(rec, B)
+    head = wl.draw_head_weights(shape, rec.seed, device)
+    layers = [wl.draw_layer_weights(shape, rec.seed, l, device) for l in range(shape.n_layers)]
+    pool_dims = (shape.n_layers, b["n_pages"], shape.n_kv_heads)
+    k_pool = torch.zeros(pool_dims + (wl.PAGE_SIZE, shape.head_dim), dtype=torch.bfloat16, device=device)
+    v_pool = torch.zeros(pool_dims + (shape.head_dim, wl.PAGE_SIZE), dtype=torch.bfloat16, device=device)
+    ver = synera.Verifier(shape, head, layers, max_batch=B, max_tokens=int(b["n_draft"].sum()) + B,
+                          max_pages=b["max_pages"])
+    # cached context: N(0,1) K/V at positions 0..L-2, then a real decode of a random token at L-1
+    L = b["ctx_len"]
+    n_fill = (L - 1).astype(np.int32)
+    zeros = np.zeros(B, np.int32)
+    for l in range(shape.n_layers):
+        kr, vr = wl.draw_context_kv(shape, rec.seed, l, int(n_fill.sum()), device)
+        ver.kv_append(l, zeros, n_fill, kr, vr, b["block_table"], b["n_pages"], k_pool, v_pool)
+        torch.cuda.synchronize()
+    last = torch.from_numpy(rnd["last_ctx_tok"]).to(device)
+    out = ver.verify(n_fill, zeros, np.ones(B, np.int32), last, torch.zeros(B, dtype=torch.int32, device=device),
+                     b["block_table"], b["n_pages"], k_pool, v_pool, want_logits=False)
+    anchor = out["argmax"].clone()
+    # drafts from the library's own greedy chain
+    anchors = anchor.cpu().numpy()
+    drafts = [[] for _ in range(B)]
+    greedy = [int(a) for a in anchors]
+    for j in range(int(b["n_draft"].max())):
+        live = [i for i in range(B) if b["n_draft"][i] > j]
+        for i in live:
+            drafts[i].append(greedy[i] if rnd["u"][i][j] < rec.p_match else int(rnd["tok"][i][j]))
+        toks = torch.tensor([t for i in live for t in drafts[i]], dtype=torch.int32, device=device)
+        o = ver.verify(L[live], np.zeros(len(live), np.int32), np.full(len(live), j + 1, np.int32), toks,
+                       anchor[live], b["block_table"][live], b["n_pages"], k_pool, v_pool, want_logits=False)
+        am = o["argmax"].cpu().numpy()
+        for n, i in enumerate(live):
+            greedy[i] = int(am[(n + 1) * (j + 1) - 1])
+    tokens = torch.tensor([t for d in drafts for t in d], dtype=torch.int32, device=device)
+    return dict(rec=rec, shape=shape, batch=b, head=head, layers=layers, ver=ver, k_pool=k_pool, v_pool=v_pool,
+                tokens=tokens, anchor=anchor, drafts=drafts, rnd=rnd)
+
+
+def cpu_baseline(w, device):
+    """Times oracle.verify_chunks on a bounded sample: the first `n_req` requests through the first 2 and
+    the first 4 decoder layers (plus final norm, LM head and the verification itself), and extrapolates
+    linearly in the layer count to the full depth."""
+    import numpy as np
+    import oracle
+    import workloads as wl
+
+    rec, shape, b = w["rec"], w["shape"], w["batch"]
+    n_req, depth = 8, (2, 4)
+    to_np = lambda t: t.detach().to("cpu").float().numpy()                     # noqa: E731
+    head = {k: to_np(v) for k, v in w["head"].items()}
+    lay = [{k: to_np(v) for k, v in w["layers"][l].items()} for l in range(max(depth))]
+    L = b["ctx_len"]
+    n_fill = (L - 1).astype(np.int64)
+    starts = np.concatenate([[0], np.cumsum(n_fill)])
+    pages = [p for i in range(n_req) for p in b["block_table"][i] if p >= 0]
+    times = {}
+    n_tok = int(b["n_draft"][:n_req].sum())
+    for nl in depth:
+        model = oracle.OracleModel(nl, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                                   shape.vocab, head["embed"], lay[:nl], head["final_norm"], head["lm_head"],
+                                   rope_base=shape.rope_base, rms_eps=shape.rms_eps, dtype=np.float32)
+        kv = oracle.PagedKV(nl, b["n_pages"], shape.n_kv_heads, shape.head_dim, pages=pages)
+        for l in range(nl):
+            kr, vr = wl.draw_context_kv(shape, rec.seed, l, int(n_fill.sum()), device)
+            for i in range(n_req):
+                sl = slice(int(starts[i]), int(starts[i + 1]))
+                kv.append_many(l, b["block_table"][i], 0, to_np(kr[sl]), to_np(vr[sl]))
+        reqs = [{"block_table": b["block_table"][i], "ctx_len": int(L[i]) - 1,
+                 "uncached": [int(w["rnd"]["last_ctx_tok"][i])], "drafts": w["drafts"][i], "anchor": -1}
+                for i in range(n_req)]
+        t0 = time.perf_counter()
+        oracle.verify_chunks(model, kv, reqs)
+        times[nl] = time.perf_counter() - t0
+    per_layer = (times[depth[1]] - times[depth[0]]) / (depth[1] - depth[0])
+    fixed = max(times[depth[0]] - depth[0] * per_layer, 0.0)
+    full = fixed + shape.n_layers * per_layer
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": n_tok / full, "unit": "verified draft tokens/s", "cores": cores, "kind": "oracle",
+            "sample": (f"oracle.verify_chunks (numpy fp32) on the first {n_req} requests ({n_tok} draft tokens, "
+                       f"their real contexts) through {depth[0]} and {depth[1]} layers + LM head: "
+                       f"{times[depth[0]]:.2f}s / {times[depth[1]]:.2f}s, extrapolated linearly to "
+                       f"{shape.n_layers} layers = {full:.1f}s")}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=3, help="workload number (3 = the headline ragged batch-64 8B config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="also print per-stage times to stderr")
+    ap.add_argument("--stage", default="gate_up", help="kernel stage the roofline object reports")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (requests are independent, so N GPUs would each verify a "
+              "disjoint share of the batch with no exchange step); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2511_07423_amd as synera
+    assert torch.cuda.is_available(), "bench.py needs the GPU; there is no CPU path"
+    device = "cuda:0"
+    w = build_workload(args.config, device)
+    b, ver, shape = w["batch"], w["ver"], w["shape"]
+    B = len(b["ctx_len"])
+    T = int(b["n_draft"].sum())
+    zeros = np.zeros(B, np.int32)
+    ctx, nd, bt = (np.ascontiguousarray(b[k], dtype=np.int32) for k in ("ctx_len", "n_draft", "block_table"))
+    out = {"logits": None, "argmax": torch.empty(T, dtype=torch.int32, device=device),
+           "top1_prob": torch.empty(T, dtype=torch.float32, device=device),
+           "entropy": torch.empty(T, dtype=torch.float32, device=device),
+           "accept_len": torch.empty(B, dtype=torch.int32, device=device),
+           "correction": torch.empty(B, dtype=torch.int32, device=device)}
+
+    def step():
+        ver.verify_into(ctx, zeros, nd, w["tokens"], w["anchor"], bt, b["n_pages"], w["k_pool"], w["v_pool"], out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    stage = synera.STAGES[args.stage]
+    ver.profile_begin(stage)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_launch, stage_ms = ver.profile_end()
+    ms_per_step = dt * 1000.0 / args.steps
+    accepted = int(out["accept_len"].sum().item())
+
+    d, f, V = shape.d_model, shape.d_ffn, shape.vocab
+    qd, kd = shape.q_dim, shape.kv_dim
+    stage_flops = {"qkv": 2.0 * T * d * (qd + 2 * kd), "o": 2.0 * T * qd * d, "gate_up": 2.0 * T * d * 2 * f,
+                   "down": 2.0 * T * f * d, "lm_head": 2.0 * T * d * V}
+    kv_bytes_layer = float((b["ctx_len"] + b["n_draft"]).sum()) * 2 * shape.kv_dim * 2
+    avg_ms = stage_ms / max(n_launch, 1)
+    if args.stage in stage_flops:
+        ach = stage_flops[args.stage] / (avg_ms * 1e-3) / 1e12
+        roof = {"kernel": args.stage, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                "avg_launch_ms": avg_ms, "launches": n_launch,
+                "note": "algorithmic FLOPs 2*T*params; the kernel issues twice that (bf16 hi+lo activation pairs)"}
+    else:
+        nbytes = {"attention": kv_bytes_layer, "confidence": float(T) * V * 4}[args.stage]
+        ach = nbytes / (avg_ms * 1e-3) / 1e9
+        roof = {"kernel": args.stage, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": ach / HBM_PEAK_GBS, "traffic": None, "avg_launch_ms": avg_ms, "launches": n_launch}
+
+    res = {"metric": "verified draft tokens/sec (8B-shape bf16, batch 64) + % of HBM/MFMA roofline",
+           "value": T / (ms_per_step * 1e-3), "unit": "verified draft tokens/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": w["rec"].name, "requests": B, "draft_tokens": T,
+                      "context_tokens": int(b["ctx_len"].sum()), "accepted_plus_correction_tokens": accepted + B,
+                      "shape": shape.name},
+           "roofline": roof}
+    if args.breakdown:                      # extra passes, one stage bracketed at a time (stderr, not the JSON line)
+        total = 0.0
+        for name, sid in synera.STAGES.items():
+            if sid == 0:
+                continue
+            ver.profile_begin(sid)
+            for _ in range(args.steps):
+                step()
+            torch.cuda.synchronize()
+            n, ms = ver.profile_end()
+            total += ms / args.steps
+            print(f"[breakdown] {name:12s} {ms / args.steps:8.3f} ms/step  {n // args.steps:4d} launches/step  "
+                  f"{ms / max(n, 1) * 1e3:9.1f} us/launch", file=sys.stderr, flush=True)
+        print(f"[breakdown] stages sum {total:.3f} ms/step vs {ms_per_step:.3f} ms/step wall", file=sys.stderr)
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, device)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

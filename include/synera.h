@@ -201,13 +201,48 @@ int32_t synera_kv_append(synera_ctx* ctx, int32_t layer, int32_t B, const int32_
                          int32_t n_pages_in_pool, void* d_k_pool, void* d_v_pool, void* stream);
 
 /*
+ * Stage timing, for the roofline measurement of the kernels inside a verify
+ * (the paper gives no breakdown of where the forward pass spends its time;
+ * Section 6.7 only separates scheduling from compute).  After
+ * synera_profile_begin(ctx, stage) every launch of that stage in later
+ * synera_verify calls is bracketed by a HIP event pair on the call's stream.
+ * synera_profile_end waits for those events, returns how many launches were
+ * bracketed and the sum of their durations in milliseconds, and switches the
+ * timing off.  Errors: EINVAL (null, unknown stage), EHIP.
+ */
+typedef enum synera_stage {
+  SYNERA_STAGE_NONE = 0,
+  SYNERA_STAGE_QKV = 1,        /* Wq|Wk|Wv projection                       */
+  SYNERA_STAGE_ATTENTION = 2,  /* paged chunk attention incl. the split merge */
+  SYNERA_STAGE_O = 3,          /* output projection + residual              */
+  SYNERA_STAGE_GATE_UP = 4,    /* gate/up projection + SiLU*mul             */
+  SYNERA_STAGE_DOWN = 5,       /* down projection + residual                */
+  SYNERA_STAGE_LM_HEAD = 6,
+  SYNERA_STAGE_CONFIDENCE = 7, /* fused softmax/argmax/entropy              */
+  SYNERA_STAGE_NORM = 8,       /* RMSNorm launches inside the layers        */
+  SYNERA_STAGE_ROPE_APPEND = 9
+} synera_stage;
+int32_t synera_profile_begin(synera_ctx* ctx, int32_t stage);
+int32_t synera_profile_end(synera_ctx* ctx, int32_t* n_launches, float* total_ms);
+
+/*
  * C = A * W^T on the matrix cores, the contraction every projection of the
  * decoder uses (exported for tests and the GEMM roofline sweep).
  * d_a bf16 [M][K] row-major, d_w bf16 [N][K] row-major, d_c f32 [M][N].
+ * d_a_lo, if not NULL, is the low part of a bf16 (hi, lo) activation pair (same
+ * layout as d_a): the result is (A + A_lo) * W^T, which is how the decoder's
+ * projections keep about 16 mantissa bits of their fp32 inputs.
  * K must be a multiple of 64 and N of 128 (else EUNSUP).  Errors: EINVAL, EUNSUP, EHIP.
  */
-int32_t synera_gemm_bf16(const void* d_a, const void* d_w, float* d_c, int32_t M, int32_t N,
-                         int32_t K, void* stream);
+int32_t synera_gemm_bf16(const void* d_a, const void* d_a_lo, const void* d_w, float* d_c,
+                         int32_t M, int32_t N, int32_t K, void* stream);
+
+/*
+ * Tuning hook for the GEMM sweep: force tile configuration `variant` for every
+ * later contraction whose shape it fits (-1 restores the automatic choice).
+ * Process-wide; not for production callers.
+ */
+int32_t synera_debug_set_gemm_tile(int32_t variant);
 
 #ifdef __cplusplus
 }

@@ -6,6 +6,6 @@ runs in the HIP kernels of libsynera.so; this package only marshals arguments
 importing the binding without the built library raises.
 """
 from .binding import (  # noqa: F401
-    SyneraError, Verifier, confidence, gemm_bf16, validate_batch, version, lib_path,
-    OK, EINVAL, ERANGE, ENOSPC, EUNSUP, EHIP, ENOMEM, PAGE_SIZE, MAX_CHUNK,
+    SyneraError, Verifier, confidence, gemm_bf16, debug_set_gemm_tile, validate_batch, version, lib_path,
+    OK, EINVAL, ERANGE, ENOSPC, EUNSUP, EHIP, ENOMEM, PAGE_SIZE, MAX_CHUNK, STAGES,
 )

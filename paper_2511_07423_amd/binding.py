@@ -8,6 +8,8 @@ import torch
 OK, EINVAL, ERANGE, ENOSPC, EUNSUP, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6
 PAGE_SIZE = 16
 MAX_CHUNK = 32
+STAGES = {"none": 0, "qkv": 1, "attention": 2, "o": 3, "gate_up": 4, "down": 5, "lm_head": 6, "confidence": 7,
+          "norm": 8, "rope_append": 9}
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libsynera.so")
@@ -63,8 +65,14 @@ _lib.synera_confidence.argtypes = [_vp, C.c_int32, C.c_int64, C.c_int64, C.c_int
 _lib.synera_kv_append.restype = C.c_int32
 _lib.synera_kv_append.argtypes = [_vp, C.c_int32, C.c_int32, _i32p, _i32p, _vp, _vp, _i32p, C.c_int32, C.c_int32,
                                   _vp, _vp, _vp]
+_lib.synera_profile_begin.restype = C.c_int32
+_lib.synera_profile_begin.argtypes = [_vp, C.c_int32]
+_lib.synera_profile_end.restype = C.c_int32
+_lib.synera_profile_end.argtypes = [_vp, C.POINTER(C.c_int32), C.POINTER(C.c_float)]
 _lib.synera_gemm_bf16.restype = C.c_int32
-_lib.synera_gemm_bf16.argtypes = [_vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
+_lib.synera_gemm_bf16.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
+_lib.synera_debug_set_gemm_tile.restype = C.c_int32
+_lib.synera_debug_set_gemm_tile.argtypes = [C.c_int32]
 
 
 class SyneraError(RuntimeError):
@@ -133,14 +141,20 @@ def confidence(logits, want_prob=True, want_entropy=True):
     return ids, p, h
 
 
-def gemm_bf16(a, w):
-    """C = A W^T on the matrix cores; a bf16 [M,K], w bf16 [N,K] -> f32 [M,N]."""
+def gemm_bf16(a, w, a_lo=None, out=None):
+    """C = (A + A_lo) W^T on the matrix cores; a (and a_lo) bf16 [M,K], w bf16 [N,K] -> f32 [M,N]."""
     M, K = a.shape
     N = w.shape[0]
-    c = torch.empty((M, N), dtype=torch.float32, device=a.device)
-    st = _lib.synera_gemm_bf16(_dev(a, torch.bfloat16), _dev(w, torch.bfloat16), c.data_ptr(), M, N, K, _stream())
+    c = torch.empty((M, N), dtype=torch.float32, device=a.device) if out is None else out
+    st = _lib.synera_gemm_bf16(_dev(a, torch.bfloat16), _dev(a_lo, torch.bfloat16), _dev(w, torch.bfloat16),
+                               c.data_ptr(), M, N, K, _stream())
     _check(st, "synera_gemm_bf16")
     return c
+
+
+def debug_set_gemm_tile(variant):
+    """Tuning hook: force a GEMM tile configuration (-1 = automatic)."""
+    _lib.synera_debug_set_gemm_tile(variant)
 
 
 class Verifier:
@@ -209,6 +223,16 @@ class Verifier:
             _dev(out["top1_prob"]), _dev(out["entropy"]), _dev(out["accept_len"]), _dev(out["correction"]),
             _stream())
         _check(st, "synera_verify")
+
+    def profile_begin(self, stage):
+        """Bracket every launch of `stage` (a STAGES value) in later verifies with HIP events."""
+        _check(_lib.synera_profile_begin(self._ctx, stage), "synera_profile_begin")
+
+    def profile_end(self):
+        """-> (number of bracketed launches, their total duration in ms); switches the timing off."""
+        n, ms = C.c_int32(0), C.c_float(0.0)
+        _check(_lib.synera_profile_end(self._ctx, C.byref(n), C.byref(ms)), "synera_profile_end")
+        return n.value, ms.value
 
     def kv_append(self, layer, ctx_len, n_new, k, v, block_table, n_pages_in_pool, k_pool, v_pool):
         """Scatter bf16 rows k, v [sum n_new, Hkv, hd] of one layer into the paged pools."""

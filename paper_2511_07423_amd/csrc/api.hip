@@ -109,6 +109,30 @@ struct synera_ctx {
   hipEvent_t done[N_STAGE];
   bool pending[N_STAGE];
   uint64_t calls;
+  // optional per-stage timing: every launch of `prof_stage` is bracketed by an event pair
+  int32_t prof_stage;
+  std::vector<hipEvent_t> prof_events;   // start/stop pairs, created on demand and reused
+  size_t prof_used;
+};
+
+struct StageTimer {                      // brackets one stage launch when profiling of it is on
+  synera_ctx* c;
+  hipStream_t s;
+  bool on;
+  StageTimer(synera_ctx* c_, int32_t stage, hipStream_t s_) : c(c_), s(s_), on(c_->prof_stage == stage) {
+    if (on) mark();
+  }
+  ~StageTimer() {
+    if (on) mark();
+  }
+  void mark() {
+    if (c->prof_used == c->prof_events.size()) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) { on = false; (void)hipGetLastError(); return; }
+      c->prof_events.push_back(e);
+    }
+    (void)hipEventRecord(c->prof_events[c->prof_used++], s);
+  }
 };
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -214,6 +238,8 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
     return SYNERA_ENOMEM;
   }
   c->calls = 0;
+  c->prof_stage = SYNERA_STAGE_NONE;
+  c->prof_used = 0;
   *out = c;
   return SYNERA_OK;
 }
@@ -226,6 +252,7 @@ extern "C" int32_t synera_destroy(synera_ctx* c) {
     if (c->h_meta[s]) (void)hipHostFree(c->h_meta[s]);
     if (c->d_meta[s]) (void)hipFree(c->d_meta[s]);
   }
+  for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
   if (c->arena) (void)hipFree(c->arena);
   delete c;
   return SYNERA_OK;
@@ -452,24 +479,49 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
     const synera_layer_weights& w = c->layers[l];
     bf16_t* k_layer = static_cast<bf16_t*>(d_k_pool) + (size_t)l * layer_elems;
     bf16_t* v_layer = static_cast<bf16_t*>(d_v_pool) + (size_t)l * layer_elems;
-    HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.attn_norm), nullptr, c->y, c->y_lo, T, d, m.rms_eps,
-                           s));
-    if ((st = run_gemm(c->y, c->y_lo, w.wq, qd, w.wk, kd, w.wv, kd, c->qkv, nullptr, T, qd + 2 * kd, d,
-                       GEMM_STORE_F32, s)))
-      return st;
-    HIP_TRY(launch_rope_append(c->qkv, c->cs, p.meta, c->q, c->q_lo, k_layer, v_layer, T, Hq, Hkv, hd, s));
+    {
+      StageTimer t(c, SYNERA_STAGE_NORM, s);
+      HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.attn_norm), nullptr, c->y, c->y_lo, T, d, m.rms_eps,
+                             s));
+    }
+    {
+      StageTimer t(c, SYNERA_STAGE_QKV, s);
+      if ((st = run_gemm(c->y, c->y_lo, w.wq, qd, w.wk, kd, w.wv, kd, c->qkv, nullptr, T, qd + 2 * kd, d,
+                         GEMM_STORE_F32, s)))
+        return st;
+    }
+    {
+      StageTimer t(c, SYNERA_STAGE_ROPE_APPEND, s);
+      HIP_TRY(launch_rope_append(c->qkv, c->cs, p.meta, c->q, c->q_lo, k_layer, v_layer, T, Hq, Hkv, hd, s));
+    }
     al.k_layer = k_layer;
     al.v_layer = v_layer;
-    HIP_TRY(launch_attention(al, s));
-    if ((st = run_gemm(c->o, c->o_lo, w.wo, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, qd, GEMM_ADD_F32, s)))
-      return st;
-    HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.mlp_norm), nullptr, c->y, c->y_lo, T, d, m.rms_eps, s));
-    if ((st = run_gemm(c->y, c->y_lo, w.w_gate, 0, w.w_up, 0, nullptr, 0, c->act, c->act_lo, T, 2 * m.d_ffn, d,
-                       GEMM_SWIGLU_BF16, s)))
-      return st;
-    if ((st = run_gemm(c->act, c->act_lo, w.w_down, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, m.d_ffn,
-                       GEMM_ADD_F32, s)))
-      return st;
+    {
+      StageTimer t(c, SYNERA_STAGE_ATTENTION, s);
+      HIP_TRY(launch_attention(al, s));
+    }
+    {
+      StageTimer t(c, SYNERA_STAGE_O, s);
+      if ((st = run_gemm(c->o, c->o_lo, w.wo, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, qd, GEMM_ADD_F32, s)))
+        return st;
+    }
+    {
+      StageTimer t(c, SYNERA_STAGE_NORM, s);
+      HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.mlp_norm), nullptr, c->y, c->y_lo, T, d, m.rms_eps,
+                             s));
+    }
+    {
+      StageTimer t(c, SYNERA_STAGE_GATE_UP, s);
+      if ((st = run_gemm(c->y, c->y_lo, w.w_gate, 0, w.w_up, 0, nullptr, 0, c->act, c->act_lo, T, 2 * m.d_ffn, d,
+                         GEMM_SWIGLU_BF16, s)))
+        return st;
+    }
+    {
+      StageTimer t(c, SYNERA_STAGE_DOWN, s);
+      if ((st = run_gemm(c->act, c->act_lo, w.w_down, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, m.d_ffn,
+                         GEMM_ADD_F32, s)))
+        return st;
+    }
   }
 
   // LM head over the draft rows (plus the last uncached row of requests that have one).
@@ -477,12 +529,18 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(c->final_norm), p.meta.sel_rows, c->ysel, c->ysel_lo,
                          p.R_all, d, m.rms_eps, s));
   float* logits = (d_logits && !extra) ? d_logits : c->logits;
-  if ((st = run_gemm(c->ysel, c->ysel_lo, c->lm_head, m.vocab, nullptr, 0, nullptr, 0, logits, nullptr, p.R_all,
-                     m.vocab, d, GEMM_STORE_F32, s)))
-    return st;
+  {
+    StageTimer t(c, SYNERA_STAGE_LM_HEAD, s);
+    if ((st = run_gemm(c->ysel, c->ysel_lo, c->lm_head, m.vocab, nullptr, 0, nullptr, 0, logits, nullptr, p.R_all,
+                       m.vocab, d, GEMM_STORE_F32, s)))
+      return st;
+  }
   float* p_out = (d_top1_prob && !extra) ? d_top1_prob : c->lm_p;
   float* h_out = (d_entropy && !extra) ? d_entropy : c->lm_h;
-  HIP_TRY(launch_confidence(logits, 0, p.R_all, m.vocab, m.vocab, c->lm_ids, p_out, h_out, s));
+  {
+    StageTimer t(c, SYNERA_STAGE_CONFIDENCE, s);
+    HIP_TRY(launch_confidence(logits, 0, p.R_all, m.vocab, m.vocab, c->lm_ids, p_out, h_out, s));
+  }
   if (extra) {
     if (d_logits)
       HIP_TRY(hipMemcpyAsync(d_logits, c->logits, (size_t)p.R * m.vocab * 4, hipMemcpyDeviceToDevice, s));
@@ -491,6 +549,31 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   }
   HIP_TRY(launch_accept(d_tokens, d_anchor, c->lm_ids, p.meta, B, p.R, d_argmax, d_accept_len, d_correction, s));
   return finish_call(c, p, s);
+}
+
+// ------------------------------------------------------------------------------------ stage timing
+extern "C" int32_t synera_profile_begin(synera_ctx* c, int32_t stage) {
+  if (!c || stage < SYNERA_STAGE_NONE || stage > SYNERA_STAGE_ROPE_APPEND) return SYNERA_EINVAL;
+  c->prof_stage = stage;
+  c->prof_used = 0;
+  return SYNERA_OK;
+}
+
+extern "C" int32_t synera_profile_end(synera_ctx* c, int32_t* n_launches, float* total_ms) {
+  if (!c || !n_launches || !total_ms) return SYNERA_EINVAL;
+  *n_launches = 0;
+  *total_ms = 0.f;
+  c->prof_stage = SYNERA_STAGE_NONE;
+  const size_t pairs = c->prof_used / 2;
+  c->prof_used = 0;
+  for (size_t i = 0; i < pairs; ++i) {
+    HIP_TRY(hipEventSynchronize(c->prof_events[2 * i + 1]));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, c->prof_events[2 * i], c->prof_events[2 * i + 1]));
+    *total_ms += ms;
+  }
+  *n_launches = (int32_t)pairs;
+  return SYNERA_OK;
 }
 
 // ------------------------------------------------------------------------------------ confidence
@@ -532,10 +615,15 @@ extern "C" int32_t synera_kv_append(synera_ctx* c, int32_t layer, int32_t B, con
 }
 
 // ------------------------------------------------------------------------------------ plain GEMM
-extern "C" int32_t synera_gemm_bf16(const void* d_a, const void* d_w, float* d_c, int32_t M, int32_t N, int32_t K,
-                                    void* stream) {
+extern "C" int32_t synera_debug_set_gemm_tile(int32_t variant) {
+  gemm_force_variant(variant);
+  return SYNERA_OK;
+}
+
+extern "C" int32_t synera_gemm_bf16(const void* d_a, const void* d_a_lo, const void* d_w, float* d_c, int32_t M,
+                                    int32_t N, int32_t K, void* stream) {
   if (!d_a || !d_w || !d_c || M < 1 || N < 1 || K < 1) return SYNERA_EINVAL;
   if (N % 128 != 0 || K % 64 != 0) return SYNERA_EUNSUP;
-  return run_gemm(static_cast<const bf16_t*>(d_a), nullptr, d_w, N, nullptr, 0, nullptr, 0, d_c, nullptr, M, N, K,
+  return run_gemm(static_cast<const bf16_t*>(d_a), static_cast<const bf16_t*>(d_a_lo), d_w, N, nullptr, 0, nullptr, 0, d_c, nullptr, M, N, K,
                   GEMM_STORE_F32, static_cast<hipStream_t>(stream));
 }

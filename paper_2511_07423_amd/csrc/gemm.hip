@@ -9,6 +9,9 @@
 // The lo term reuses the weight fragments already in registers, so it costs MFMA
 // issue slots but no extra weight traffic from HBM, L2 or LDS.
 //
+// Launch: a 1-D grid whose block index is mapped to (M tile, N tile) so that the blocks sharing a
+// weight tile land on the same XCD (see the kernel).
+//
 // Tiling: a block of WGM x WGN wavefronts owns a BM x BN output tile; each wavefront
 // a (BM/WGM) x (BN/WGN) sub-tile made of 32x32 MFMA blocks.  K advances in steps of BK
 // through double-buffered LDS tiles whose 16-byte chunks are XOR-swizzled by row, so
@@ -44,7 +47,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  // XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so
+  // block b runs on XCD b % 8.  Within an XCD consecutive blocks walk the M tiles of one N tile: the
+  // blocks that share a weight tile run together on one L2 and the weights leave HBM once.
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / BN;
+  const int xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
+  const int n_tile = (within / m_tiles) * 8 + xcd;
+  if (n_tile >= n_tiles) return;
+  const int m0 = (within % m_tiles) * BM, n0 = n_tile * BN;
   const int K = g.K, M = g.M;
   const int k_per = K / g.split_k;                 // multiple of BK (checked by the launcher)
   const int k_begin = blockIdx.z * k_per;
@@ -96,61 +106,66 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  uint4 ra[NA][A_CH], rb[B_CH];
-  auto fetch = [&](int step) {
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      ra[0][i] = *reinterpret_cast<const uint4*>(a_src[i] + (size_t)step * BK);
-      if (SPLIT) ra[NA - 1][i] = *reinterpret_cast<const uint4*>(a_src[i] + lo_delta + (size_t)step * BK);
-    }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const uint4*>(b_src[i] + (size_t)step * BK);
-  };
-  auto park = [&](int buf) {
-    bf16_t* s = smem + buf * STAGE;
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-      *reinterpret_cast<uint4*>(s + a_off[i]) = ra[0][i];
-      if (SPLIT) *reinterpret_cast<uint4*>(s + A_ELEMS + a_off[i]) = ra[NA - 1][i];
-    }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) *reinterpret_cast<uint4*>(s + NA * A_ELEMS + b_off[i]) = rb[i];
-  };
-
-  fetch(0);
-  park(0);
-  __syncthreads();
-
+  // Staging registers for the next K step.  The loop body is branch-free (the last step is peeled):
+  // with the fetch under a condition the compiler kept these arrays in scratch memory.
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+  u32x4 ra[A_CH], rl[A_CH], rb[B_CH];
+#define SY_FETCH(STEP)                                                                              \
+  _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                                \
+    ra[i] = *reinterpret_cast<const u32x4*>(a_src[i] + (size_t)(STEP) * BK);                        \
+    if (SPLIT) rl[i] = *reinterpret_cast<const u32x4*>(a_src[i] + lo_delta + (size_t)(STEP) * BK);  \
+  }                                                                                                 \
+  _Pragma("unroll") for (int i = 0; i < B_CH; ++i)                                                  \
+      rb[i] = *reinterpret_cast<const u32x4*>(b_src[i] + (size_t)(STEP) * BK);
+#define SY_PARK(BUF)                                                                                \
+  {                                                                                                 \
+    bf16_t* s_ = smem + (BUF) * STAGE;                                                              \
+    _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                              \
+      *reinterpret_cast<u32x4*>(s_ + a_off[i]) = ra[i];                                             \
+      if (SPLIT) *reinterpret_cast<u32x4*>(s_ + A_ELEMS + a_off[i]) = rl[i];                        \
+    }                                                                                               \
+    _Pragma("unroll") for (int i = 0; i < B_CH; ++i)                                                \
+        *reinterpret_cast<u32x4*>(s_ + NA * A_ELEMS + b_off[i]) = rb[i];                            \
+  }
   const int l32 = lane & 31, kb = lane >> 5;
-  for (int step = 0; step < n_steps; ++step) {
+#define SY_COMPUTE(BUF)                                                                             \
+  {                                                                                                 \
+    const bf16_t* sA = smem + (BUF) * STAGE;                                                        \
+    const bf16_t* sB = sA + NA * A_ELEMS;                                                           \
+    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                        \
+      bf16x8 fb[NJ];                                                                                \
+      _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                                \
+          fb[j] = *reinterpret_cast<const bf16x8*>(sB + swz<CPR>(wn * WN + j * 32 + l32, ks * 2 + kb)); \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                              \
+        const int ar = wm * WM + i * 32 + l32;                                                      \
+        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(sA + swz<CPR>(ar, ks * 2 + kb));         \
+        _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                              \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[i][j], 0, 0, 0);     \
+        if (SPLIT) {                                                                                \
+          const bf16x8 fl = *reinterpret_cast<const bf16x8*>(sA + A_ELEMS + swz<CPR>(ar, ks * 2 + kb)); \
+          _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                            \
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl, fb[j], acc[i][j], 0, 0, 0);   \
+        }                                                                                           \
+      }                                                                                             \
+    }                                                                                               \
+  }
+
+  SY_FETCH(0)
+  SY_PARK(0)
+  __syncthreads();
+  for (int step = 0; step + 1 < n_steps; ++step) {
     const int buf = step & 1;
-    if (step + 1 < n_steps) fetch(step + 1);
-    const bf16_t* sA = smem + buf * STAGE;
-    const bf16_t* sB = sA + NA * A_ELEMS;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fb[NJ];
-#pragma unroll
-      for (int j = 0; j < NJ; ++j)
-        fb[j] = *reinterpret_cast<const bf16x8*>(sB + swz<CPR>(wn * WN + j * 32 + l32, ks * 2 + kb));
-#pragma unroll
-      for (int i = 0; i < MI; ++i) {
-        const int ar = wm * WM + i * 32 + l32;
-        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(sA + swz<CPR>(ar, ks * 2 + kb));
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[i][j], 0, 0, 0);
-        if (SPLIT) {
-          const bf16x8 fl = *reinterpret_cast<const bf16x8*>(sA + A_ELEMS + swz<CPR>(ar, ks * 2 + kb));
-#pragma unroll
-          for (int j = 0; j < NJ; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl, fb[j], acc[i][j], 0, 0, 0);
-        }
-      }
-    }
-    if (step + 1 < n_steps) park(buf ^ 1);
+    SY_FETCH(step + 1)
+    __builtin_amdgcn_sched_barrier(0);   // keep the global loads ahead of the MFMAs: the scheduler otherwise
+    SY_COMPUTE(buf)                      // sinks them to just before the LDS stores and exposes their latency
+    __builtin_amdgcn_sched_barrier(0);
+    SY_PARK(buf ^ 1)
     __syncthreads();
   }
+  SY_COMPUTE((n_steps - 1) & 1)
+#undef SY_FETCH
+#undef SY_PARK
+#undef SY_COMPUTE
 
   // Epilogue.  A 32x32 accumulator block leaves lane (l32, kb) with column l32 and rows
   // 8*(r/4) + 4*kb + r%4, r = 0..15.
@@ -191,13 +206,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 // ---------------------------------------------------------------------------------------------
 // Tile configurations.  N tile 256 halves the weight re-reads from L2 per MFMA; the 128-wide
 // one serves outputs whose N is not a multiple of 256 and small problems.
-struct TileCfg { int bm, bn; };
-
 template <int BM, int BN, int BK, int WGM, int WGN, bool SPLIT>
 static hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
   constexpr int NA = SPLIT ? 2 : 1;
   const size_t lds = (size_t)2 * (NA * BM * BK + BN * BK) * sizeof(bf16_t);
-  const dim3 grid(g.N / BN, (g.M + BM - 1) / BM, g.split_k);
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / BN;
+  const dim3 grid(8 * ((n_tiles + 7) / 8) * m_tiles, 1, g.split_k);
   const dim3 block(64 * WGM * WGN);
 #define SY_LAUNCH(EPI)                                                                                      \
   do {                                                                                                      \
@@ -221,25 +235,37 @@ static hipError_t launch_cfg(const GemmArgs& g, hipStream_t s) {
   return hipGetLastError();
 }
 
-static int g_gemm_variant = -1;   // test / tuning hook: force a tile configuration (-1 = automatic)
+static int g_gemm_variant = -1;   // tuning hook: force a tile configuration (-1 = automatic)
 void gemm_force_variant(int v) { g_gemm_variant = v; }
 
-static int pick_variant(const GemmArgs& g) {
-  if (g_gemm_variant >= 0) return g_gemm_variant;
-  bool wide_ok = g.N % 256 == 0;
+struct Variant { int bm, bn; };
+static const Variant kVariants[] = {{128, 128}, {128, 256}, {256, 128}, {256, 256}, {64, 256}, {192, 256}, {256, 256},
+                                   {128, 256}, {64, 128}, {128, 128}, {64, 256}};
+static const int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+static bool variant_fits(const GemmArgs& g, int v) {
+  const int bn = kVariants[v].bn;
+  if (g.N % bn != 0) return false;
   if (g.epilogue != GEMM_SWIGLU_BF16)
-    for (int i = 0; i < 3; ++i) wide_ok = wide_ok && g.w_rows[i] % 256 == 0;
-  return (wide_ok && g.M > 64) ? 1 : 0;
+    for (int i = 0; i < 3; ++i)
+      if (g.w_rows[i] % bn != 0) return false;
+  return true;
 }
 
-static int variant_bn(int v) { return v == 0 ? 128 : 256; }
-static int variant_bm(int v) { return 128; }
+static int pick_variant(const GemmArgs& g) {
+  if (g_gemm_variant >= 0 && g_gemm_variant < kNumVariants && variant_fits(g, g_gemm_variant)) return g_gemm_variant;
+  // From the tile sweep on MI355X (hi+lo activations): 128x256 with 8 wavefronts wins for large M,
+  // 128x128x32 in between, 64x128 (more, smaller blocks) for skinny problems.
+  if (g.M >= 768 && variant_fits(g, 7)) return 7;
+  if (g.M > 128) return 9;
+  return 8;
+}
 
 int gemm_pick_split(const GemmArgs& g) {
   if (g.epilogue == GEMM_SWIGLU_BF16) return 1;
   // Enough blocks to cover the 256 compute units about twice; K slices stay >= 512.
-  const int v = pick_variant(g);
-  const long tiles = (long)((g.M + variant_bm(v) - 1) / variant_bm(v)) * (g.N / variant_bn(v));
+  const Variant v = kVariants[pick_variant(g)];
+  const long tiles = (long)((g.M + v.bm - 1) / v.bm) * (g.N / v.bn);
   int split = 1;
   while (tiles * split < 512 && g.K % (split * 2 * 64) == 0 && g.K / (split * 2) >= 512) split *= 2;
   return split;
@@ -248,22 +274,31 @@ int gemm_pick_split(const GemmArgs& g) {
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0) return hipSuccess;
   const int v = pick_variant(g);
-  const int bn = variant_bn(v);
-  if (g.N % bn != 0 || g.K % 64 != 0 || g.split_k < 1 || g.K % (g.split_k * 64) != 0) return hipErrorInvalidValue;
+  if (!variant_fits(g, v) || g.K % 64 != 0 || g.split_k < 1 || g.K % (g.split_k * 64) != 0)
+    return hipErrorInvalidValue;
   if (g.epilogue == GEMM_SWIGLU_BF16) {
     if (g.split_k != 1 || !g.c_lo) return hipErrorInvalidValue;
   } else {
     long rows = 0;
-    for (int i = 0; i < 3; ++i) {
-      if (g.w_rows[i] % bn != 0) return hipErrorInvalidValue;
-      rows += g.w_rows[i];
-    }
+    for (int i = 0; i < 3; ++i) rows += g.w_rows[i];
     if (rows != g.N) return hipErrorInvalidValue;
   }
   const bool split = g.a_lo != nullptr;
+#define SY_VARIANT(BM_, BN_, BK_, WGM_, WGN_) \
+  return split ? launch_cfg<BM_, BN_, BK_, WGM_, WGN_, true>(g, s) : launch_cfg<BM_, BN_, BK_, WGM_, WGN_, false>(g, s)
   switch (v) {
-    case 0: return split ? launch_cfg<128, 128, 64, 2, 2, true>(g, s) : launch_cfg<128, 128, 64, 2, 2, false>(g, s);
-    case 1: return split ? launch_cfg<128, 256, 32, 2, 2, true>(g, s) : launch_cfg<128, 256, 32, 2, 2, false>(g, s);
+    case 0: SY_VARIANT(128, 128, 64, 2, 2);
+    case 1: SY_VARIANT(128, 256, 32, 2, 2);
+    case 2: SY_VARIANT(256, 128, 32, 2, 2);
+    case 3: SY_VARIANT(256, 256, 32, 2, 4);
+    case 4: SY_VARIANT(64, 256, 32, 1, 4);
+    case 5: SY_VARIANT(192, 256, 32, 2, 2);
+    case 6: SY_VARIANT(256, 256, 32, 2, 2);
+    case 7: SY_VARIANT(128, 256, 32, 2, 4);
+    case 8: SY_VARIANT(64, 128, 32, 1, 2);
+    case 9: SY_VARIANT(128, 128, 32, 2, 2);
+    case 10: SY_VARIANT(64, 256, 64, 1, 4);
     default: return hipErrorInvalidValue;
   }
+#undef SY_VARIANT
 }
