@@ -16,6 +16,8 @@ def build_library(verbose=False):
     res = subprocess.run(cmd, capture_output=True, text=True)
     # hipcc's host pass does not know the packed-fp32 target feature and says so; harmless.
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if len(err) > 6000:
+        err = err[:3000] + "\n...\n" + err[-3000:]
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():

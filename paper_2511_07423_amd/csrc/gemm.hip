@@ -150,6 +150,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     }                                                                                               \
   }
 
+  // Instruction order inside one K step: the fragment reads of k-slice ks+1 are interleaved one by one
+  // with the MFMAs of k-slice ks, so a wavefront covers its own LDS latency.
+#define SY_SCHED()                                                                                  \
+  {                                                                                                 \
+    constexpr int RPK = NJ + MI * NA, MPK = MI * NJ * NA, KSN = BK / 16;                            \
+    constexpr int REST = MPK > RPK ? MPK - RPK : 0;                                                 \
+    __builtin_amdgcn_sched_group_barrier(0x100, RPK, 0);                                            \
+    _Pragma("unroll") for (int ks = 0; ks + 1 < KSN; ++ks) {                                        \
+      _Pragma("unroll") for (int i = 0; i < RPK; ++i) {                                             \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                          \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                          \
+      }                                                                                             \
+      __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);                                         \
+    }                                                                                               \
+    __builtin_amdgcn_sched_group_barrier(0x008, MPK, 0);                                            \
+  }
+
   SY_FETCH(0)
   SY_PARK(0)
   __syncthreads();
@@ -158,6 +175,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     SY_FETCH(step + 1)
     __builtin_amdgcn_sched_barrier(0);   // keep the global loads ahead of the MFMAs: the scheduler otherwise
     SY_COMPUTE(buf)                      // sinks them to just before the LDS stores and exposes their latency
+    SY_SCHED()
     __builtin_amdgcn_sched_barrier(0);
     SY_PARK(buf ^ 1)
     __syncthreads();
@@ -166,6 +184,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 #undef SY_FETCH
 #undef SY_PARK
 #undef SY_COMPUTE
+#undef SY_SCHED
 
   // Epilogue.  A 32x32 accumulator block leaves lane (l32, kb) with column l32 and rows
   // 8*(r/4) + 4*kb + r%4, r = 0..15.
@@ -201,6 +220,196 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
       }
     }
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Variant with asynchronous global->LDS copies (global_load_lds_dwordx4): the tile rows
+// [A_hi | A_lo | W] of K step s+2 stream straight into LDS while step s is multiplied, with no
+// staging registers and no LDS store instructions.  Three LDS stages, BK = 32.  A copy instruction
+// of one wavefront fills 1 KB = 16 tile rows; the XOR swizzle is applied on the global side (lane i
+// fetches the chunk that belongs at LDS position i).  Synchronisation per K step: each wavefront
+// waits for its own copies of the step (s_waitcnt vmcnt), one s_barrier makes every wavefront's
+// copies visible and certifies that the stage about to be overwritten is no longer read.
+// The three stages are separate arrays so the compiler can tell copies in flight from fragment
+// reads apart (with one array it waits for ALL copies before every LDS read).
+// The copy is issued from inline assembly: through the compiler builtin every later LDS read is
+// preceded by a wait for ALL copies in flight once more than a few distinct copy instructions
+// exist, which would serialise the pipeline.  m0 carries the wavefront-uniform LDS address; lane i
+// lands at that address + 16 i.
+__device__ __forceinline__ void glds16(const void* gptr, const void* lds_ptr) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds_ptr);
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
+#define SY_GLDS16(gptr, lptr) glds16((gptr), (lptr))
+
+template <int BM, int BN, int BK, int WGM, int WGN, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
+  constexpr int CPR = BK / 8, NW = WGM * WGN;
+  constexpr int RPI = 64 / CPR;             // tile rows filled by one copy instruction (1 KB)
+  constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NJ = WN / 32;
+  constexpr int R = 2 * BM + BN;            // tile rows per stage: A_hi, A_lo, W
+  constexpr int IPS = R / RPI, IPW = IPS / NW;
+  static_assert(R % RPI == 0 && IPS % NW == 0, "rows per stage must split evenly over the wavefronts");
+  static_assert(EPI != GEMM_SWIGLU_BF16 || NJ % 2 == 0, "SwiGLU needs gate/up column-block pairs per wavefront");
+  __shared__ __attribute__((aligned(16))) bf16_t st0[R * BK];
+  __shared__ __attribute__((aligned(16))) bf16_t st1[R * BK];
+  __shared__ __attribute__((aligned(16))) bf16_t st2[R * BK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / BN;
+  const int xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
+  const int n_tile = (within / m_tiles) * 8 + xcd;
+  if (n_tile >= n_tiles) return;
+  const int m0 = (within % m_tiles) * BM, n0 = n_tile * BN;
+  const int K = g.K, M = g.M;
+  const int k_per = K / g.split_k;
+  const int k_begin = blockIdx.z * k_per;
+  const int n_steps = k_per / BK;
+
+  // Source of this lane for each of the wavefront's copy instructions.
+  const bf16_t* src[IPW];
+#pragma unroll
+  for (int j = 0; j < IPW; ++j) {
+    const int r = (wave * IPW + j) * RPI + lane / CPR;
+    const int ch = (lane % CPR) ^ ((r / (8 / CPR)) % CPR);
+    const bf16_t* base;
+    if (r < 2 * BM) {
+      int am = m0 + (r < BM ? r : r - BM);
+      am = am < M ? am : M - 1;                    // rows past M are copied (clamped) and never stored
+      base = (r < BM ? g.a : g.a_lo) + (size_t)am * K;
+    } else {
+      const int col = r - 2 * BM;
+      int wrow;
+      const bf16_t* wbase;
+      if (EPI == GEMM_SWIGLU_BF16) {
+        wrow = (n0 >> 1) + ((col >> 6) << 5) + (col & 31);
+        wbase = ((col >> 5) & 1) ? g.w[1] : g.w[0];
+      } else {
+        wrow = n0 + col;
+        wbase = g.w[0];
+        if (wrow >= g.w_rows[0]) {
+          wrow -= g.w_rows[0];
+          wbase = g.w[1];
+          if (wrow >= g.w_rows[1]) {
+            wrow -= g.w_rows[1];
+            wbase = g.w[2];
+          }
+        }
+      }
+      base = wbase + (size_t)wrow * K;
+    }
+    src[j] = base + k_begin + ch * 8;
+  }
+
+  f32x16 acc[MI][NJ];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int l32 = lane & 31, kb = lane >> 5;
+#define SY_ISSUE(STAGE, STEP)                                                                     \
+  _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                                 \
+      SY_GLDS16(src[j] + (size_t)(STEP) * BK, STAGE + (wave * IPW + j) * RPI * BK);
+#define SY_MULT(STAGE)                                                                            \
+  {                                                                                               \
+    _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                      \
+      bf16x8 fb[NJ];                                                                              \
+      _Pragma("unroll") for (int j = 0; j < NJ; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(    \
+          STAGE + 2 * BM * BK + swz<CPR>(wn * WN + j * 32 + l32, ks * 2 + kb));                   \
+      _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                            \
+        const int ar = wm * WM + i * 32 + l32;                                                    \
+        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(STAGE + swz<CPR>(ar, ks * 2 + kb));    \
+        const bf16x8 fl = *reinterpret_cast<const bf16x8*>(STAGE + BM * BK + swz<CPR>(ar, ks * 2 + kb)); \
+        _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                            \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[i][j], 0, 0, 0);   \
+        _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                            \
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl, fb[j], acc[i][j], 0, 0, 0);   \
+      }                                                                                           \
+    }                                                                                             \
+  }
+  // One K step: CUR holds step s; NXT (the stage read in step s-1) receives step s+2.  Past the end
+  // the last step is copied again (never read): exactly one younger copy group is then always in
+  // flight, so the wait count is a constant and no branch surrounds the copies (under a branch the
+  // compiler loses track of which stage a copy targets and waits for all of them before every read).
+#define SY_STEP(CUR, NXT, S_)                                                                     \
+  {                                                                                               \
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(IPW) : "memory");                         \
+    asm volatile("s_barrier" ::: "memory");                                                       \
+    const int nxt_ = (S_) + 2 < n_steps ? (S_) + 2 : n_steps - 1;                                 \
+    SY_ISSUE(NXT, nxt_)                                                                           \
+    SY_MULT(CUR)                                                                                  \
+  }
+
+  SY_ISSUE(st0, 0)
+  {
+    const int one_ = n_steps > 1 ? 1 : 0;
+    SY_ISSUE(st1, one_)
+  }
+  int s = 0;
+  for (; s + 3 <= n_steps; s += 3) {
+    SY_STEP(st0, st2, s)
+    SY_STEP(st1, st0, s + 1)
+    SY_STEP(st2, st1, s + 2)
+  }
+  if (s < n_steps) {
+    SY_STEP(st0, st2, s)
+    if (s + 1 < n_steps) SY_STEP(st1, st0, s + 1)
+  }
+#undef SY_ISSUE
+#undef SY_MULT
+#undef SY_STEP
+
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
+      if (m >= M) continue;
+      if (EPI == GEMM_SWIGLU_BF16) {
+#pragma unroll
+        for (int j = 0; j < NJ; j += 2) {
+          const float gate = acc[i][j][r], up = acc[i][j + 1][r];
+          const float v = gate / (1.0f + __expf(-gate)) * up;
+          const size_t at = (size_t)m * (g.N >> 1) + (n0 >> 1) + ((wn * WN + j * 32) >> 1) + l32;
+          const uint32_t hi = f2bf(v);
+          reinterpret_cast<bf16_t*>(g.c)[at] = (bf16_t)hi;
+          reinterpret_cast<bf16_t*>(g.c_lo)[at] = (bf16_t)f2bf(v - bf2f(hi));
+        }
+      } else {
+        float* c = reinterpret_cast<float*>(g.c) + (size_t)m * g.N + n0 + wn * WN + l32;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const float v = acc[i][j][r];
+          if (g.split_k > 1) {
+            unsafeAtomicAdd(c + j * 32, v);
+          } else if (EPI == GEMM_ADD_F32) {
+            c[j * 32] += v;
+          } else {
+            c[j * 32] = v;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN>
+static hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / BN;
+  const dim3 grid(8 * ((n_tiles + 7) / 8) * m_tiles, 1, g.split_k);
+  const dim3 block(64 * WGM * WGN);
+  switch (g.epilogue) {
+    case GEMM_STORE_F32: gemm_dma_kernel<BM, BN, BK, WGM, WGN, GEMM_STORE_F32><<<grid, block, 0, s>>>(g); break;
+    case GEMM_ADD_F32: gemm_dma_kernel<BM, BN, BK, WGM, WGN, GEMM_ADD_F32><<<grid, block, 0, s>>>(g); break;
+    case GEMM_SWIGLU_BF16: gemm_dma_kernel<BM, BN, BK, WGM, WGN, GEMM_SWIGLU_BF16><<<grid, block, 0, s>>>(g); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -240,7 +449,9 @@ void gemm_force_variant(int v) { g_gemm_variant = v; }
 
 struct Variant { int bm, bn; };
 static const Variant kVariants[] = {{128, 128}, {128, 256}, {256, 128}, {256, 256}, {64, 256}, {192, 256}, {256, 256},
-                                   {128, 256}, {64, 128}, {128, 128}, {64, 256}};
+                                   {128, 256}, {64, 128}, {128, 128}, {64, 256},
+                                   {128, 128}, {128, 256}, {128, 256}, {64, 256},    // 11..: async-copy kernels
+                                   {64, 256}, {128, 128}, {64, 128}};
 static const int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 static bool variant_fits(const GemmArgs& g, int v) {
@@ -253,9 +464,16 @@ static bool variant_fits(const GemmArgs& g, int v) {
 }
 
 static int pick_variant(const GemmArgs& g) {
-  if (g_gemm_variant >= 0 && g_gemm_variant < kNumVariants && variant_fits(g, g_gemm_variant)) return g_gemm_variant;
-  // From the tile sweep on MI355X (hi+lo activations): 128x256 with 8 wavefronts wins for large M,
-  // 128x128x32 in between, 64x128 (more, smaller blocks) for skinny problems.
+  if (g_gemm_variant >= 0 && g_gemm_variant < kNumVariants && variant_fits(g, g_gemm_variant) &&
+      (g_gemm_variant < 11 || g.a_lo))
+    return g_gemm_variant;
+  // From the tile sweeps on MI355X.  With (hi, lo) activations the asynchronous-copy kernels win:
+  // 128x256 with 8 wavefronts for large M, 64x256 otherwise, 128x128 where N is not a multiple of 256.
+  if (g.a_lo) {
+    if (g.M >= 768 && variant_fits(g, 13)) return 13;
+    if (variant_fits(g, 14)) return 14;
+    return 11;
+  }
   if (g.M >= 768 && variant_fits(g, 7)) return 7;
   if (g.M > 128) return 9;
   return 8;
@@ -276,6 +494,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   const int v = pick_variant(g);
   if (!variant_fits(g, v) || g.K % 64 != 0 || g.split_k < 1 || g.K % (g.split_k * 64) != 0)
     return hipErrorInvalidValue;
+  if (v >= 11 && !g.a_lo) return hipErrorInvalidValue;
   if (g.epilogue == GEMM_SWIGLU_BF16) {
     if (g.split_k != 1 || !g.c_lo) return hipErrorInvalidValue;
   } else {
@@ -298,6 +517,13 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     case 8: SY_VARIANT(64, 128, 32, 1, 2);
     case 9: SY_VARIANT(128, 128, 32, 2, 2);
     case 10: SY_VARIANT(64, 256, 64, 1, 4);
+    case 11: return launch_dma<128, 128, 32, 2, 2>(g, s);
+    case 12: return launch_dma<128, 256, 32, 2, 2>(g, s);
+    case 13: return launch_dma<128, 256, 32, 2, 4>(g, s);
+    case 14: return launch_dma<64, 256, 32, 1, 4>(g, s);
+    case 15: return launch_dma<64, 256, 64, 1, 4>(g, s);
+    case 16: return launch_dma<128, 128, 64, 2, 2>(g, s);
+    case 17: return launch_dma<64, 128, 64, 2, 2>(g, s);
     default: return hipErrorInvalidValue;
   }
 #undef SY_VARIANT
