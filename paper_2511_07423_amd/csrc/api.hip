@@ -13,7 +13,7 @@
 
 #define SY_VERSION 100
 #define N_STAGE 4              // metadata staging slots (calls may run this far ahead of the GPU)
-#define ATTN_TARGET_BLOCKS 1536
+#define ATTN_TARGET_BLOCKS 768
 
 #define HIP_TRY(expr)                       \
   do {                                      \
@@ -377,6 +377,10 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
       for (const AttnItem& it : items[cls]) hi[w++] = it;
     }
     p.class_begin[3] = (int32_t)w;
+    // one launch takes them all: longest key ranges first, so the tail of the grid is short work
+    std::stable_sort(hi, hi + w, [](const AttnItem& x, const AttnItem& y) {
+      return (x.key_end - x.key_begin) > (y.key_end - y.key_begin);
+    });
     at = o_items + w * 8;
   }
   if (at * 4 > c->meta_cap) return SYNERA_ENOSPC;

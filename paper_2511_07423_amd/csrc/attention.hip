@@ -4,55 +4,31 @@
 // causally, the chunk itself (a prefill "with an existing KV-cached prefix",
 // Section 3.4).  Grouped-query attention: q head hq reads KV head hq / G.
 //
-// Design (gfx950, 64-wide wavefronts, no LDS in the main loop):
-//   * A work item is (request, group of <= 64 query rows = chunk tokens x G heads
-//     of one KV head, key range).  One 256-thread block per (item, KV head); its
-//     four wavefronts take 32-key tiles (two pages) round-robin, each running its
-//     own online softmax, and merge through LDS once at the end.
-//   * Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_16x16x32_bf16:
-//     the A operand is a K page read straight from HBM (lane = (slot, 16-byte dim
-//     chunk), so a page is fetched as whole 64-byte segments exactly once), the B
-//     operand is Q held in registers for the whole item.  The result leaves each
-//     lane with 4 keys x 1 query row, so softmax statistics are per-lane plus two
-//     cross-lane exchanges, and the probabilities are already laid out as the B
-//     operand of O^T = V^T P^T.  V pages are stored dim-major ([dim][slot]), which
-//     makes the A operand of that product two plain 8-byte loads per lane.
+// Design (gfx950, 64-wide wavefronts):
+//   * A work item is (request, group of <= 64 query rows = chunk tokens x G heads of one KV head,
+//     key range).  One 256-thread block per (item, KV head).
+//   * K/V pages are staged in LDS by asynchronous global->LDS copies (global_load_lds_dwordx4): a
+//     page tile is 4 KB (2 KB at head_dim 64) contiguous in HBM, so every copy instruction moves one
+//     fully coalesced kilobyte, needs no registers, and a ring of 4 key tiles per block (two blocks,
+//     64-96 KB per compute unit) stays in flight behind the ones being multiplied.  Each K/V byte of the key range leaves
+//     HBM once per KV head and is shared by all G x k_i query rows.
+//   * The four wavefronts split the row group into 16-row blocks (RBN = 2 or 4 of them) and, with
+//     two blocks, the keys of a super-tile into two phases of 32 keys (two pages); a wavefront
+//     owns one (row block, phase).  Phases merge through LDS at the
+//     end; key ranges of one row group merge in attn_combine_kernel.
+//   * Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_16x16x32_bf16: the A operand is
+//     a K page fragment (lane = (slot, 16-byte dim chunk); chunks are XOR-swizzled by slot on the
+//     way into LDS so the reads are bank-conflict free), the B operand is Q in registers.  The
+//     result leaves each lane with 4 keys x 1 query row: softmax statistics are per-lane plus two
+//     cross-lane exchanges, and the probabilities are already the B operand of O^T = V^T P^T.
+//     V pages are stored dim-major ([dim][slot]), which makes the A operand of that product plain
+//     8-byte LDS reads.
 //   * q and the probabilities enter the matrix cores as bf16 (hi, lo) pairs (two MFMAs per
 //     product, K/V fragments reused), and o leaves as a pair: single bf16 terms here cost the
-//     logits of a deep decoder an order of magnitude in accuracy.  The Q pairs of the row
-//     group sit in LDS in fragment order (each lane re-reads its own 16 bytes per tile).
-//   * Every K/V byte of the key range is read once per KV head and shared by the
-//     G x k_i query rows.  Ranges are split across blocks for occupancy; partial
-//     (m, l, O) results are merged by attn_combine_kernel.
+//     logits of a deep decoder an order of magnitude in accuracy.
 #include "common.h"
 
 #define NEG_BIG (-1e30f)
-
-template <int HD>
-struct KVTile {
-  bf16x8 k[2][HD / 32];   // [page][k-step]: 8 dims of one key slot
-  uint2 v[HD / 16][2];    // [dim block][page]: 4 key slots of one dim
-};
-
-template <int HD>
-__device__ __forceinline__ void load_tile(KVTile<HD>& t, const bf16_t* __restrict__ k_layer,
-                                          const bf16_t* __restrict__ v_layer, int pa, int pb, int Hkv, int kh,
-                                          int n16, int g) {
-  const bf16_t* ka = k_layer + ((size_t)pa * Hkv + kh) * (SY_PAGE * HD) + n16 * HD + 8 * g;
-  const bf16_t* kb = k_layer + ((size_t)pb * Hkv + kh) * (SY_PAGE * HD) + n16 * HD + 8 * g;
-#pragma unroll
-  for (int s = 0; s < HD / 32; ++s) {
-    t.k[0][s] = *reinterpret_cast<const bf16x8*>(ka + 32 * s);
-    t.k[1][s] = *reinterpret_cast<const bf16x8*>(kb + 32 * s);
-  }
-  const bf16_t* va = v_layer + ((size_t)pa * Hkv + kh) * (SY_PAGE * HD) + n16 * SY_PAGE + 4 * g;
-  const bf16_t* vb = v_layer + ((size_t)pb * Hkv + kh) * (SY_PAGE * HD) + n16 * SY_PAGE + 4 * g;
-#pragma unroll
-  for (int db = 0; db < HD / 16; ++db) {
-    t.v[db][0] = *reinterpret_cast<const uint2*>(va + db * 16 * SY_PAGE);
-    t.v[db][1] = *reinterpret_cast<const uint2*>(vb + db * 16 * SY_PAGE);
-  }
-}
 
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -67,221 +43,279 @@ __device__ __forceinline__ void store_pair(bf16_t* hi, bf16_t* lo, float a, floa
   *reinterpret_cast<uint2*>(lo) = l;
 }
 
-template <int HD, int RB>
-__global__ __launch_bounds__(256) void attn_kernel(AttnLaunch a, int item_base, float scale_log2) {
-  constexpr int KS = HD / 32;
-  constexpr int DB = HD / 16;
-  constexpr int ROWS = RB * 16;
-  constexpr int OSTRIDE = HD + 4;                 // padded LDS row (floats)
-  extern __shared__ float lds[];
-  float* s_o = lds;                               // [4][ROWS][OSTRIDE]
-  float* s_m = lds + 4 * ROWS * OSTRIDE;          // [4][ROWS]
-  float* s_l = s_m + 4 * ROWS;                    // [4][ROWS]
-  float* s_ms = s_l + 4 * ROWS;                   // [ROWS] merged max
-  float* s_ls = s_ms + ROWS;                      // [ROWS] merged sum
+// Asynchronous 16-byte-per-lane copy global -> LDS; lane i lands at lds_addr + 16 i (m0 carries the
+// wavefront-uniform LDS address).  Issued from inline assembly so that the waits are exactly the
+// ones written below.
+__device__ __forceinline__ void copy_to_lds(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
 
-  const AttnItem it = a.items[item_base + blockIdx.x];
+template <int HD, int RBN>
+__device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& it, float scale_log2) {
+  constexpr int KP = 4 / RBN;                       // key phases per super-tile
+  constexpr int S = RBN;                            // LDS stages (super-tiles): 64 KB at head_dim 128,
+                                                    // so two blocks (8 wavefronts) share a compute unit
+  constexpr int KS = HD / 32, DB = HD / 16;
+  constexpr int PAGE_B = SY_PAGE * HD * 2;          // bytes of one K or V page tile
+  constexpr int TILE_B = 4 * PAGE_B;                // K page a, K page b, V page a, V page b
+  constexpr int STAGE_B = KP * TILE_B;
+  constexpr int IPP = PAGE_B / 1024;                // copy instructions per page
+  constexpr int IPW = KP * IPP;                     // copy instructions per wavefront and super-tile
+  constexpr int CPS = HD / 8;                       // 16-byte chunks per K slot
+  constexpr int OSTRIDE = HD + 4;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
   const int kh = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n16 = lane & 15, g = lane >> 4;
+  const int rb = wave % RBN, kp = wave / RBN;
   const int Hq = a.Hq, Hkv = a.Hkv;
   const int G = Hq / Hkv;
   const int nrows = it.ntok * G;
-  const int32_t* bt = a.block_table + (size_t)it.req * a.max_pages;
-
-  // Q fragments (B operand: lane = (row n16, dim chunk g)) as (hi, lo) pairs, parked in LDS in
-  // fragment order: fragment f = (rb * KS + s) * 2 + part, 64 lanes x 16 bytes each.  Rows past the
-  // group are zero.  The region is reused by the merge at the end.
-  bf16x8* s_q = reinterpret_cast<bf16x8*>(lds);
-  int lim[RB];                                    // last key this lane's row may see
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int row = rb * 16 + n16;
-    lim[rb] = row < nrows ? it.ctx_len + it.j0 + row / G : 0x7FFFFFFF;
-  }
-  for (int f = wave; f < RB * KS * 2; f += 4) {
-    const int part = f & 1, s = (f >> 1) % KS, rb = (f >> 1) / KS;
-    const int row = rb * 16 + n16;
-    bf16x8 v = bf16x8{};
-    if (row < nrows) {
-      const bf16_t* qp = (part ? a.q_lo : a.q) + ((size_t)(it.tok0 + row / G) * Hq + kh * G + row % G) * HD;
-      v = *reinterpret_cast<const bf16x8*>(qp + 32 * s + 8 * g);
-    }
-    s_q[f * 64 + lane] = v;
-  }
-  __syncthreads();
-
-  float m_run[RB], l_run[RB];
-  f32x4 acc[RB][DB];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    m_run[rb] = NEG_BIG;
-    l_run[rb] = 0.f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db) acc[rb][db] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-
+  const int32_t* bt = a.block_table + (size_t)__builtin_amdgcn_readfirstlane(it.req) * a.max_pages;
   const int key_end = it.key_end;
-  const int free_end = min(key_end, it.ctx_len + it.j0 + 1);   // keys below this need no mask at all
-  int kb = it.key_begin + 32 * wave;
+  const int last_page = (key_end - 1) >> 4;
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds;
 
-  auto pages_of = [&](int kbase, int& pa, int& pb) {
-    pa = bt[kbase >> 4];
-    pb = (kbase + 16 < key_end) ? bt[(kbase >> 4) + 1] : pa;
-  };
-
-  KVTile<HD> cur;
-  int pa = 0, pb = 0;
-  if (kb < key_end) {
-    pages_of(kb, pa, pb);
-    load_tile<HD>(cur, a.k_layer, a.v_layer, pa, pb, Hkv, kh, n16, g);
-  }
-  while (kb < key_end) {
-    const int kb_next = kb + 128;
-    KVTile<HD> nxt;
-    if (kb_next < key_end) {                       // issue the next tile's loads before computing
-      int na, nb;
-      pages_of(kb_next, na, nb);
-      load_tile<HD>(nxt, a.k_layer, a.v_layer, na, nb, Hkv, kh, n16, g);
+  // ---- what this lane copies: per instruction j the page slot inside the stage and the lane's element
+  //      offset inside the page (K chunks are swizzled by slot, V is copied straight)
+  int c_tile[IPW], c_pg[IPW], c_q[IPW], c_off[IPW];
+#pragma unroll
+  for (int j = 0; j < IPW; ++j) {
+    const int e = wave * IPW + j;
+    c_q[j] = e % IPP;
+    c_pg[j] = (e / IPP) % 4;
+    c_tile[j] = e / (4 * IPP);
+    if (c_pg[j] < 2) {
+      const int slot = c_q[j] * (1024 / (HD * 2)) + lane / CPS;
+      c_off[j] = slot * HD + (((lane % CPS) ^ (slot & 7)) << 3);
+    } else {
+      c_off[j] = c_q[j] * 512 + lane * 8;
     }
+  }
+  const size_t page_elems = (size_t)Hkv * SY_PAGE * HD;
+  const bf16_t* k_head = a.k_layer + (size_t)kh * SY_PAGE * HD;
+  const bf16_t* v_head = a.v_layer + (size_t)kh * SY_PAGE * HD;
 
-    if (kb + 32 > key_end) {                       // tail tile: blank V slots past the range (may be junk)
+  const int n_keys = key_end - it.key_begin;
+  const int n_iter = (n_keys + 32 * KP - 1) / (32 * KP);
+  // Copies of super-tile `iter` into stage iter % S.  Past the last super-tile the same number of
+  // copies is still issued (the wait counts below stay constant), into a per-wavefront dump kilobyte.
+  // All copies of one wavefront belong to one 32-key tile of the super-tile (c_tile[0]); its two
+  // page ids come from the block table through the scalar unit (explicitly: after an asm memory
+  // clobber the compiler would fetch them with vector loads and wait for every copy in flight).
+  auto issue = [&](int iter) {
+    const bool real = iter < n_iter;
+    const int it_ = real ? iter : n_iter - 1;
+    const uint32_t stage = lds_base + (uint32_t)(it_ % S) * STAGE_B;
+    const uint32_t dump = lds_base + S * STAGE_B + wave * 1024;
+    int i0 = (it.key_begin + (it_ * KP + c_tile[0]) * 32) >> 4;
+    i0 = i0 < last_page ? i0 : last_page;            // past the range: a valid page, masked later
+    const int i1 = i0 + 1 < last_page ? i0 + 1 : last_page;
+    const int32_t* p0 = bt + __builtin_amdgcn_readfirstlane(i0);
+    const int32_t* p1 = bt + __builtin_amdgcn_readfirstlane(i1);
+    int page_a, page_b;
+    asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(page_a), "=&s"(page_b)
+                 : "s"(p0), "s"(p1)
+                 : "memory");
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) {
+      const int page = (c_pg[j] & 1) ? page_b : page_a;
+      const bf16_t* src = (c_pg[j] < 2 ? k_head : v_head) + (size_t)page * page_elems + c_off[j];
+      copy_to_lds(src, real ? stage + c_tile[j] * TILE_B + c_pg[j] * PAGE_B + c_q[j] * 1024 : dump);
+    }
+  };
+#pragma unroll
+  for (int p = 0; p < S - 1; ++p) issue(p);
+
+  // ---- Q fragments of this wavefront's row block (B operand: lane = (row n16, dim chunk g))
+  const int row = rb * 16 + n16;
+  bf16x8 qh[KS], ql[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    qh[s] = bf16x8{};
+    ql[s] = bf16x8{};
+  }
+  if (row < nrows) {
+    const size_t qat = ((size_t)(it.tok0 + row / G) * Hq + kh * G + row % G) * HD + 8 * g;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      qh[s] = *reinterpret_cast<const bf16x8*>(a.q + qat + 32 * s);
+      ql[s] = *reinterpret_cast<const bf16x8*>(a.q_lo + qat + 32 * s);
+    }
+  }
+  const int lim = row < nrows ? it.ctx_len + it.j0 + row / G : 0x7FFFFFFF;   // last key this row may see
+  const int free_end = min(key_end, it.ctx_len + it.j0 + 1);                 // keys below need no mask
+
+  float m_run = NEG_BIG, l_run = 0.f;
+  f32x4 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  for (int iter = 0; iter < n_iter; ++iter) {
+    // Own copies of this super-tile have landed (S-2 younger groups may still be in flight), own LDS
+    // reads of the previous one are done; the barrier extends both facts to the whole block.
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((S - 2) * IPW) : "memory");
+    asm volatile("s_barrier" ::: "memory");
+    issue(iter + S - 1);
+    const int kb = it.key_begin + (iter * KP + kp) * 32;
+    if (kb >= key_end) continue;                      // wavefront-uniform
+    const unsigned char* tile = lds + (size_t)(iter % S) * STAGE_B + kp * TILE_B;
+
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const int ch = ((4 * s + g) ^ (n16 & 7)) << 4;
+      const bf16x8 ka = *reinterpret_cast<const bf16x8*>(tile + n16 * (HD * 2) + ch);
+      const bf16x8 kbf = *reinterpret_cast<const bf16x8*>(tile + PAGE_B + n16 * (HD * 2) + ch);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qh[s], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kbf, qh[s], s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, ql[s], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kbf, ql[s], s1, 0, 0, 0);
+    }
+    float sv[8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      sv[r] = s0[r] * scale_log2;
+      sv[4 + r] = s1[r] * scale_log2;
+    }
+    bool vis[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) vis[r] = true;
+    if (kb + 32 > free_end) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int tau = kb + 16 * (r >> 2) + 4 * g + (r & 3);
+        vis[r] = (tau < key_end) && (tau <= lim);
+        sv[r] = vis[r] ? sv[r] : NEG_BIG;
+      }
+    }
+    float mx = sv[0];
+#pragma unroll
+    for (int r = 1; r < 8; ++r) mx = fmaxf(mx, sv[r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = ex2(m_run - m_new);
+    m_run = m_new;
+    float p[8], psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      p[r] = vis[r] ? ex2(sv[r] - m_new) : 0.f;
+      psum += p[r];
+    }
+    l_run = l_run * alpha + psum;
+    uint4 pk, pl;
+    pk.x = pack_bf2(p[0], p[1]);
+    pk.y = pack_bf2(p[2], p[3]);
+    pk.z = pack_bf2(p[4], p[5]);
+    pk.w = pack_bf2(p[6], p[7]);
+    pl.x = pack_bf2(p[0] - bf2f(pk.x & 0xFFFF), p[1] - bf2f(pk.x >> 16));
+    pl.y = pack_bf2(p[2] - bf2f(pk.y & 0xFFFF), p[3] - bf2f(pk.y >> 16));
+    pl.z = pack_bf2(p[4] - bf2f(pk.z & 0xFFFF), p[5] - bf2f(pk.z >> 16));
+    pl.w = pack_bf2(p[6] - bf2f(pk.w & 0xFFFF), p[7] - bf2f(pk.w >> 16));
+    const bf16x8 pf = __builtin_bit_cast(bf16x8, pk);
+    const bf16x8 pfl = __builtin_bit_cast(bf16x8, pl);
+    // V slots past the key range may hold junk (0 * NaN): blank them.  Only the last tile can need it.
+    uint32_t vm[4] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+    if (kb + 32 > key_end) {
 #pragma unroll
       for (int pg = 0; pg < 2; ++pg) {
         const int t0 = kb + 16 * pg + 4 * g;
-        const uint32_t m0 = (t0 + 0 < key_end ? 0x0000FFFFu : 0u) | (t0 + 1 < key_end ? 0xFFFF0000u : 0u);
-        const uint32_t m1 = (t0 + 2 < key_end ? 0x0000FFFFu : 0u) | (t0 + 3 < key_end ? 0xFFFF0000u : 0u);
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          cur.v[db][pg].x &= m0;
-          cur.v[db][pg].y &= m1;
-        }
+        vm[2 * pg] = (t0 + 0 < key_end ? 0x0000FFFFu : 0u) | (t0 + 1 < key_end ? 0xFFFF0000u : 0u);
+        vm[2 * pg + 1] = (t0 + 2 < key_end ? 0x0000FFFFu : 0u) | (t0 + 3 < key_end ? 0xFFFF0000u : 0u);
       }
-    }
-    const bool need_mask = kb + 32 > free_end;
-
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        const bf16x8 qh = s_q[((rb * KS + s) * 2 + 0) * 64 + lane];
-        const bf16x8 ql = s_q[((rb * KS + s) * 2 + 1) * 64 + lane];
-        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[0][s], qh, s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[1][s], qh, s1, 0, 0, 0);
-        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[0][s], ql, s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[1][s], ql, s1, 0, 0, 0);
-      }
-      float sv[8];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        sv[r] = s0[r] * scale_log2;
-        sv[4 + r] = s1[r] * scale_log2;
-      }
-      bool vis[8];
-#pragma unroll
-      for (int r = 0; r < 8; ++r) vis[r] = true;
-      if (need_mask) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-          const int tau = kb + 16 * (r >> 2) + 4 * g + (r & 3);
-          vis[r] = (tau < key_end) && (tau <= lim[rb]);
-          sv[r] = vis[r] ? sv[r] : NEG_BIG;
-        }
-      }
-      float mx = sv[0];
-#pragma unroll
-      for (int r = 1; r < 8; ++r) mx = fmaxf(mx, sv[r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run[rb], mx);
-      const float alpha = ex2(m_run[rb] - m_new);
-      m_run[rb] = m_new;
-      float p[8], psum = 0.f;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        p[r] = vis[r] ? ex2(sv[r] - m_new) : 0.f;
-        psum += p[r];
-      }
-      l_run[rb] = l_run[rb] * alpha + psum;
-      uint4 pk, pl;
-      pk.x = pack_bf2(p[0], p[1]);
-      pk.y = pack_bf2(p[2], p[3]);
-      pk.z = pack_bf2(p[4], p[5]);
-      pk.w = pack_bf2(p[6], p[7]);
-      pl.x = pack_bf2(p[0] - bf2f(pk.x & 0xFFFF), p[1] - bf2f(pk.x >> 16));
-      pl.y = pack_bf2(p[2] - bf2f(pk.y & 0xFFFF), p[3] - bf2f(pk.y >> 16));
-      pl.z = pack_bf2(p[4] - bf2f(pk.z & 0xFFFF), p[5] - bf2f(pk.z >> 16));
-      pl.w = pack_bf2(p[6] - bf2f(pk.w & 0xFFFF), p[7] - bf2f(pk.w >> 16));
-      const bf16x8 pf = __builtin_bit_cast(bf16x8, pk);
-      const bf16x8 pfl = __builtin_bit_cast(bf16x8, pl);
-#pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        uint4 vv;
-        vv.x = cur.v[db][0].x; vv.y = cur.v[db][0].y;
-        vv.z = cur.v[db][1].x; vv.w = cur.v[db][1].y;
-        const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
-        f32x4 o = acc[rb][db];
-        o[0] *= alpha; o[1] *= alpha; o[2] *= alpha; o[3] *= alpha;
-        o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o, 0, 0, 0);
-        acc[rb][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pfl, o, 0, 0, 0);
-      }
-    }
-    cur = nxt;
-    kb = kb_next;
-  }
-
-  // ---- merge the four wavefronts' (m, l, O) through LDS (which held Q until now)
-  __syncthreads();
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    float l = l_run[rb];
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-    if (g == 0) {
-      s_m[wave * ROWS + rb * 16 + n16] = m_run[rb];
-      s_l[wave * ROWS + rb * 16 + n16] = l;
-    }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int row = rb * 16 + n16;
-    const float m0 = s_m[row], m1 = s_m[ROWS + row], m2 = s_m[2 * ROWS + row], m3 = s_m[3 * ROWS + row];
-    const float ms = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
-    const float f = ex2(m_run[rb] - ms);
-    if (wave == 0 && g == 0) {
-      s_ms[row] = ms;
-      s_ls[row] = s_l[row] * ex2(m0 - ms) + s_l[ROWS + row] * ex2(m1 - ms) + s_l[2 * ROWS + row] * ex2(m2 - ms) +
-                  s_l[3 * ROWS + row] * ex2(m3 - ms);
     }
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
-      f32x4 o = acc[rb][db];
-      float4 w = {o[0] * f, o[1] * f, o[2] * f, o[3] * f};
-      *reinterpret_cast<float4*>(s_o + ((size_t)wave * ROWS + row) * OSTRIDE + db * 16 + 4 * g) = w;
+      const uint2 va = *reinterpret_cast<const uint2*>(tile + 2 * PAGE_B + (db * 16 + n16) * 32 + 8 * g);
+      const uint2 vb = *reinterpret_cast<const uint2*>(tile + 3 * PAGE_B + (db * 16 + n16) * 32 + 8 * g);
+      uint4 vv;
+      vv.x = va.x & vm[0];
+      vv.y = va.y & vm[1];
+      vv.z = vb.x & vm[2];
+      vv.w = vb.y & vm[3];
+      const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
+      f32x4 o = acc[db];
+      o[0] *= alpha; o[1] *= alpha; o[2] *= alpha; o[3] *= alpha;
+      o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o, 0, 0, 0);
+      acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pfl, o, 0, 0, 0);
     }
+  }
+
+  // ---- finish: every copy has landed and every wavefront is past its last read before LDS is reused
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  asm volatile("s_barrier" ::: "memory");
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+
+  if (KP == 1) {                                      // the wavefront owns its rows outright
+    if (row < nrows) {
+      const float inv = 1.0f / l_run;
+      if (it.part < 0) {
+        const size_t at = ((size_t)(it.tok0 + row / G) * Hq + kh * G + row % G) * HD + 4 * g;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          store_pair(a.o + at + db * 16, a.o_lo + at + db * 16, acc[db][0] * inv, acc[db][1] * inv,
+                     acc[db][2] * inv, acc[db][3] * inv);
+      } else {
+        const size_t base = ((size_t)it.part * Hkv + kh) * 64 + row;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+          *reinterpret_cast<float4*>(a.part_o + base * HD + db * 16 + 4 * g) =
+              make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
+        if (g == 0) *reinterpret_cast<float2*>(a.part_ml + base * 2) = make_float2(m_run, l_run);
+      }
+    }
+    return;
+  }
+
+  // ---- merge the key phases of each row block through LDS
+  float* s_o = reinterpret_cast<float*>(lds);         // [4 wavefronts][16][OSTRIDE]
+  float* s_m = s_o + 4 * 16 * OSTRIDE;                // [4][16]
+  float* s_l = s_m + 64;                              // [4][16]
+  if (g == 0) {
+    s_m[wave * 16 + n16] = m_run;
+    s_l[wave * 16 + n16] = l_run;
+  }
+  __syncthreads();
+  {
+    float ms = NEG_BIG;
+#pragma unroll
+    for (int q = 0; q < KP; ++q) ms = fmaxf(ms, s_m[(q * RBN + rb) * 16 + n16]);
+    const float f = ex2(m_run - ms);
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      *reinterpret_cast<float4*>(s_o + ((size_t)wave * 16 + n16) * OSTRIDE + db * 16 + 4 * g) =
+          make_float4(acc[db][0] * f, acc[db][1] * f, acc[db][2] * f, acc[db][3] * f);
   }
   __syncthreads();
   for (int e = threadIdx.x; e < nrows * (HD / 4); e += 256) {
-    const int row = e / (HD / 4), d4 = (e % (HD / 4)) * 4;
-    float4 sum = {0.f, 0.f, 0.f, 0.f};
+    const int orow = e / (HD / 4), d4 = (e % (HD / 4)) * 4;
+    const int orb = orow >> 4, r16 = orow & 15;
+    float ms = NEG_BIG;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float4 v = *reinterpret_cast<const float4*>(s_o + ((size_t)w * ROWS + row) * OSTRIDE + d4);
+    for (int q = 0; q < KP; ++q) ms = fmaxf(ms, s_m[(q * RBN + orb) * 16 + r16]);
+    float4 sum = {0.f, 0.f, 0.f, 0.f};
+    float l = 0.f;
+#pragma unroll
+    for (int q = 0; q < KP; ++q) {
+      const int w = q * RBN + orb;
+      const float4 v = *reinterpret_cast<const float4*>(s_o + ((size_t)w * 16 + r16) * OSTRIDE + d4);
       sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+      l += s_l[w * 16 + r16] * ex2(s_m[w * 16 + r16] - ms);
     }
     if (it.part < 0) {
-      const float inv = 1.0f / s_ls[row];
-      const size_t at = ((size_t)(it.tok0 + row / G) * Hq + kh * G + row % G) * HD + d4;
+      const float inv = 1.0f / l;
+      const size_t at = ((size_t)(it.tok0 + orow / G) * Hq + kh * G + orow % G) * HD + d4;
       store_pair(a.o + at, a.o_lo + at, sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
     } else {
-      *reinterpret_cast<float4*>(a.part_o + (((size_t)it.part * Hkv + kh) * 64 + row) * HD + d4) = sum;
+      const size_t base = ((size_t)it.part * Hkv + kh) * 64 + orow;
+      *reinterpret_cast<float4*>(a.part_o + base * HD + d4) = sum;
+      if (d4 == 0) *reinterpret_cast<float2*>(a.part_ml + base * 2) = make_float2(ms, l);
     }
-  }
-  if (it.part >= 0 && threadIdx.x < nrows) {
-    float2 ml = {s_ms[threadIdx.x], s_ls[threadIdx.x]};
-    *reinterpret_cast<float2*>(a.part_ml + (((size_t)it.part * Hkv + kh) * 64 + threadIdx.x) * 2) = ml;
   }
 }
 
@@ -313,32 +347,36 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnLaunch a) {
   }
 }
 
-template <int HD, int RB>
-static hipError_t launch_class(const AttnLaunch& a, int cls, float scale_log2, hipStream_t s) {
-  const int n = a.class_begin[cls + 1] - a.class_begin[cls];
-  if (n <= 0) return hipSuccess;
-  constexpr int ROWS = RB * 16;
-  const size_t lds_merge = (size_t)(4 * ROWS * (HD + 4) + 8 * ROWS + 2 * ROWS) * sizeof(float);
-  const size_t lds_q = (size_t)RB * (HD / 32) * 2 * 64 * 16;
-  const size_t lds = lds_merge > lds_q ? lds_merge : lds_q;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<HD, RB>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  attn_kernel<HD, RB><<<dim3(n, a.Hkv), 256, lds, s>>>(a, a.class_begin[cls], scale_log2);
-  return hipGetLastError();
+// One launch covers every work item; the block picks the code path for its row-group size.
+template <int HD>
+__global__ __launch_bounds__(256) void attn_kernel(AttnLaunch a, float scale_log2) {
+  const AttnItem it = a.items[blockIdx.x];
+  const int rows = it.ntok * (a.Hq / a.Hkv);
+  if (rows <= 32)                       // up to two 16-row blocks x two key phases
+    attn_body<HD, 2>(a, it, scale_log2);
+  else                                  // four 16-row blocks, every wavefront sees every key
+    attn_body<HD, 4>(a, it, scale_log2);
 }
 
 template <int HD>
 static hipError_t launch_hd(const AttnLaunch& a, hipStream_t s) {
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
-  hipError_t e;
-  if ((e = launch_class<HD, 1>(a, 0, scale_log2, s)) != hipSuccess) return e;
-  if ((e = launch_class<HD, 2>(a, 1, scale_log2, s)) != hipSuccess) return e;
-  if ((e = launch_class<HD, 4>(a, 2, scale_log2, s)) != hipSuccess) return e;
+  const int n = a.class_begin[3];
+  if (n > 0) {
+    const size_t lds_ring = (size_t)4 * 4 * SY_PAGE * HD * 2 + 4 * 1024;   // 4 tiles of 32 keys + dump kilobytes
+    const size_t lds_merge = (size_t)(4 * 16 * (HD + 4) + 128) * sizeof(float);
+    const size_t lds = lds_ring > lds_merge ? lds_ring : lds_merge;
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_kernel<HD>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    attn_kernel<HD><<<dim3(n, a.Hkv), 256, lds, s>>>(a, scale_log2);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   if (a.any_split) {
     attn_combine_kernel<<<a.T, 256, 0, s>>>(a);
     return hipGetLastError();
