@@ -4,6 +4,7 @@
 // No arithmetic of the method happens on the host.
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -13,7 +14,8 @@
 
 #define SY_VERSION 100
 #define N_STAGE 4              // metadata staging slots (calls may run this far ahead of the GPU)
-#define ATTN_TARGET_BLOCKS 768
+#define ATTN_TARGET_BLOCKS 768   // default number of attention blocks a verify aims for (splits long contexts)
+#define ATTN_TARGET_BLOCKS_MAX 8192
 
 #define HIP_TRY(expr)                       \
   do {                                      \
@@ -79,7 +81,7 @@ struct synera_ctx {
   const void* embed;
   const void* final_norm;
   const void* lm_head;
-  int32_t max_batch, max_tokens, max_pages, max_rows, items_cap, rows_per_group_tokens;
+  int32_t max_batch, max_tokens, max_pages, max_rows, items_cap, rows_per_group_tokens, attn_target_blocks;
   int device;
   // device scratch (one allocation)
   char* arena;
@@ -176,7 +178,13 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   const int G = m.n_q_heads / m.n_kv_heads;
   c->rows_per_group_tokens = std::max(1, 64 / G);
   const int rg_max = (SYNERA_MAX_CHUNK + c->rows_per_group_tokens - 1) / c->rows_per_group_tokens;
-  c->items_cap = ATTN_TARGET_BLOCKS + max_batch * rg_max;
+  c->attn_target_blocks = ATTN_TARGET_BLOCKS;
+  if (const char* env = getenv("SYNERA_ATTN_TARGET_BLOCKS")) {   // tuning knob
+    const long v = strtol(env, nullptr, 10);
+    if (v >= 64 && v <= ATTN_TARGET_BLOCKS_MAX) c->attn_target_blocks = (int32_t)v;
+  }
+  // key ranges are at most 1024 keys long: a request contributes <= rg_max * (keys / 1024 + 2) items
+  c->items_cap = c->attn_target_blocks + max_batch * rg_max * (max_pages * SYNERA_PAGE_SIZE / 1024 + 2);
 
   const size_t T = (size_t)max_tokens, R = (size_t)c->max_rows;
   const size_t qkv_dim = (size_t)(qd + 2 * kd);
@@ -332,8 +340,9 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
       const int qn = n_unc[i] + n_draft[i];
       for (int j0 = 0; j0 < qn; j0 += tg) key_work += (int64_t)ctx_len[i] + std::min(qn, j0 + tg);
     }
-    int64_t chunk = (key_work * c->desc.n_kv_heads + ATTN_TARGET_BLOCKS - 1) / ATTN_TARGET_BLOCKS;
+    int64_t chunk = (key_work * c->desc.n_kv_heads + c->attn_target_blocks - 1) / c->attn_target_blocks;
     chunk = std::max<int64_t>(256, (chunk + 127) / 128 * 128);
+    chunk = std::min<int64_t>(chunk, 1024);        // the attention kernel keeps a range's page ids in 64 lanes
     std::vector<AttnItem> items[3];
     AttnCombine* comb = reinterpret_cast<AttnCombine*>(h + o_comb);
     int32_t n_part = 0;
@@ -458,7 +467,7 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   const int T = p.T, d = m.d_model, Hq = m.n_q_heads, Hkv = m.n_kv_heads, hd = m.head_dim;
   const int qd = Hq * hd, kd = Hkv * hd;
   const size_t layer_elems = (size_t)n_pages_in_pool * Hkv * SY_PAGE * hd;
-  HIP_TRY(launch_embed(static_cast<const bf16_t*>(c->embed), d_tokens, c->x, T, d, s));
+  HIP_TRY(launch_embed(static_cast<const bf16_t*>(c->embed), d_tokens, c->x, T, d, m.vocab, s));
   HIP_TRY(launch_rope_table(p.meta, c->cs, T, hd, m.rope_base, s));
 
   AttnLaunch al;

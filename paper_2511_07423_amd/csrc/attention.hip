@@ -32,6 +32,21 @@
 
 __device__ __forceinline__ float ex2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Reductions over the four lanes l, l^16, l^32, l^48 that hold one query row, with gfx950's lane-swap
+// instructions (plain vector ALU work, no trip through the LDS crossbar).
+__device__ __forceinline__ float row_max4(float v) {
+  auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float row_sum4(float v) {
+  auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 // Four consecutive outputs as a bf16 (hi, lo) pair: 8 bytes to each array.
 __device__ __forceinline__ void store_pair(bf16_t* hi, bf16_t* lo, float a, float b, float c, float d) {
   uint2 h, l;
@@ -102,24 +117,22 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
   const int n_iter = (n_keys + 32 * KP - 1) / (32 * KP);
   // Copies of super-tile `iter` into stage iter % S.  Past the last super-tile the same number of
   // copies is still issued (the wait counts below stay constant), into a per-wavefront dump kilobyte.
-  // All copies of one wavefront belong to one 32-key tile of the super-tile (c_tile[0]); its two
-  // page ids come from the block table through the scalar unit (explicitly: after an asm memory
-  // clobber the compiler would fetch them with vector loads and wait for every copy in flight).
+  // A key range spans at most 64 pages (the host cuts ranges at <= 1024 keys): lane l keeps the id of
+  // the range's page l, and a copy group reads its two page ids with v_readlane.
+  const int first_page = it.key_begin >> 4;
+  const int n_pages_rng = last_page - first_page + 1;
+  const int my_page = bt[first_page + (lane < n_pages_rng ? lane : n_pages_rng - 1)];
+  // All copies of one wavefront belong to one 32-key tile of the super-tile (c_tile[0]).
   auto issue = [&](int iter) {
     const bool real = iter < n_iter;
     const int it_ = real ? iter : n_iter - 1;
     const uint32_t stage = lds_base + (uint32_t)(it_ % S) * STAGE_B;
     const uint32_t dump = lds_base + S * STAGE_B + wave * 1024;
-    int i0 = (it.key_begin + (it_ * KP + c_tile[0]) * 32) >> 4;
-    i0 = i0 < last_page ? i0 : last_page;            // past the range: a valid page, masked later
-    const int i1 = i0 + 1 < last_page ? i0 + 1 : last_page;
-    const int32_t* p0 = bt + __builtin_amdgcn_readfirstlane(i0);
-    const int32_t* p1 = bt + __builtin_amdgcn_readfirstlane(i1);
-    int page_a, page_b;
-    asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&s"(page_a), "=&s"(page_b)
-                 : "s"(p0), "s"(p1)
-                 : "memory");
+    int i0 = ((it_ * KP + c_tile[0]) * 32) >> 4;     // page index relative to the range's first page
+    i0 = i0 < n_pages_rng - 1 ? i0 : n_pages_rng - 1;   // past the range: a valid page, masked later
+    const int i1 = i0 + 1 < n_pages_rng - 1 ? i0 + 1 : n_pages_rng - 1;
+    const int page_a = __builtin_amdgcn_readlane(my_page, i0);
+    const int page_b = __builtin_amdgcn_readlane(my_page, i1);
 #pragma unroll
     for (int j = 0; j < IPW; ++j) {
       const int page = (c_pg[j] & 1) ? page_b : page_a;
@@ -195,8 +208,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
     float mx = sv[0];
 #pragma unroll
     for (int r = 1; r < 8; ++r) mx = fmaxf(mx, sv[r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = row_max4(mx);
     const float m_new = fmaxf(m_run, mx);
     const float alpha = ex2(m_run - m_new);
     m_run = m_new;
@@ -218,38 +230,56 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
     pl.w = pack_bf2(p[6] - bf2f(pk.w & 0xFFFF), p[7] - bf2f(pk.w >> 16));
     const bf16x8 pf = __builtin_bit_cast(bf16x8, pk);
     const bf16x8 pfl = __builtin_bit_cast(bf16x8, pl);
-    // V slots past the key range may hold junk (0 * NaN): blank them.  Only the last tile can need it.
-    uint32_t vm[4] = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+    // Rescale the accumulators only when some row's running max moved (rare after the first tiles).
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        acc[db][0] *= alpha; acc[db][1] *= alpha; acc[db][2] *= alpha; acc[db][3] *= alpha;
+      }
+    }
     if (kb + 32 > key_end) {
+      // Last tile of the range: V slots past it may hold junk (0 * NaN), blank them.
+      uint32_t vm[4];
 #pragma unroll
       for (int pg = 0; pg < 2; ++pg) {
         const int t0 = kb + 16 * pg + 4 * g;
         vm[2 * pg] = (t0 + 0 < key_end ? 0x0000FFFFu : 0u) | (t0 + 1 < key_end ? 0xFFFF0000u : 0u);
         vm[2 * pg + 1] = (t0 + 2 < key_end ? 0x0000FFFFu : 0u) | (t0 + 3 < key_end ? 0xFFFF0000u : 0u);
       }
-    }
 #pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      const uint2 va = *reinterpret_cast<const uint2*>(tile + 2 * PAGE_B + (db * 16 + n16) * 32 + 8 * g);
-      const uint2 vb = *reinterpret_cast<const uint2*>(tile + 3 * PAGE_B + (db * 16 + n16) * 32 + 8 * g);
-      uint4 vv;
-      vv.x = va.x & vm[0];
-      vv.y = va.y & vm[1];
-      vv.z = vb.x & vm[2];
-      vv.w = vb.y & vm[3];
-      const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
-      f32x4 o = acc[db];
-      o[0] *= alpha; o[1] *= alpha; o[2] *= alpha; o[3] *= alpha;
-      o = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, o, 0, 0, 0);
-      acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pfl, o, 0, 0, 0);
+      for (int db = 0; db < DB; ++db) {
+        const uint2 va = *reinterpret_cast<const uint2*>(tile + 2 * PAGE_B + (db * 16 + n16) * 32 + 8 * g);
+        const uint2 vb = *reinterpret_cast<const uint2*>(tile + 3 * PAGE_B + (db * 16 + n16) * 32 + 8 * g);
+        uint4 vv;
+        vv.x = va.x & vm[0];
+        vv.y = va.y & vm[1];
+        vv.z = vb.x & vm[2];
+        vv.w = vb.y & vm[3];
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
+        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, acc[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pfl, acc[db], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const uint2 va = *reinterpret_cast<const uint2*>(tile + 2 * PAGE_B + (db * 16 + n16) * 32 + 8 * g);
+        const uint2 vb = *reinterpret_cast<const uint2*>(tile + 3 * PAGE_B + (db * 16 + n16) * 32 + 8 * g);
+        uint4 vv;
+        vv.x = va.x;
+        vv.y = va.y;
+        vv.z = vb.x;
+        vv.w = vb.y;
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
+        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf, acc[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pfl, acc[db], 0, 0, 0);
+      }
     }
   }
 
   // ---- finish: every copy has landed and every wavefront is past its last read before LDS is reused
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   asm volatile("s_barrier" ::: "memory");
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
+  l_run = row_sum4(l_run);
 
   if (KP == 1) {                                      // the wavefront owns its rows outright
     if (row < nrows) {

@@ -14,13 +14,15 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 // Activations travel between kernels as a bf16 pair (hi, lo): hi = bf16(v), lo = bf16(v - hi), which keeps
 // about 16 mantissa bits while every matrix-core operand stays bf16.
-// Round-to-nearest-even fp32 -> bf16 bits (finite inputs).
-__device__ __forceinline__ uint32_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+// fp32 -> bf16, round-to-nearest-even, two at a time with gfx950's v_cvt_pk_bf16_f32.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
+__device__ __forceinline__ uint32_t f2bf(float f) { return pack_bf2(f, 0.f) & 0xFFFFu; }
 __device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
-__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) { return f2bf(lo) | (f2bf(hi) << 16); }
 
 // ---------------------------------------------------------------- elementwise.hip
 struct BatchMeta {        // device pointers into one uploaded metadata blob (all int32)
@@ -35,7 +37,8 @@ struct BatchMeta {        // device pointers into one uploaded metadata blob (al
   int32_t max_pages;
 };
 
-hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, int T, int d, hipStream_t s);
+hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, int T, int d, int vocab,
+                        hipStream_t s);
 hipError_t launch_rmsnorm(const float* x, const bf16_t* gain, const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo,
                           int n_rows, int d, float eps, hipStream_t s);
 hipError_t launch_rope_table(const BatchMeta& m, float2* cs, int T, int head_dim, float base, hipStream_t s);

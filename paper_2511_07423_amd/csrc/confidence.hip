@@ -66,7 +66,9 @@ __global__ __launch_bounds__(256) void confidence_kernel(const void* __restrict_
   const char* base = reinterpret_cast<const char*>(logits) + row * stride * (BF16 ? 2 : 4);
   const uint4* src = reinterpret_cast<const uint4*>(base);
   const int n_vec = (int)(vocab / VEC);
-  ConfState st = {-1e30f, 0.f, 0.f, 0x7FFFFFFF};
+  // id starts at 0: a row without any finite entry (all NaN) then reports token 0, never an id
+  // outside the vocabulary.
+  ConfState st = {-1e30f, 0.f, 0.f, 0};
 
   auto consume = [&](const uint4& raw, int c) {
     float v[VEC];

@@ -5,12 +5,16 @@
 #include "common.h"
 
 // ------------------------------------------------------------------ embedding
-// x[t][:] = float(E[token[t]][:]).  One block per token.
+// x[t][:] = float(E[token[t]][:]).  One block per token.  Token ids live on the device and cannot
+// be validated by the host: an id outside [0, vocab) is clamped into the table instead of being
+// followed out of bounds.
 __global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ embed,
                                                     const int32_t* __restrict__ tokens,
-                                                    float* __restrict__ x, int d) {
+                                                    float* __restrict__ x, int d, int vocab) {
   const int t = blockIdx.x;
-  const bf16_t* src = embed + (size_t)tokens[t] * d;
+  int tok = tokens[t];
+  tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
+  const bf16_t* src = embed + (size_t)tok * d;
   float* dst = x + (size_t)t * d;
   for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
     uint4 v = *reinterpret_cast<const uint4*>(src + c);
@@ -21,9 +25,10 @@ __global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ e
   }
 }
 
-hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, int T, int d, hipStream_t s) {
+hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, int T, int d, int vocab,
+                        hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  embed_kernel<<<T, 256, 0, s>>>(embed, tokens, x, d);
+  embed_kernel<<<T, 256, 0, s>>>(embed, tokens, x, d, vocab);
   return hipGetLastError();
 }
 
