@@ -102,14 +102,16 @@ def gpu_chain(case, reqs, anchors):
     return {i: np.asarray(d, np.int32) for i, d in drafts.items()}
 
 
-def draw_weights(shape, seed, device, oracle_dtype=None):
+def draw_weights(shape, seed, device, oracle_dtype=None, lazy_oracle=False):
     """Weights on the device plus the oracle's widened host copy of the same bytes.  Tests of several
-    configs with one model shape may share the result."""
+    configs with one model shape may share the result.  lazy_oracle: the oracle widens one layer at a
+    time from the device copy (for models whose fp32 copy does not fit in host memory)."""
     if oracle_dtype is None:
         oracle_dtype = np.float64 if shape.d_model <= 512 else np.float32
     head = wl.draw_head_weights(shape, seed, device)
     layers = [wl.draw_layer_weights(shape, seed, l, device) for l in range(shape.n_layers)]
-    return {"head": head, "layers": layers, "model": oracle_model(shape, head, layers, oracle_dtype)}
+    src = (lambda l: layers[l]) if lazy_oracle else layers
+    return {"head": head, "layers": layers, "model": oracle_model(shape, head, src, oracle_dtype)}
 
 
 def build_case(recipe, device="cuda:0", n_oracle=None, batch_size=None, oracle_dtype=None, verbose=False,

@@ -65,6 +65,17 @@ def test_confidence_workload_recipe_strided_and_ties():
     assert ids.numel() == 0
 
 
+def test_rows_without_finite_entries_report_token_zero():
+    """A row of NaN logits must not produce an id outside the vocabulary (it would be followed as a
+    token id by a caller that feeds corrections back in)."""
+    synera = _synera()
+    t = torch.full((3, 4096), float("nan"), device=DEV)
+    t[1] = torch.randn(4096, device=DEV)
+    ids, _, _ = synera.confidence(t)
+    ids = ids.cpu().tolist()
+    assert ids[0] == 0 and ids[2] == 0 and 0 <= ids[1] < 4096
+
+
 def test_confidence_rejects_bad_arguments():
     synera = _synera()
     x = torch.zeros((4, 1001), device=DEV, dtype=torch.bfloat16)   # row stride not 16-byte aligned

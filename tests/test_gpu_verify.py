@@ -146,3 +146,23 @@ def test_chunked_verify_equals_sequential_decodes_on_gpu():
             rows[i].append(lg[n])
     seq = np.concatenate([np.stack(r) for r in rows])
     assert np.abs(seq - chunk["logits"]).max() < 2e-3
+
+
+def test_out_of_range_token_ids_are_clamped_not_followed():
+    """Token ids live in device memory, the host cannot validate them: ids outside [0, vocab) are
+    clamped into the embedding table (regression test: such an id used to index out of bounds)."""
+    case = gh.build_case(wl.config(1), DEV)
+    b, V = case.batch, case.shape.vocab
+    drafts = [d.copy() for d in case.drafts]
+    drafts[0][0], drafts[1][1], drafts[2][2] = -7, V, 2 ** 31 - 1
+    clamped = [np.clip(d, 0, V - 1) for d in drafts]
+    outs = []
+    for ds in (drafts, clamped):
+        toks = torch.from_numpy(np.concatenate(ds).astype(np.int32)).to(DEV)
+        o = case.verifier.verify(b["ctx_len"], case.n_uncached, b["n_draft"], toks,
+                                 torch.from_numpy(case.anchor.astype(np.int32)).to(DEV), b["block_table"],
+                                 b["n_pages"], case.k_pool, case.v_pool)
+        torch.cuda.synchronize()
+        outs.append(o["logits"].cpu().numpy())
+    assert np.isfinite(outs[0]).all()
+    assert np.allclose(outs[0], outs[1], rtol=0, atol=1e-5)
