@@ -244,6 +244,14 @@ int32_t synera_gemm_bf16(const void* d_a, const void* d_a_lo, const void* d_w, f
  */
 int32_t synera_debug_set_gemm_tile(int32_t variant);
 
+/*
+ * Test hook: copy one of the context's intermediate buffers, as the LAST layer of the last
+ * verify left it, to caller device memory.  which: 0 residual x (f32 [T][d]), 1/2 rotated q
+ * hi/lo (bf16 [T][Hq*h]), 3/4 attention output hi/lo (bf16 [T][Hq*h]), 5/6 SiLU*mul output
+ * hi/lo (bf16 [T][f]).  Errors: EINVAL, ENOSPC (bytes beyond the buffer), EHIP.
+ */
+int32_t synera_debug_read_scratch(synera_ctx* ctx, int32_t which, void* d_dst, int64_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

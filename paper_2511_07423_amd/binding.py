@@ -71,6 +71,8 @@ _lib.synera_profile_end.restype = C.c_int32
 _lib.synera_profile_end.argtypes = [_vp, C.POINTER(C.c_int32), C.POINTER(C.c_float)]
 _lib.synera_gemm_bf16.restype = C.c_int32
 _lib.synera_gemm_bf16.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
+_lib.synera_debug_read_scratch.restype = C.c_int32
+_lib.synera_debug_read_scratch.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp]
 _lib.synera_debug_set_gemm_tile.restype = C.c_int32
 _lib.synera_debug_set_gemm_tile.argtypes = [C.c_int32]
 
@@ -223,6 +225,12 @@ class Verifier:
             _dev(out["top1_prob"]), _dev(out["entropy"]), _dev(out["accept_len"]), _dev(out["correction"]),
             _stream())
         _check(st, "synera_verify")
+
+    def debug_read_scratch(self, which, out):
+        """Test hook: copy an intermediate buffer of the last layer of the last verify into `out`."""
+        _check(_lib.synera_debug_read_scratch(self._ctx, which, out.data_ptr(), out.numel() * out.element_size(),
+                                              _stream()), "synera_debug_read_scratch")
+        return out
 
     def profile_begin(self, stage):
         """Bracket every launch of `stage` (a STAGES value) in later verifies with HIP events."""

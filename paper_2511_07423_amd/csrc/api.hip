@@ -628,6 +628,27 @@ extern "C" int32_t synera_kv_append(synera_ctx* c, int32_t layer, int32_t B, con
 }
 
 // ------------------------------------------------------------------------------------ plain GEMM
+extern "C" int32_t synera_debug_read_scratch(synera_ctx* c, int32_t which, void* d_dst, int64_t bytes, void* stream) {
+  if (!c || !d_dst || bytes < 0) return SYNERA_EINVAL;
+  const synera_model_desc& m = c->desc;
+  const int64_t T = c->max_tokens, qd = (int64_t)m.n_q_heads * m.head_dim;
+  const void* src = nullptr;
+  int64_t cap = 0;
+  switch (which) {
+    case 0: src = c->x; cap = T * m.d_model * 4; break;
+    case 1: src = c->q; cap = T * qd * 2; break;
+    case 2: src = c->q_lo; cap = T * qd * 2; break;
+    case 3: src = c->o; cap = T * qd * 2; break;
+    case 4: src = c->o_lo; cap = T * qd * 2; break;
+    case 5: src = c->act; cap = T * (int64_t)m.d_ffn * 2; break;
+    case 6: src = c->act_lo; cap = T * (int64_t)m.d_ffn * 2; break;
+    default: return SYNERA_EINVAL;
+  }
+  if (bytes > cap) return SYNERA_ENOSPC;
+  HIP_TRY(hipMemcpyAsync(d_dst, src, (size_t)bytes, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
+  return SYNERA_OK;
+}
+
 extern "C" int32_t synera_debug_set_gemm_tile(int32_t variant) {
   gemm_force_variant(variant);
   return SYNERA_OK;
