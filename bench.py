@@ -126,6 +126,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-stage times to stderr")
     ap.add_argument("--stage", default="gate_up", help="kernel stage the roofline object reports")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run one plain 1 GiB device copy (a known-size dispatch to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (requests are independent, so N GPUs would each verify a "
@@ -137,6 +140,12 @@ def main():
     import paper_2511_07423_amd as synera
     assert torch.cuda.is_available(), "bench.py needs the GPU; there is no CPU path"
     device = "cuda:0"
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=device)     # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     w = build_workload(args.config, device)
     b, ver, shape = w["batch"], w["ver"], w["shape"]
     B = len(b["ctx_len"])

@@ -245,6 +245,18 @@ int32_t synera_gemm_bf16(const void* d_a, const void* d_a_lo, const void* d_w, f
 int32_t synera_debug_set_gemm_tile(int32_t variant);
 
 /*
+ * Test hook: one launch of the projection GEMM with the epilogue the decoder layers use
+ * (Section 3.4's partial prefill runs these three forms per layer).  Activations are the
+ * bf16 pair d_a + d_a_lo ([M][K] each).  epilogue 0: d_c f32 [M][N] = A W0^T; 1: d_c += A W0^T
+ * (the residual add of the O and down projections); 2: SwiGLU, d_w0 = gate and d_w1 = up
+ * ([N/2][K] each), d_c / d_c_lo = bf16 pair [M][N/2] of silu(A gate^T) * (A up^T).
+ * N % 128 == 0 (256 for epilogue 2), K % 64 == 0, else EUNSUP.  All pointers device.
+ */
+int32_t synera_debug_gemm_epilogue(const void* d_a, const void* d_a_lo, const void* d_w0, const void* d_w1,
+                                   void* d_c, void* d_c_lo, int32_t M, int32_t N, int32_t K, int32_t epilogue,
+                                   void* stream);
+
+/*
  * Test hook: copy one of the context's intermediate buffers, as the LAST layer of the last
  * verify left it, to caller device memory.  which: 0 residual x (f32 [T][d]), 1/2 rotated q
  * hi/lo (bf16 [T][Hq*h]), 3/4 attention output hi/lo (bf16 [T][Hq*h]), 5/6 SiLU*mul output

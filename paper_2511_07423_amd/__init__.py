@@ -5,7 +5,18 @@ runs in the HIP kernels of libsynera.so; this package only marshals arguments
 (PyTorch supplies device memory and the stream).  There is no CPU fallback:
 importing the binding without the built library raises.
 """
-from .binding import (  # noqa: F401
-    SyneraError, Verifier, confidence, gemm_bf16, debug_set_gemm_tile, validate_batch, version, lib_path,
-    OK, EINVAL, ERANGE, ENOSPC, EUNSUP, EHIP, ENOMEM, PAGE_SIZE, MAX_CHUNK, STAGES,
+_EXPORTS = (
+    "SyneraError", "Verifier", "confidence", "gemm_bf16", "debug_set_gemm_tile", "debug_gemm_epilogue",
+    "validate_batch", "version", "lib_path",
+    "OK", "EINVAL", "ERANGE", "ENOSPC", "EUNSUP", "EHIP", "ENOMEM", "PAGE_SIZE", "MAX_CHUNK", "STAGES",
 )
+__all__ = list(_EXPORTS)
+
+
+def __getattr__(name):
+    # The binding loads libsynera.so; it is imported on first use so that `paper_2511_07423_amd.build`
+    # (which compiles that library) can be imported before the library exists or while it is stale.
+    if name in _EXPORTS:
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError(f"module {__name__!r} has no attribute {name!r}")

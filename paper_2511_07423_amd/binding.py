@@ -75,6 +75,8 @@ _lib.synera_debug_read_scratch.restype = C.c_int32
 _lib.synera_debug_read_scratch.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp]
 _lib.synera_debug_set_gemm_tile.restype = C.c_int32
 _lib.synera_debug_set_gemm_tile.argtypes = [C.c_int32]
+_lib.synera_debug_gemm_epilogue.restype = C.c_int32
+_lib.synera_debug_gemm_epilogue.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp]
 
 
 class SyneraError(RuntimeError):
@@ -152,6 +154,16 @@ def gemm_bf16(a, w, a_lo=None, out=None):
                                c.data_ptr(), M, N, K, _stream())
     _check(st, "synera_gemm_bf16")
     return c
+
+
+def debug_gemm_epilogue(a, a_lo, w0, w1, c, c_lo, epilogue):
+    """Test hook: one projection GEMM with epilogue 0 (store), 1 (add into c) or 2 (SwiGLU into the bf16 pair c, c_lo)."""
+    M, K = a.shape
+    N = w0.shape[0] * (2 if epilogue == 2 else 1)
+    st = _lib.synera_debug_gemm_epilogue(_dev(a, torch.bfloat16), _dev(a_lo, torch.bfloat16), _dev(w0, torch.bfloat16),
+                                         _dev(w1, torch.bfloat16), c.data_ptr(), c_lo.data_ptr() if c_lo is not None else None,
+                                         M, N, K, epilogue, _stream())
+    _check(st, "synera_debug_gemm_epilogue")
 
 
 def debug_set_gemm_tile(variant):

@@ -654,6 +654,18 @@ extern "C" int32_t synera_debug_set_gemm_tile(int32_t variant) {
   return SYNERA_OK;
 }
 
+extern "C" int32_t synera_debug_gemm_epilogue(const void* d_a, const void* d_a_lo, const void* d_w0, const void* d_w1,
+                                              void* d_c, void* d_c_lo, int32_t M, int32_t N, int32_t K,
+                                              int32_t epilogue, void* stream) {
+  if (!d_a || !d_a_lo || !d_w0 || !d_c || M < 1 || N < 1 || K < 1 || epilogue < 0 || epilogue > 2) return SYNERA_EINVAL;
+  if (epilogue == GEMM_SWIGLU_BF16 && (!d_w1 || !d_c_lo)) return SYNERA_EINVAL;
+  if (N % (epilogue == GEMM_SWIGLU_BF16 ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
+  const bool glu = epilogue == GEMM_SWIGLU_BF16;
+  return run_gemm(static_cast<const bf16_t*>(d_a), static_cast<const bf16_t*>(d_a_lo), d_w0, glu ? N / 2 : N,
+                  glu ? d_w1 : nullptr, glu ? N / 2 : 0, nullptr, 0, d_c, d_c_lo, M, N, K, epilogue,
+                  static_cast<hipStream_t>(stream));
+}
+
 extern "C" int32_t synera_gemm_bf16(const void* d_a, const void* d_a_lo, const void* d_w, float* d_c, int32_t M,
                                     int32_t N, int32_t K, void* stream) {
   if (!d_a || !d_w || !d_c || M < 1 || N < 1 || K < 1) return SYNERA_EINVAL;

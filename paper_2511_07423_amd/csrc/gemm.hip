@@ -26,10 +26,22 @@
 // adds the partial sums with hardware fp32 atomics (the order of those adds is not fixed).
 #include "common.h"
 
+// LDS tiles hold K-major rows of CPR 16-byte chunks; chunk c of row r sits at position c ^ swz_mask(r).
+// A 16-byte fragment read (lane = row l % 32, chunk from l / 32) is served 16 lanes per cycle over the 64
+// banks, lanes l and l + 16 in the same cycle: the mask therefore varies with the row's low bits (rows
+// 128 bytes or less apart would share banks) AND with bit 4 of the row (rows r and r + 16 would collide
+// otherwise -- measured: every second LDS cycle of the fragment reads was a bank conflict without it).
+// Which k a lane feeds to an MFMA is free as long as both operands agree: in sub-step ks of a BK-wide
+// tile the lower 32 lanes take chunk ks and the upper 32 lanes chunk BK/16 + ks, which keeps the two
+// halves of the wavefront on different banks under that mask as well.
+template <int CPR>
+__device__ __forceinline__ int swz_mask(int row) {
+  return ((row / (8 / CPR)) % CPR) ^ ((row >> 4) & 1);
+}
 template <int CPR>
 __device__ __forceinline__ int swz(int row, int chunk) {
   // element offset of 16-byte chunk `chunk` of `row` in a tile with CPR chunks per row
-  return (row * CPR + (chunk ^ ((row / (8 / CPR)) % CPR))) * 8;
+  return (row * CPR + (chunk ^ swz_mask<CPR>(row))) * 8;
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool SPLIT, int EPI>
@@ -135,14 +147,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
     _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                        \
       bf16x8 fb[NJ];                                                                                \
       _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                                \
-          fb[j] = *reinterpret_cast<const bf16x8*>(sB + swz<CPR>(wn * WN + j * 32 + l32, ks * 2 + kb)); \
+          fb[j] = *reinterpret_cast<const bf16x8*>(sB + swz<CPR>(wn * WN + j * 32 + l32, kb * (BK / 16) + ks)); \
       _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                              \
         const int ar = wm * WM + i * 32 + l32;                                                      \
-        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(sA + swz<CPR>(ar, ks * 2 + kb));         \
+        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(sA + swz<CPR>(ar, kb * (BK / 16) + ks));         \
         _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                              \
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[i][j], 0, 0, 0);     \
         if (SPLIT) {                                                                                \
-          const bf16x8 fl = *reinterpret_cast<const bf16x8*>(sA + A_ELEMS + swz<CPR>(ar, ks * 2 + kb)); \
+          const bf16x8 fl = *reinterpret_cast<const bf16x8*>(sA + A_ELEMS + swz<CPR>(ar, kb * (BK / 16) + ks)); \
           _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                            \
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fl, fb[j], acc[i][j], 0, 0, 0);   \
         }                                                                                           \
@@ -239,9 +251,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(GemmArgs g) {
 __device__ __forceinline__ void glds16(const void* gptr, const void* lds_ptr) {
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane(
       (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds_ptr);
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
 #define SY_GLDS16(gptr, lptr) glds16((gptr), (lptr))
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+__device__ __forceinline__ void glds16_at(const void* gptr, uint32_t lds_addr) {   // lds_addr: wavefront-uniform
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
 
 template <int BM, int BN, int BK, int WGM, int WGN, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
@@ -273,7 +291,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
 #pragma unroll
   for (int j = 0; j < IPW; ++j) {
     const int r = (wave * IPW + j) * RPI + lane / CPR;
-    const int ch = (lane % CPR) ^ ((r / (8 / CPR)) % CPR);
+    const int ch = (lane % CPR) ^ swz_mask<CPR>(r);
     const bf16_t* base;
     if (r < 2 * BM) {
       int am = m0 + (r < BM ? r : r - BM);
@@ -320,11 +338,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
     _Pragma("unroll") for (int ks = 0; ks < BK / 16; ++ks) {                                      \
       bf16x8 fb[NJ];                                                                              \
       _Pragma("unroll") for (int j = 0; j < NJ; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(    \
-          STAGE + 2 * BM * BK + swz<CPR>(wn * WN + j * 32 + l32, ks * 2 + kb));                   \
+          STAGE + 2 * BM * BK + swz<CPR>(wn * WN + j * 32 + l32, kb * (BK / 16) + ks));                   \
       _Pragma("unroll") for (int i = 0; i < MI; ++i) {                                            \
         const int ar = wm * WM + i * 32 + l32;                                                    \
-        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(STAGE + swz<CPR>(ar, ks * 2 + kb));    \
-        const bf16x8 fl = *reinterpret_cast<const bf16x8*>(STAGE + BM * BK + swz<CPR>(ar, ks * 2 + kb)); \
+        const bf16x8 fa = *reinterpret_cast<const bf16x8*>(STAGE + swz<CPR>(ar, kb * (BK / 16) + ks));    \
+        const bf16x8 fl = *reinterpret_cast<const bf16x8*>(STAGE + BM * BK + swz<CPR>(ar, kb * (BK / 16) + ks)); \
         _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                            \
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[j], acc[i][j], 0, 0, 0);   \
         _Pragma("unroll") for (int j = 0; j < NJ; ++j)                                            \
@@ -363,6 +381,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
 #undef SY_ISSUE
 #undef SY_MULT
 #undef SY_STEP
+  // the surplus copies of the last steps are still in flight: let them land before the block's LDS is released
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
@@ -413,6 +433,216 @@ static hipError_t launch_dma(const GemmArgs& g, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Tall-tile variant for verification batches (a few hundred rows): the block tile spans BM = 32 MB
+// rows -- half of M, or all of it -- by 256 columns, so a weight tile is pulled from L2 at most
+// twice and the operand bytes moved L2 -> LDS per multiply drop by about 2.5x against the 64-row
+// tile (that traffic, not the matrix cores, bounds the smaller tiles).  Four wavefronts, one per
+// SIMD, each own all BM rows of 64 columns: 2 MB accumulator fragments of v_mfma_f32_32x32x16_bf16
+// (a single wavefront keeps the matrix core busy with this 8-pass instruction; with the 4-pass 16x16x32
+// one it reaches about half the rate).  Per K step of 32 a wavefront reads its 4 weight fragments once
+// and streams the 4 MB activation fragments (hi, lo) through them.  LDS: three stages of
+// (2 BM + 256) rows x 64 B, filled by the same asynchronous copies as above; one block per CU.
+// K may be split unevenly over blockIdx.z (in units of BK) so that tiles x splits fills the chip.
+//
+// The MFMAs are issued from inline assembly with the accumulator tied to the destination: left to the
+// compiler, accumulators migrate between registers from one K step to the next (dozens of copies per
+// step, and spills once they need more than the 256 AGPRs).  Row blocks 0..7 accumulate in AGPRs, a
+// ninth in VGPRs.  The copies of K step s+2 are spread over the row blocks of step s: issued together
+// right after the barrier, the four wavefronts queue ~50 copy instructions on the CU's one address
+// unit and none of them reaches its first MFMA for several hundred cycles.
+template <int MB, int EPI>
+__global__ __launch_bounds__(256) void gemm_tall_kernel(GemmArgs g) {
+  constexpr int BM = 32 * MB, BN = 256, BK = 32, CPR = 4;
+  constexpr int A_INS = 4 * MB;                  // copy instructions (16 tile rows each) for [A_hi | A_lo]
+  constexpr int A_IPW = MB;                      // per wavefront
+  constexpr int W_IPW = BN / 16 / 4;
+  constexpr int IPW = A_IPW + W_IPW;
+  constexpr int R = 2 * BM + BN;
+  static_assert(MB >= 1 && MB <= 9, "accumulators: 32 MB registers per lane, stages: 3 (2 BM + 256) x 64 B of LDS");
+  __shared__ __attribute__((aligned(16))) bf16_t st0[R * BK];
+  __shared__ __attribute__((aligned(16))) bf16_t st1[R * BK];
+  __shared__ __attribute__((aligned(16))) bf16_t st2[R * BK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / BN;
+  const int xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
+  const int n_tile = (within / m_tiles) * 8 + xcd;
+  if (n_tile >= n_tiles) return;
+  const int m0 = (within % m_tiles) * BM, n0 = n_tile * BN;
+  const int K = g.K, M = g.M;
+  const int total_steps = K / BK;
+  const int step_begin = (int)((long)blockIdx.z * total_steps / g.split_k);
+  const int n_steps = (int)((long)(blockIdx.z + 1) * total_steps / g.split_k) - step_begin;
+  if (n_steps <= 0) return;
+
+  const bf16_t* src[IPW];
+  uint32_t dst[IPW];                             // byte offset of the copy's 16 rows inside a stage
+#pragma unroll
+  for (int j = 0; j < IPW; ++j) {
+    const int grp = j < A_IPW ? wave + 4 * j : A_INS + wave * W_IPW + (j - A_IPW);   // 16-row group of the stage
+    const int r = grp * 16 + lane / CPR;
+    const int ch = (lane % CPR) ^ swz_mask<CPR>(r);
+    const bf16_t* base;
+    if (r < 2 * BM) {
+      int am = m0 + (r < BM ? r : r - BM);
+      am = am < M ? am : M - 1;                  // rows past M are copied (clamped) and never stored
+      base = (r < BM ? g.a : g.a_lo) + (size_t)am * K;
+    } else {
+      const int col = r - 2 * BM;
+      int wrow;
+      const bf16_t* wbase;
+      if (EPI == GEMM_SWIGLU_BF16) {             // 32-column blocks alternate gate, up
+        wrow = (n0 >> 1) + ((col >> 6) << 5) + (col & 31);
+        wbase = ((col >> 5) & 1) ? g.w[1] : g.w[0];
+      } else {
+        wrow = n0 + col;
+        wbase = g.w[0];
+        if (wrow >= g.w_rows[0]) {
+          wrow -= g.w_rows[0];
+          wbase = g.w[1];
+          if (wrow >= g.w_rows[1]) {
+            wrow -= g.w_rows[1];
+            wbase = g.w[2];
+          }
+        }
+      }
+      base = wbase + (size_t)wrow * K;
+    }
+    src[j] = base + (size_t)step_begin * BK + ch * 8;
+    dst[j] = grp * 16 * BK * 2;
+  }
+
+  f32x16 acc[MB][2];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int l32 = lane & 31, kb = lane >> 5;
+  // fragment offsets of sub-step 0; sub-step 1 is the next chunk (its XOR partner, see swz)
+  const int a_off0 = swz<CPR>(l32, kb * 2), a_off1 = swz<CPR>(l32, kb * 2 + 1);             // + i * 32 rows; + BM rows: lo
+  const int w_off0 = 2 * BM * BK + swz<CPR>(wave * 64 + l32, kb * 2);                        // + j * 32 rows
+  const int w_off1 = 2 * BM * BK + swz<CPR>(wave * 64 + l32, kb * 2 + 1);
+#define SY_COPY(J_, NXT, STEP) glds16_at(src[J_] + (size_t)(STEP) * BK, NXT + dst[J_]);
+#define SY_ISSUE(NXT, STEP) _Pragma("unroll") for (int j = 0; j < IPW; ++j) SY_COPY(j, NXT, STEP)
+#define SY_MFMA(ACC, FA, FW, I_)                                                                  \
+  if ((I_) < 8) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(FA), "v"(FW)); \
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(ACC) : "v"(FA), "v"(FW));
+#define SY_LOAD_A(I_, STAGE)                                                                      \
+  if ((I_) < MB) {                                                                                \
+    fa[((I_) >> 1) & 1][(I_) & 1][0] = *reinterpret_cast<const bf16x8*>(STAGE + a_off0 + (I_) * 32 * BK);        \
+    fa[((I_) >> 1) & 1][(I_) & 1][1] = *reinterpret_cast<const bf16x8*>(STAGE + a_off1 + (I_) * 32 * BK);        \
+    fa[((I_) >> 1) & 1][(I_) & 1][2] = *reinterpret_cast<const bf16x8*>(STAGE + a_off0 + (BM + (I_) * 32) * BK); \
+    fa[((I_) >> 1) & 1][(I_) & 1][3] = *reinterpret_cast<const bf16x8*>(STAGE + a_off1 + (BM + (I_) * 32) * BK); \
+  }
+// Row blocks go through the matrix core in pairs: (block, column half) gives four independent
+// accumulators per fragment term, so an accumulator is needed again only four MFMAs later (an MFMA that
+// accumulates onto the result of the one issued just before the previous one still waits for it).
+#define SY_MULT(STAGE, NXT, NSTEP)                                                                \
+  {                                                                                               \
+    constexpr int NP = (MB + 1) / 2;                                                              \
+    bf16x8 fw[2][2], fa[2][2][4];                /* fw[j][ks]; fa[buffer][block of the pair][hi ks0, hi ks1, lo ks0, lo ks1] */ \
+    _Pragma("unroll") for (int j = 0; j < 2; ++j) {                                               \
+      fw[j][0] = *reinterpret_cast<const bf16x8*>(STAGE + w_off0 + j * 32 * BK);                  \
+      fw[j][1] = *reinterpret_cast<const bf16x8*>(STAGE + w_off1 + j * 32 * BK);                  \
+    }                                                                                             \
+    SY_LOAD_A(0, STAGE)                                                                           \
+    SY_LOAD_A(1, STAGE)                                                                           \
+    _Pragma("unroll") for (int p = 0; p < NP; ++p) {                                              \
+      SY_LOAD_A(2 * p + 2, STAGE)                                                                 \
+      SY_LOAD_A(2 * p + 3, STAGE)                                                                 \
+      _Pragma("unroll") for (int j = 0; j < IPW; ++j)                                             \
+          if (j * NP / IPW == p) SY_COPY(j, NXT, NSTEP)                                           \
+      _Pragma("unroll") for (int t = 0; t < 4; ++t)                                               \
+          _Pragma("unroll") for (int b = 0; b < 2; ++b)                                           \
+              _Pragma("unroll") for (int j = 0; j < 2; ++j)                                       \
+                  if (2 * p + b < MB) SY_MFMA(acc[2 * p + b][j], fa[p & 1][b][t], fw[j][t & 1], 2 * p + b) \
+    }                                                                                             \
+  }
+#define SY_STEP(CUR, NXT, S_)                                                                     \
+  {                                                                                               \
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(IPW) : "memory");                         \
+    asm volatile("s_barrier" ::: "memory");                                                       \
+    const int nxt_ = (S_) + 2 < n_steps ? (S_) + 2 : n_steps - 1;                                 \
+    SY_MULT(CUR, NXT, nxt_)                                                                       \
+  }
+
+  const uint32_t l0 = lds_addr_of(st0), l1 = lds_addr_of(st1), l2 = lds_addr_of(st2);
+  SY_ISSUE(l0, 0)
+  {
+    const int one_ = n_steps > 1 ? 1 : 0;
+    SY_ISSUE(l1, one_)
+  }
+  int s = 0;
+  for (; s + 3 <= n_steps; s += 3) {
+    SY_STEP(st0, l2, s)
+    SY_STEP(st1, l0, s + 1)
+    SY_STEP(st2, l1, s + 2)
+  }
+  if (s < n_steps) {
+    SY_STEP(st0, l2, s)
+    if (s + 1 < n_steps) SY_STEP(st1, l0, s + 1)
+  }
+#undef SY_COPY
+#undef SY_ISSUE
+#undef SY_MFMA
+#undef SY_LOAD_A
+#undef SY_MULT
+#undef SY_STEP
+  // The surplus copies of the last steps are still in flight: let them land before the block's LDS is
+  // released.  The MFMAs above are inline assembly: the compiler does not know that the accumulators were
+  // just written by them, so the wait the hardware needs before other instructions read an MFMA result is
+  // spelled out here.
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+
+#pragma unroll
+  for (int i = 0; i < MB; ++i) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + i * 32 + 8 * (r >> 2) + 4 * kb + (r & 3);
+      if (m >= M) continue;
+      if (EPI == GEMM_SWIGLU_BF16) {
+        const float gate = acc[i][0][r], up = acc[i][1][r];
+        const float v = gate / (1.0f + __expf(-gate)) * up;
+        const size_t at = (size_t)m * (g.N >> 1) + (n0 >> 1) + wave * 32 + l32;
+        const uint32_t hi = f2bf(v);
+        reinterpret_cast<bf16_t*>(g.c)[at] = (bf16_t)hi;
+        reinterpret_cast<bf16_t*>(g.c_lo)[at] = (bf16_t)f2bf(v - bf2f(hi));
+      } else {
+        float* c = reinterpret_cast<float*>(g.c) + (size_t)m * g.N + n0 + wave * 64 + l32;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const float v = acc[i][j][r];
+          if (g.split_k > 1) {
+            unsafeAtomicAdd(c + j * 32, v);
+          } else if (EPI == GEMM_ADD_F32) {
+            c[j * 32] += v;
+          } else {
+            c[j * 32] = v;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int MT>
+static hipError_t launch_tall(const GemmArgs& g, hipStream_t s) {
+  constexpr int BM = 32 * MT;
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / 256;
+  const dim3 grid(8 * ((n_tiles + 7) / 8) * m_tiles, 1, g.split_k);
+  switch (g.epilogue) {
+    case GEMM_STORE_F32: gemm_tall_kernel<MT, GEMM_STORE_F32><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_ADD_F32: gemm_tall_kernel<MT, GEMM_ADD_F32><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_SWIGLU_BF16: gemm_tall_kernel<MT, GEMM_SWIGLU_BF16><<<grid, 256, 0, s>>>(g); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // Tile configurations.  N tile 256 halves the weight re-reads from L2 per MFMA; the 128-wide
 // one serves outputs whose N is not a multiple of 256 and small problems.
 template <int BM, int BN, int BK, int WGM, int WGN, bool SPLIT>
@@ -451,7 +681,9 @@ struct Variant { int bm, bn; };
 static const Variant kVariants[] = {{128, 128}, {128, 256}, {256, 128}, {256, 256}, {64, 256}, {192, 256}, {256, 256},
                                    {128, 256}, {64, 128}, {128, 128}, {64, 256},
                                    {128, 128}, {128, 256}, {128, 256}, {64, 256},    // 11..: async-copy kernels
-                                   {64, 256}, {128, 128}, {64, 128}};
+                                   {64, 256}, {128, 128}, {64, 128},
+                                   {128, 256}, {160, 256}, {192, 256}, {224, 256}, {256, 256}, {288, 256}};   // 18..: tall tiles
+static const int kFirstTall = 18;
 static const int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 static bool variant_fits(const GemmArgs& g, int v) {
@@ -463,14 +695,52 @@ static bool variant_fits(const GemmArgs& g, int v) {
   return true;
 }
 
+// Tall-tile plan: the row-block count MB (tile = 32 MB rows) and the K split with the least modelled time.
+// Blocks are equal-sized and one runs per compute unit, so a launch takes ceil(blocks / 256) rounds of
+//   K steps per block x (0.30 + 0.14 MB) us        (fit of MI355X timings at M = 300..1030)
+// plus, with K split, the atomic adds of the partial tiles (about 8.5 us per split per 2.2 M outputs).
+static int tall_split(const GemmArgs& g, int mb) {
+  if (g.epilogue == GEMM_SWIGLU_BF16) return 1;
+  const long tiles = (long)((g.M + 32 * mb - 1) / (32 * mb)) * (g.N / 256);
+  long split = 256 / tiles;
+  const long most = g.K / 32 / 8;               // at least 8 K steps per slice
+  split = split < most ? split : most;
+  return split < 1 ? 1 : (int)split;
+}
+static double tall_cost(const GemmArgs& g, int mb, int split) {
+  const long tiles = (long)((g.M + 32 * mb - 1) / (32 * mb)) * (g.N / 256);
+  const long rounds = (tiles * split + 255) / 256;
+  const double steps = (double)(g.K / 32) / split;
+  const double atomics = split > 1 ? 8.5 * split * ((double)g.M * g.N / 2.2e6) : 0.0;
+  return rounds * steps * (0.30 + 0.14 * mb) + atomics;
+}
+static int pick_tall(const GemmArgs& g, int* split_out) {
+  int best = -1, best_split = 1;
+  double best_cost = 0.0;
+  for (int mb = 4; mb <= 9; ++mb) {
+    const int tile_split = tall_split(g, mb);
+    for (int split = 1; split <= tile_split; ++split) {    // fewer slices than fit can win: fewer atomics
+      const double c = tall_cost(g, mb, split);
+      if (best < 0 || c < best_cost) {
+        best = mb;
+        best_cost = c;
+        best_split = split;
+      }
+    }
+  }
+  if (split_out) *split_out = best_split;
+  return kFirstTall + (best - 4);
+}
+
 static int pick_variant(const GemmArgs& g) {
   if (g_gemm_variant >= 0 && g_gemm_variant < kNumVariants && variant_fits(g, g_gemm_variant) &&
       (g_gemm_variant < 11 || g.a_lo))
     return g_gemm_variant;
-  // From the tile sweeps on MI355X.  With (hi, lo) activations the asynchronous-copy kernels win:
-  // 128x256 with 8 wavefronts for large M, 64x256 otherwise, 128x128 where N is not a multiple of 256.
+  // From the tile sweeps on MI355X.  With (hi, lo) activations: tall tiles from about a hundred rows up
+  // (verification batches), the 64-row asynchronous-copy kernel below that (decode steps), 128x128 where N
+  // is not a multiple of 256.
   if (g.a_lo) {
-    if (g.M >= 768 && variant_fits(g, 13)) return 13;
+    if (g.M > 96 && variant_fits(g, kFirstTall)) return pick_tall(g, nullptr);
     if (variant_fits(g, 14)) return 14;
     return 11;
   }
@@ -481,9 +751,16 @@ static int pick_variant(const GemmArgs& g) {
 
 int gemm_pick_split(const GemmArgs& g) {
   if (g.epilogue == GEMM_SWIGLU_BF16) return 1;
-  // Enough blocks to cover the 256 compute units about twice; K slices stay >= 512.
-  const Variant v = kVariants[pick_variant(g)];
+  const int vi = pick_variant(g);
+  if (vi >= kFirstTall) {
+    int split = 1;
+    if (g_gemm_variant >= 0) return tall_split(g, vi - kFirstTall + 4);   // forced tile: as many slices as fit
+    pick_tall(g, &split);
+    return split;
+  }
+  const Variant v = kVariants[vi];
   const long tiles = (long)((g.M + v.bm - 1) / v.bm) * (g.N / v.bn);
+  // Enough blocks to cover the 256 compute units about twice; K slices stay >= 512.
   int split = 1;
   while (tiles * split < 512 && g.K % (split * 2 * 64) == 0 && g.K / (split * 2) >= 512) split *= 2;
   return split;
@@ -492,8 +769,8 @@ int gemm_pick_split(const GemmArgs& g) {
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0) return hipSuccess;
   const int v = pick_variant(g);
-  if (!variant_fits(g, v) || g.K % 64 != 0 || g.split_k < 1 || g.K % (g.split_k * 64) != 0)
-    return hipErrorInvalidValue;
+  if (!variant_fits(g, v) || g.K % 64 != 0 || g.split_k < 1) return hipErrorInvalidValue;
+  if (v >= kFirstTall ? g.split_k > g.K / 32 : g.K % (g.split_k * 64) != 0) return hipErrorInvalidValue;
   if (v >= 11 && !g.a_lo) return hipErrorInvalidValue;
   if (g.epilogue == GEMM_SWIGLU_BF16) {
     if (g.split_k != 1 || !g.c_lo) return hipErrorInvalidValue;
@@ -524,6 +801,12 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     case 15: return launch_dma<64, 256, 64, 1, 4>(g, s);
     case 16: return launch_dma<128, 128, 64, 2, 2>(g, s);
     case 17: return launch_dma<64, 128, 64, 2, 2>(g, s);
+    case 18: return launch_tall<4>(g, s);
+    case 19: return launch_tall<5>(g, s);
+    case 20: return launch_tall<6>(g, s);
+    case 21: return launch_tall<7>(g, s);
+    case 22: return launch_tall<8>(g, s);
+    case 23: return launch_tall<9>(g, s);
     default: return hipErrorInvalidValue;
   }
 #undef SY_VARIANT

@@ -154,6 +154,46 @@ def test_gemm_matches_float64(M, N, K):
     assert (c - ref).abs().max().item() < 1e-3 * scale + 1e-5
 
 
+def _split_pair(x):
+    hi = x.to(torch.bfloat16)
+    return hi, (x - hi.float()).to(torch.bfloat16)
+
+
+# tile configurations: 11, 13, 14 = 128x128 / 128x256 / 64x256 asynchronous-copy kernels, 18..23 = tall tiles of 128..288 rows
+@pytest.mark.parametrize("variant", [-1, 11, 13, 14, 18, 19, 20, 21, 22, 23])
+@pytest.mark.parametrize("M,N,K", [(1, 256, 64), (97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (600, 4096, 1792)])
+def test_gemm_pair_activations_every_tile_and_epilogue(variant, M, N, K):
+    """(hi, lo) activations through each tile configuration: store (K split included), residual add,
+    SwiGLU; compared with the float64 product of the same bf16 operands."""
+    synera = _synera()
+    g = torch.Generator(device=DEV).manual_seed(1000 * M + N + K)
+    x = torch.randn((M, K), generator=g, device=DEV)
+    a, al = _split_pair(x)
+    w = wl.draw_normal_bf16((N, K), 0.02, 17 * N + K, DEV)
+    xd = a.double() + al.double()
+    want = xd @ w.double().T
+    tol = 3e-6 * 0.02 * K + 1e-6
+    synera.debug_set_gemm_tile(variant)
+    try:
+        c = synera.gemm_bf16(a, w, a_lo=al)
+        base = torch.randn((M, N), generator=g, device=DEV)
+        c_add = base.clone()
+        synera.debug_gemm_epilogue(a, al, w, None, c_add, None, 1)
+        half = N // 2
+        act_hi = torch.empty((M, half), dtype=torch.bfloat16, device=DEV)
+        act_lo = torch.empty_like(act_hi)
+        synera.debug_gemm_epilogue(a, al, w[:half].contiguous(), w[half:].contiguous(), act_hi, act_lo, 2)
+        torch.cuda.synchronize()
+    finally:
+        synera.debug_set_gemm_tile(-1)
+    assert (c.double() - want).abs().max().item() < tol
+    assert (c_add.double() - (base.double() + want)).abs().max().item() < tol + 1e-6
+    gate, up = want[:, :half], want[:, half:]
+    glu = gate / (1 + torch.exp(-gate)) * up
+    got = act_hi.double() + act_lo.double()
+    assert (got - glu).abs().max().item() < 2 * tol + 2.0 ** -15 * glu.abs().max().item()
+
+
 def test_gemm_rejects_unsupported_shapes():
     synera = _synera()
     a = torch.zeros((4, 96), dtype=torch.bfloat16, device=DEV)
