@@ -62,7 +62,15 @@ __device__ __forceinline__ void store_pair(bf16_t* hi, bf16_t* lo, float a, floa
 // wavefront-uniform LDS address).  Issued from inline assembly so that the waits are exactly the
 // ones written below.
 __device__ __forceinline__ void copy_to_lds(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
+
+// XOR mask of a K slot's 16-byte chunks in LDS.  A fragment read (lane = slot l % 16, chunk 4 s + l / 16)
+// is served 16 lanes per cycle over 64 banks, lanes l and l + 16 together: slots that share banks (all of
+// them at head_dim 128, every second one at 64) must differ in the chunk bits that l / 16 leaves alone.
+template <int HD>
+__device__ __forceinline__ int kswz(int slot) {
+  return HD == 128 ? (((slot & 3) << 2) | (((slot >> 2) & 1) << 1)) : ((((slot >> 1) & 1) << 2) | (((slot >> 2) & 1) << 1));
 }
 
 template <int HD, int RBN>
@@ -104,7 +112,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
     c_tile[j] = e / (4 * IPP);
     if (c_pg[j] < 2) {
       const int slot = c_q[j] * (1024 / (HD * 2)) + lane / CPS;
-      c_off[j] = slot * HD + (((lane % CPS) ^ (slot & 7)) << 3);
+      c_off[j] = slot * HD + (((lane % CPS) ^ kswz<HD>(slot)) << 3);
     } else {
       c_off[j] = c_q[j] * 512 + lane * 8;
     }
@@ -159,6 +167,12 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
       ql[s] = *reinterpret_cast<const bf16x8*>(a.q_lo + qat + 32 * s);
     }
   }
+  // Make the compiler finish the Q loads HERE.  It cannot see the asynchronous copies issued from inline
+  // assembly, so with the Q loads still "pending" at the loop head it guards every first use of a Q register
+  // inside the loop with s_waitcnt vmcnt(k), k counted from the Q loads: in reality those waits drain the
+  // K/V copies just issued, once per iteration, and the ring never runs ahead.
+#pragma unroll
+  for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(qh[s]), "v"(ql[s]));
   const int lim = row < nrows ? it.ctx_len + it.j0 + row / G : 0x7FFFFFFF;   // last key this row may see
   const int free_end = min(key_end, it.ctx_len + it.j0 + 1);                 // keys below need no mask
 
@@ -180,7 +194,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      const int ch = ((4 * s + g) ^ (n16 & 7)) << 4;
+      const int ch = ((4 * s + g) ^ kswz<HD>(n16)) << 4;
       const bf16x8 ka = *reinterpret_cast<const bf16x8*>(tile + n16 * (HD * 2) + ch);
       const bf16x8 kbf = *reinterpret_cast<const bf16x8*>(tile + PAGE_B + n16 * (HD * 2) + ch);
       s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qh[s], s0, 0, 0, 0);
