@@ -40,13 +40,6 @@ __device__ __forceinline__ float row_max4(float v) {
   auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
-__device__ __forceinline__ float row_sum4(float v) {
-  auto a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
-  auto b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
-}
-
 // Four consecutive outputs as a bf16 (hi, lo) pair: 8 bytes to each array.
 __device__ __forceinline__ void store_pair(bf16_t* hi, bf16_t* lo, float a, float b, float c, float d) {
   uint2 h, l;
@@ -73,17 +66,32 @@ __device__ __forceinline__ int kswz(int slot) {
   return HD == 128 ? (((slot & 3) << 2) | (((slot >> 2) & 1) << 1)) : ((((slot >> 1) & 1) << 2) | (((slot >> 2) & 1) << 1));
 }
 
+// Wait until at most `tiles` x IPP of this wavefront's copies are in flight and its LDS reads are done
+// (the wait count is an immediate, so the few possible values are spelled out; `tiles` is wavefront-uniform).
+template <int IPP, int MAX_TILES>
+__device__ __forceinline__ void wait_copies(int tiles) {
+  static_assert(MAX_TILES <= 3, "add cases");
+  if (tiles >= 3 && MAX_TILES >= 3) {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(3 * IPP) : "memory");
+  } else if (tiles == 2 && MAX_TILES >= 2) {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(2 * IPP) : "memory");
+  } else if (tiles == 1 && MAX_TILES >= 1) {
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(1 * IPP) : "memory");
+  } else {
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  }
+}
+
 template <int HD, int RBN>
 __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& it, float scale_log2) {
-  constexpr int KP = 4 / RBN;                       // key phases per super-tile
-  constexpr int S = RBN;                            // LDS stages (super-tiles): 64 KB at head_dim 128,
-                                                    // so two blocks (8 wavefronts) share a compute unit
+  constexpr int KP = 4 / RBN;                       // key phases: 32-key tiles consumed per iteration
+  constexpr int NT = 5;                             // LDS ring: tile t lives in slot t % NT; NT - KP tiles stay
+                                                    // in flight behind the KP being multiplied (80 KB at
+                                                    // head_dim 128, so two blocks share a compute unit)
   constexpr int KS = HD / 32, DB = HD / 16;
   constexpr int PAGE_B = SY_PAGE * HD * 2;          // bytes of one K or V page tile
   constexpr int TILE_B = 4 * PAGE_B;                // K page a, K page b, V page a, V page b
-  constexpr int STAGE_B = KP * TILE_B;
-  constexpr int IPP = PAGE_B / 1024;                // copy instructions per page
-  constexpr int IPW = KP * IPP;                     // copy instructions per wavefront and super-tile
+  constexpr int IPP = PAGE_B / 1024;                // copy instructions per page = per wavefront and tile
   constexpr int CPS = HD / 8;                       // 16-byte chunks per K slot
   constexpr int OSTRIDE = HD + 4;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -101,55 +109,42 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
   const int last_page = (key_end - 1) >> 4;
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)lds;
 
-  // ---- what this lane copies: per instruction j the page slot inside the stage and the lane's element
-  //      offset inside the page (K chunks are swizzled by slot, V is copied straight)
-  int c_tile[IPW], c_pg[IPW], c_q[IPW], c_off[IPW];
+  // ---- copies: of every tile this wavefront copies page tile `wave` (K page a, K page b, V page a, V page b),
+  //      IPP instructions of one kilobyte; the lane's element offset inside the page is fixed
+  //      (K chunks are swizzled by slot, V is copied straight)
+  int c_off[IPP];
 #pragma unroll
-  for (int j = 0; j < IPW; ++j) {
-    const int e = wave * IPW + j;
-    c_q[j] = e % IPP;
-    c_pg[j] = (e / IPP) % 4;
-    c_tile[j] = e / (4 * IPP);
-    if (c_pg[j] < 2) {
-      const int slot = c_q[j] * (1024 / (HD * 2)) + lane / CPS;
+  for (int j = 0; j < IPP; ++j) {
+    if (wave < 2) {
+      const int slot = j * (1024 / (HD * 2)) + lane / CPS;
       c_off[j] = slot * HD + (((lane % CPS) ^ kswz<HD>(slot)) << 3);
     } else {
-      c_off[j] = c_q[j] * 512 + lane * 8;
+      c_off[j] = j * 512 + lane * 8;
     }
   }
   const size_t page_elems = (size_t)Hkv * SY_PAGE * HD;
-  const bf16_t* k_head = a.k_layer + (size_t)kh * SY_PAGE * HD;
-  const bf16_t* v_head = a.v_layer + (size_t)kh * SY_PAGE * HD;
+  const bf16_t* my_pool = (wave < 2 ? a.k_layer : a.v_layer) + (size_t)kh * SY_PAGE * HD;
 
   const int n_keys = key_end - it.key_begin;
-  const int n_iter = (n_keys + 32 * KP - 1) / (32 * KP);
-  // Copies of super-tile `iter` into stage iter % S.  Past the last super-tile the same number of
-  // copies is still issued (the wait counts below stay constant), into a per-wavefront dump kilobyte.
+  const int n_tiles = (n_keys + 31) / 32;
+  const int n_iter = (n_tiles + KP - 1) / KP;
   // A key range spans at most 64 pages (the host cuts ranges at <= 1024 keys): lane l keeps the id of
-  // the range's page l, and a copy group reads its two page ids with v_readlane.
+  // the range's page l, and a copy reads its page id with v_readlane.
   const int first_page = it.key_begin >> 4;
   const int n_pages_rng = last_page - first_page + 1;
   const int my_page = bt[first_page + (lane < n_pages_rng ? lane : n_pages_rng - 1)];
-  // All copies of one wavefront belong to one 32-key tile of the super-tile (c_tile[0]).
-  auto issue = [&](int iter) {
-    const bool real = iter < n_iter;
-    const int it_ = real ? iter : n_iter - 1;
-    const uint32_t stage = lds_base + (uint32_t)(it_ % S) * STAGE_B;
-    const uint32_t dump = lds_base + S * STAGE_B + wave * 1024;
-    int i0 = ((it_ * KP + c_tile[0]) * 32) >> 4;     // page index relative to the range's first page
-    i0 = i0 < n_pages_rng - 1 ? i0 : n_pages_rng - 1;   // past the range: a valid page, masked later
-    const int i1 = i0 + 1 < n_pages_rng - 1 ? i0 + 1 : n_pages_rng - 1;
-    const int page_a = __builtin_amdgcn_readlane(my_page, i0);
-    const int page_b = __builtin_amdgcn_readlane(my_page, i1);
+  // Copies of tile t into slot t % NT; nothing past the range's last tile.
+  auto issue_tile = [&](int t) {
+    if (t >= n_tiles) return;                         // wavefront-uniform
+    int pi = 2 * t + (wave & 1);                      // page index relative to the range's first page
+    pi = pi < n_pages_rng - 1 ? pi : n_pages_rng - 1; // the last tile may have one page only
+    const bf16_t* src = my_pool + (size_t)__builtin_amdgcn_readlane(my_page, pi) * page_elems;
+    const uint32_t dst = lds_base + (uint32_t)(t % NT) * TILE_B + wave * PAGE_B;
 #pragma unroll
-    for (int j = 0; j < IPW; ++j) {
-      const int page = (c_pg[j] & 1) ? page_b : page_a;
-      const bf16_t* src = (c_pg[j] < 2 ? k_head : v_head) + (size_t)page * page_elems + c_off[j];
-      copy_to_lds(src, real ? stage + c_tile[j] * TILE_B + c_pg[j] * PAGE_B + c_q[j] * 1024 : dump);
-    }
+    for (int j = 0; j < IPP; ++j) copy_to_lds(src + c_off[j], dst + j * 1024);
   };
 #pragma unroll
-  for (int p = 0; p < S - 1; ++p) issue(p);
+  for (int t = 0; t < NT - KP; ++t) issue_tile(t);
 
   // ---- Q fragments of this wavefront's row block (B operand: lane = (row n16, dim chunk g))
   const int row = rb * 16 + n16;
@@ -176,20 +171,31 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
   const int lim = row < nrows ? it.ctx_len + it.j0 + row / G : 0x7FFFFFFF;   // last key this row may see
   const int free_end = min(key_end, it.ctx_len + it.j0 + 1);                 // keys below need no mask
 
-  float m_run = NEG_BIG, l_run = 0.f;
+  float m_run = NEG_BIG;
+  f32x4 acc_l = {0.f, 0.f, 0.f, 0.f};
+  bf16x8 ones;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
   f32x4 acc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   for (int iter = 0; iter < n_iter; ++iter) {
-    // Own copies of this super-tile have landed (S-2 younger groups may still be in flight), own LDS
-    // reads of the previous one are done; the barrier extends both facts to the whole block.
-    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((S - 2) * IPW) : "memory");
+    // Own copies of this iteration's KP tiles have landed (the NT - 2 KP younger tiles may still be in
+    // flight), own LDS reads of the previous ones are done; the barrier extends both facts to the block.
+    // Tiles issued so far: min(n_tiles, iter KP + NT - KP); the ones after this iteration's may stay in flight.
+    {
+      const int issued = min(n_tiles, iter * KP + NT - KP);
+      const int younger = max(0, issued - (iter + 1) * KP);
+      wait_copies<IPP, NT - 2 * KP>(younger);
+    }
     asm volatile("s_barrier" ::: "memory");
-    issue(iter + S - 1);
-    const int kb = it.key_begin + (iter * KP + kp) * 32;
+#pragma unroll
+    for (int q = 0; q < KP; ++q) issue_tile(iter * KP + NT - KP + q);   // into the slots read last iteration
+    const int tile_no = iter * KP + kp;
+    const int kb = it.key_begin + tile_no * 32;
     if (kb >= key_end) continue;                      // wavefront-uniform
-    const unsigned char* tile = lds + (size_t)(iter % S) * STAGE_B + kp * TILE_B;
+    const unsigned char* tile = lds + (size_t)(tile_no % NT) * TILE_B;
 
     f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -202,16 +208,17 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
       s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, ql[s], s0, 0, 0, 0);
       s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kbf, ql[s], s1, 0, 0, 0);
     }
+    // Softmax in the exponent-2 domain on the raw scores: p = 2^(s c - m c), c = log2(e) / sqrt(h) > 0,
+    // m the running row maximum of the raw scores.
     float sv[8];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      sv[r] = s0[r] * scale_log2;
-      sv[4 + r] = s1[r] * scale_log2;
+      sv[r] = s0[r];
+      sv[4 + r] = s1[r];
     }
+    const bool masked = kb + 32 > free_end;           // wavefront-uniform: only the last tiles of a range
     bool vis[8];
-#pragma unroll
-    for (int r = 0; r < 8; ++r) vis[r] = true;
-    if (kb + 32 > free_end) {
+    if (masked) {
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
         const int tau = kb + 16 * (r >> 2) + 4 * g + (r & 3);
@@ -219,20 +226,19 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
         sv[r] = vis[r] ? sv[r] : NEG_BIG;
       }
     }
-    float mx = sv[0];
-#pragma unroll
-    for (int r = 1; r < 8; ++r) mx = fmaxf(mx, sv[r]);
+    float mx = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
     mx = row_max4(mx);
     const float m_new = fmaxf(m_run, mx);
-    const float alpha = ex2(m_run - m_new);
+    const float alpha = ex2((m_run - m_new) * scale_log2);
+    const float mc = m_new * scale_log2;
     m_run = m_new;
-    float p[8], psum = 0.f;
+    float p[8];
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      p[r] = vis[r] ? ex2(sv[r] - m_new) : 0.f;
-      psum += p[r];
+    for (int r = 0; r < 8; ++r) p[r] = ex2(fmaf(sv[r], scale_log2, -mc));
+    if (masked) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) p[r] = vis[r] ? p[r] : 0.f;
     }
-    l_run = l_run * alpha + psum;
     uint4 pk, pl;
     pk.x = pack_bf2(p[0], p[1]);
     pk.y = pack_bf2(p[2], p[3]);
@@ -250,7 +256,12 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
       for (int db = 0; db < DB; ++db) {
         acc[db][0] *= alpha; acc[db][1] *= alpha; acc[db][2] *= alpha; acc[db][3] *= alpha;
       }
+      acc_l[0] *= alpha; acc_l[1] *= alpha; acc_l[2] *= alpha; acc_l[3] *= alpha;
     }
+    // Row sums ride on the matrix core: an all-ones "V row" accumulates sum_k p[k] of the lane's query
+    // row, the (hi, lo) pair makes it exact to fp32, and no cross-lane reduction is needed.
+    acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf, acc_l, 0, 0, 0);
+    acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pfl, acc_l, 0, 0, 0);
     if (kb + 32 > key_end) {
       // Last tile of the range: V slots past it may hold junk (0 * NaN), blank them.
       uint32_t vm[4];
@@ -293,7 +304,8 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
   // ---- finish: every copy has landed and every wavefront is past its last read before LDS is reused
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   asm volatile("s_barrier" ::: "memory");
-  l_run = row_sum4(l_run);
+  const float l_run = acc_l[0];
+  const float m_fin = m_run * scale_log2;             // running maximum in the exponent-2 domain, as the merges use it
 
   if (KP == 1) {                                      // the wavefront owns its rows outright
     if (row < nrows) {
@@ -310,7 +322,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
         for (int db = 0; db < DB; ++db)
           *reinterpret_cast<float4*>(a.part_o + base * HD + db * 16 + 4 * g) =
               make_float4(acc[db][0], acc[db][1], acc[db][2], acc[db][3]);
-        if (g == 0) *reinterpret_cast<float2*>(a.part_ml + base * 2) = make_float2(m_run, l_run);
+        if (g == 0) *reinterpret_cast<float2*>(a.part_ml + base * 2) = make_float2(m_fin, l_run);
       }
     }
     return;
@@ -321,7 +333,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
   float* s_m = s_o + 4 * 16 * OSTRIDE;                // [4][16]
   float* s_l = s_m + 64;                              // [4][16]
   if (g == 0) {
-    s_m[wave * 16 + n16] = m_run;
+    s_m[wave * 16 + n16] = m_fin;
     s_l[wave * 16 + n16] = l_run;
   }
   __syncthreads();
@@ -329,7 +341,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const AttnItem& i
     float ms = NEG_BIG;
 #pragma unroll
     for (int q = 0; q < KP; ++q) ms = fmaxf(ms, s_m[(q * RBN + rb) * 16 + n16]);
-    const float f = ex2(m_run - ms);
+    const float f = ex2(m_fin - ms);
 #pragma unroll
     for (int db = 0; db < DB; ++db)
       *reinterpret_cast<float4*>(s_o + ((size_t)wave * 16 + n16) * OSTRIDE + db * 16 + 4 * g) =
@@ -407,7 +419,7 @@ static hipError_t launch_hd(const AttnLaunch& a, hipStream_t s) {
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)HD);
   const int n = a.class_begin[3];
   if (n > 0) {
-    const size_t lds_ring = (size_t)4 * 4 * SY_PAGE * HD * 2 + 4 * 1024;   // 4 tiles of 32 keys + dump kilobytes
+    const size_t lds_ring = (size_t)5 * 4 * SY_PAGE * HD * 2;              // 5 tiles of 32 keys
     const size_t lds_merge = (size_t)(4 * 16 * (HD + 4) + 128) * sizeof(float);
     const size_t lds = lds_ring > lds_merge ? lds_ring : lds_merge;
     static bool attr_set = false;
