@@ -1,0 +1,69 @@
+"""Kernel-level measurements of the standalone entry points (not the end-to-end benchmark, which is
+bench.py at the repository root):
+
+    python -m paper_2511_07423_amd.measure confidence   # synera_confidence on a 2048 x 128256 logits block
+    python -m paper_2511_07423_amd.measure gemm         # the four projection shapes of the 8B decoder at M = 532
+
+Each line gives the average launch time over HIP events on the launch stream and the achieved rate
+against MI355X's peak (HBM 8 TB/s; dense bf16 MFMA 2.5 PFLOP/s, algorithmic FLOPs).  Inputs are seeded
+and synthetic (workloads/)."""
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def _time(fn, n=20, warm=3):
+    import torch
+    for _ in range(warm):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n
+
+
+def confidence():
+    import torch
+    import paper_2511_07423_amd as synera
+    import workloads as wl
+    from workloads import shapes
+    for dtype, name in ((torch.float32, "f32"), (torch.bfloat16, "bf16")):
+        x = wl.draw_confidence_logits(shapes.C5B_ROWS, shapes.C5B_VOCAB, shapes.C5B_STD, shapes.C5B_BOOST_HI,
+                                      wl.config(5).seed, "cuda:0", dtype)
+        ms = _time(lambda: synera.confidence(x))
+        nbytes = x.numel() * x.element_size()
+        print(json.dumps({"kernel": "synera_confidence", "rows": shapes.C5B_ROWS, "vocab": shapes.C5B_VOCAB,
+                          "dtype": name, "bytes": nbytes, "avg_launch_ms": ms, "bound": "hbm",
+                          "achieved_GBs": nbytes / ms / 1e6, "peak_GBs": 8000.0, "frac": nbytes / ms / 1e6 / 8000.0}))
+
+
+def gemm():
+    import torch
+    import paper_2511_07423_amd as synera
+    import workloads as wl
+    M = 532
+    for name, N, K in (("qkv", 6144, 4096), ("o", 4096, 4096), ("gate_up (store epilogue)", 28672, 4096),
+                       ("down", 4096, 14336)):
+        x = torch.randn((M, K), generator=torch.Generator(device="cuda:0").manual_seed(7), device="cuda:0")
+        a = x.to(torch.bfloat16)
+        al = (x - a.float()).to(torch.bfloat16)
+        ws = [wl.draw_normal_bf16((N, K), 0.02, 100 + i, "cuda:0") for i in range(3)]     # rotated: no cache reuse
+        c = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
+        it = iter(range(10 ** 9))
+        ms = _time(lambda: synera.gemm_bf16(a, ws[next(it) % 3], a_lo=al, out=c), n=18)
+        fl = 2.0 * M * N * K
+        print(json.dumps({"kernel": "synera_gemm_bf16", "shape": name, "M": M, "N": N, "K": K, "avg_launch_ms": ms,
+                          "bound": "mfma", "achieved_TFLOPs": fl / ms / 1e9, "executed_TFLOPs": 2 * fl / ms / 1e9,
+                          "peak_TFLOPs": 2500.0, "frac": fl / ms / 1e9 / 2500.0}))
+
+
+if __name__ == "__main__":
+    which = sys.argv[1] if len(sys.argv) > 1 else "confidence"
+    {"confidence": confidence, "gemm": gemm}[which]()
