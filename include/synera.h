@@ -258,7 +258,8 @@ int32_t synera_debug_gemm_epilogue(const void* d_a, const void* d_a_lo, const vo
 
 /*
  * Test hook: copy one of the context's intermediate buffers, as the LAST layer of the last
- * verify left it, to caller device memory.  which: 0 residual x (f32 [T][d]), 1/2 rotated q
+ * verify left it, to caller device memory.  which: 0 residual x (f32 [T][d]; when the last
+ * down projection ran K-split, its slices have been added only to the rows the LM head reads), 1/2 rotated q
  * hi/lo (bf16 [T][Hq*h]), 3/4 attention output hi/lo (bf16 [T][Hq*h]), 5/6 SiLU*mul output
  * hi/lo (bf16 [T][f]).  Errors: EINVAL, ENOSPC (bytes beyond the buffer), EHIP.
  */

@@ -104,6 +104,8 @@ struct synera_ctx {
   float2* cs;
   float* part_o;
   float* part_ml;
+  float* gparts;               // K-split slices of one projection: [SY_MAX_DEFERRED_SPLIT][max_tokens][max(d, q+2kv)]
+  size_t gpart_elems;          // elements of one slice slot
   // metadata staging ring
   size_t meta_cap;             // bytes per slot
   int32_t* h_meta[N_STAGE];    // pinned host
@@ -200,6 +202,8 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   const size_t o_cs = take(T * (m.head_dim / 2) * 8);
   const size_t o_po = take((size_t)c->items_cap * m.n_kv_heads * 64 * m.head_dim * 4);
   const size_t o_pml = take((size_t)c->items_cap * m.n_kv_heads * 64 * 2 * 4);
+  c->gpart_elems = T * std::max<size_t>(qkv_dim, (size_t)m.d_model);
+  const size_t o_gp = take(SY_MAX_DEFERRED_SPLIT * c->gpart_elems * 4);
   if (hipMalloc(reinterpret_cast<void**>(&c->arena), off) != hipSuccess) {
     (void)hipGetLastError();
     delete c;
@@ -224,6 +228,7 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   c->cs = reinterpret_cast<float2*>(c->arena + o_cs);
   c->part_o = reinterpret_cast<float*>(c->arena + o_po);
   c->part_ml = reinterpret_cast<float*>(c->arena + o_pml);
+  c->gparts = reinterpret_cast<float*>(c->arena + o_gp);
 
   const size_t meta_ints = (size_t)max_batch * 5 + 2 + (size_t)max_tokens + (size_t)c->max_rows +
                            (size_t)max_batch * max_pages + (size_t)max_tokens * 4 + (size_t)c->items_cap * 8 + 64;
@@ -424,9 +429,12 @@ static int32_t finish_call(synera_ctx* c, const Plan& p, hipStream_t stream) {
   return SYNERA_OK;
 }
 
+// parts / n_parts: if given and the contraction is K-split on the tall tiles, the slices are stored to
+// `parts` ([n][M][N], *n_parts = n) for the consumer kernel to add, and cbuf is left alone; otherwise
+// *n_parts = 0 and cbuf holds the result (K-split slices added with atomics).
 static int32_t run_gemm(const bf16_t* a, const bf16_t* a_lo, const void* w0, int r0, const void* w1, int r1,
                         const void* w2, int r2, void* cbuf, void* cbuf_lo, int M, int N, int K, int epi,
-                        hipStream_t s) {
+                        hipStream_t s, float* parts = nullptr, int* n_parts = nullptr) {
   GemmArgs g;
   g.a = a;
   g.a_lo = a_lo;
@@ -443,8 +451,17 @@ static int32_t run_gemm(const bf16_t* a, const bf16_t* a_lo, const void* w0, int
   g.K = K;
   g.epilogue = epi;
   g.split_k = 1;
+  g.deferred = 0;
+  g.c_parts = parts;
+  if (n_parts) *n_parts = 0;
+  if (parts && n_parts && epi != GEMM_SWIGLU_BF16 && a_lo && gemm_uses_tall_tiles(g)) g.deferred = 1;
   g.split_k = gemm_pick_split(g);
-  if (epi == GEMM_STORE_F32 && g.split_k > 1) HIP_TRY(launch_fill_zero(static_cast<float*>(cbuf), (size_t)M * N, s));
+  if (g.deferred && g.split_k > 1) {
+    *n_parts = g.split_k;
+  } else {
+    g.deferred = 0;
+    if (epi == GEMM_STORE_F32 && g.split_k > 1) HIP_TRY(launch_fill_zero(static_cast<float*>(cbuf), (size_t)M * N, s));
+  }
   HIP_TRY(launch_gemm(g, s));
   return SYNERA_OK;
 }
@@ -493,24 +510,31 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   al.hd = hd;
   al.any_split = p.any_split ? 1 : 0;
 
+  // K-split projections leave their slices in c->gparts; the kernel that reads the result next adds them
+  // (RMSNorm for the two residual projections, RoPE for QKV).  pend = slices waiting to be added to x.
+  int pend = 0;
+  const size_t x_stride = (size_t)T * d, qkv_stride = (size_t)T * (qd + 2 * kd);
   for (int l = 0; l < m.n_layers; ++l) {
     const synera_layer_weights& w = c->layers[l];
     bf16_t* k_layer = static_cast<bf16_t*>(d_k_pool) + (size_t)l * layer_elems;
     bf16_t* v_layer = static_cast<bf16_t*>(d_v_pool) + (size_t)l * layer_elems;
     {
       StageTimer t(c, SYNERA_STAGE_NORM, s);
-      HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.attn_norm), nullptr, c->y, c->y_lo, T, d, m.rms_eps,
-                             s));
+      HIP_TRY(launch_rmsnorm(c->x, c->gparts, pend, x_stride, static_cast<const bf16_t*>(w.attn_norm), nullptr, c->y,
+                             c->y_lo, T, d, m.rms_eps, s));
+      pend = 0;
     }
+    int qkv_parts = 0;
     {
       StageTimer t(c, SYNERA_STAGE_QKV, s);
       if ((st = run_gemm(c->y, c->y_lo, w.wq, qd, w.wk, kd, w.wv, kd, c->qkv, nullptr, T, qd + 2 * kd, d,
-                         GEMM_STORE_F32, s)))
+                         GEMM_STORE_F32, s, c->gparts, &qkv_parts)))
         return st;
     }
     {
       StageTimer t(c, SYNERA_STAGE_ROPE_APPEND, s);
-      HIP_TRY(launch_rope_append(c->qkv, c->cs, p.meta, c->q, c->q_lo, k_layer, v_layer, T, Hq, Hkv, hd, s));
+      HIP_TRY(launch_rope_append(qkv_parts ? c->gparts : c->qkv, qkv_parts, qkv_stride, c->cs, p.meta, c->q, c->q_lo,
+                                 k_layer, v_layer, T, Hq, Hkv, hd, s));
     }
     al.k_layer = k_layer;
     al.v_layer = v_layer;
@@ -520,13 +544,15 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
     }
     {
       StageTimer t(c, SYNERA_STAGE_O, s);
-      if ((st = run_gemm(c->o, c->o_lo, w.wo, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, qd, GEMM_ADD_F32, s)))
+      if ((st = run_gemm(c->o, c->o_lo, w.wo, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, qd, GEMM_ADD_F32, s,
+                         c->gparts, &pend)))
         return st;
     }
     {
       StageTimer t(c, SYNERA_STAGE_NORM, s);
-      HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(w.mlp_norm), nullptr, c->y, c->y_lo, T, d, m.rms_eps,
-                             s));
+      HIP_TRY(launch_rmsnorm(c->x, c->gparts, pend, x_stride, static_cast<const bf16_t*>(w.mlp_norm), nullptr, c->y,
+                             c->y_lo, T, d, m.rms_eps, s));
+      pend = 0;
     }
     {
       StageTimer t(c, SYNERA_STAGE_GATE_UP, s);
@@ -537,15 +563,16 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
     {
       StageTimer t(c, SYNERA_STAGE_DOWN, s);
       if ((st = run_gemm(c->act, c->act_lo, w.w_down, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, m.d_ffn,
-                         GEMM_ADD_F32, s)))
+                         GEMM_ADD_F32, s, c->gparts, &pend)))
         return st;
     }
   }
 
   // LM head over the draft rows (plus the last uncached row of requests that have one).
   const bool extra = p.R_all > p.R;
-  HIP_TRY(launch_rmsnorm(c->x, static_cast<const bf16_t*>(c->final_norm), p.meta.sel_rows, c->ysel, c->ysel_lo,
-                         p.R_all, d, m.rms_eps, s));
+  // (the last down projection's slices are added here, for the selected rows only)
+  HIP_TRY(launch_rmsnorm(c->x, c->gparts, pend, x_stride, static_cast<const bf16_t*>(c->final_norm), p.meta.sel_rows,
+                         c->ysel, c->ysel_lo, p.R_all, d, m.rms_eps, s));
   float* logits = (d_logits && !extra) ? d_logits : c->logits;
   {
     StageTimer t(c, SYNERA_STAGE_LM_HEAD, s);

@@ -39,11 +39,16 @@ struct BatchMeta {        // device pointers into one uploaded metadata blob (al
 
 hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, int T, int d, int vocab,
                         hipStream_t s);
-hipError_t launch_rmsnorm(const float* x, const bf16_t* gain, const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo,
-                          int n_rows, int d, float eps, hipStream_t s);
+// parts / n_parts: pending K-split slices [n_parts][T][d] of the projection that feeds the residual; the
+// kernel adds them to x first (and writes x back), so the GEMM needs no atomics.  n_parts = 0: none.
+hipError_t launch_rmsnorm(float* x, const float* parts, int n_parts, size_t part_stride, const bf16_t* gain,
+                          const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo, int n_rows, int d, float eps,
+                          hipStream_t s);
 hipError_t launch_rope_table(const BatchMeta& m, float2* cs, int T, int head_dim, float base, hipStream_t s);
-hipError_t launch_rope_append(const float* qkv, const float2* cs, const BatchMeta& m, bf16_t* q_hi, bf16_t* q_lo,
-                              bf16_t* k_layer, bf16_t* v_layer, int T, int Hq, int Hkv, int hd, hipStream_t s);
+// n_parts > 0: qkv points at K-split slices [n_parts][T][(Hq+2Hkv) hd] whose sum is the projection.
+hipError_t launch_rope_append(const float* qkv, int n_parts, size_t part_stride, const float2* cs, const BatchMeta& m,
+                              bf16_t* q_hi, bf16_t* q_lo, bf16_t* k_layer, bf16_t* v_layer, int T, int Hq, int Hkv,
+                              int hd, hipStream_t s);
 hipError_t launch_kv_append(const bf16_t* k, const bf16_t* v, const BatchMeta& m, int B, bf16_t* k_layer,
                             bf16_t* v_layer, int T, int Hkv, int hd, hipStream_t s);
 hipError_t launch_accept(const int32_t* tokens, const int32_t* anchor, const int32_t* lm_argmax, const BatchMeta& m,
@@ -102,8 +107,14 @@ struct GemmArgs {
   void* c_lo;            // SWIGLU only: low part of the bf16 output pair
   int32_t M, N, K;       // N = total output columns of the contraction (gate + up for SWIGLU)
   int32_t epilogue;
-  int32_t split_k;       // >= 1; > 1 only with STORE (pre-zeroed C) or ADD: partial sums are added atomically
+  int32_t split_k;       // >= 1; > 1 only with STORE or ADD
+  int32_t deferred;      // K-split results: 0 = added into c with fp32 atomics (STORE: c pre-zeroed);
+                         // 1 = slice z stored plainly to c_parts + z*M*N, c untouched: the consumer kernel
+                         // (RMSNorm, RoPE) adds the slices (tall tiles only; the launcher falls back to 0)
+  float* c_parts;        // deferred only: [split_k][M][N] fp32
 };
+#define SY_MAX_DEFERRED_SPLIT 8
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 int gemm_pick_split(const GemmArgs& g);
+bool gemm_uses_tall_tiles(const GemmArgs& g);   // the tile family that can defer the K-split merge
 void gemm_force_variant(int v);   // tuning hook: -1 automatic, else a tile configuration index

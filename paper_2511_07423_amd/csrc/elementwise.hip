@@ -35,16 +35,27 @@ hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, in
 // ------------------------------------------------------------------ RMSNorm
 // y = x * rsqrt(mean(x^2) + eps) * g, fp32 in, bf16 (hi, lo) pair out.  One block per
 // output row; `rows` (optional) selects which input row feeds output row r.
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x,
+// With n_parts > 0 the row first takes the pending K-split slices of the projection before it,
+// x += sum_s parts[s], and the sum is written back to x (each thread re-reads only what it wrote).
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ parts,
+                                                      int n_parts, size_t part_stride,
                                                       const bf16_t* __restrict__ gain,
                                                       const int32_t* __restrict__ rows,
                                                       bf16_t* __restrict__ y, bf16_t* __restrict__ y_lo, int d,
                                                       float eps) {
   const int r = blockIdx.x;
-  const float* src = x + (size_t)(rows ? rows[r] : r) * d;
+  const size_t row_at = (size_t)(rows ? rows[r] : r) * d;
+  float* src = x + row_at;
   float ss = 0.f;
   for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
     float4 v = *reinterpret_cast<const float4*>(src + c);
+    if (n_parts > 0) {
+      for (int s = 0; s < n_parts; ++s) {
+        const float4 pv = *reinterpret_cast<const float4*>(parts + (size_t)s * part_stride + row_at + c);
+        v.x += pv.x; v.y += pv.y; v.z += pv.z; v.w += pv.w;
+      }
+      *reinterpret_cast<float4*>(src + c) = v;
+    }
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
@@ -69,10 +80,11 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   }
 }
 
-hipError_t launch_rmsnorm(const float* x, const bf16_t* gain, const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo,
-                          int n_rows, int d, float eps, hipStream_t s) {
+hipError_t launch_rmsnorm(float* x, const float* parts, int n_parts, size_t part_stride, const bf16_t* gain,
+                          const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo, int n_rows, int d, float eps,
+                          hipStream_t s) {
   if (n_rows <= 0) return hipSuccess;
-  rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, gain, rows, y_hi, y_lo, d, eps);
+  rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
   return hipGetLastError();
 }
 
@@ -102,7 +114,8 @@ hipError_t launch_rope_table(const BatchMeta& m, float2* cs, int T, int head_dim
 // q and k are rotated on adjacent pairs; q goes to a bf16 (hi, lo) pair [T][Hq][hd]; k and v go to
 // the token's page (position t lives in page block_table[t/16], slot t%16):
 // K page [kv_head][slot][dim], V page [kv_head][dim][slot].
-__global__ __launch_bounds__(256) void rope_append_kernel(const float* __restrict__ qkv,
+__global__ __launch_bounds__(256) void rope_append_kernel(const float* __restrict__ qkv, int n_parts,
+                                                          size_t part_stride,
                                                           const float2* __restrict__ cs, BatchMeta m,
                                                           bf16_t* __restrict__ q, bf16_t* __restrict__ q_lo,
                                                           bf16_t* __restrict__ k_layer, bf16_t* __restrict__ v_layer,
@@ -117,7 +130,12 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
   const float* row = qkv + (size_t)t * (Hq + 2 * Hkv) * hd;
   for (int p = threadIdx.x; p < n_pairs; p += 256) {
     const int head = p / half, i = p % half;
-    const float2 v = *reinterpret_cast<const float2*>(row + (size_t)head * hd + 2 * i);
+    float2 v = *reinterpret_cast<const float2*>(row + (size_t)head * hd + 2 * i);
+    for (int s = 1; s < n_parts; ++s) {         // the projection arrives as K-split slices: add them
+      const float2 pv = *reinterpret_cast<const float2*>(row + (size_t)s * part_stride + (size_t)head * hd + 2 * i);
+      v.x += pv.x;
+      v.y += pv.y;
+    }
     if (head < Hq + Hkv) {
       const float2 c = cs[(size_t)t * half + i];
       const float r0 = v.x * c.x - v.y * c.y;
@@ -141,10 +159,11 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
   }
 }
 
-hipError_t launch_rope_append(const float* qkv, const float2* cs, const BatchMeta& m, bf16_t* q_hi, bf16_t* q_lo,
-                              bf16_t* k_layer, bf16_t* v_layer, int T, int Hq, int Hkv, int hd, hipStream_t s) {
+hipError_t launch_rope_append(const float* qkv, int n_parts, size_t part_stride, const float2* cs, const BatchMeta& m,
+                              bf16_t* q_hi, bf16_t* q_lo, bf16_t* k_layer, bf16_t* v_layer, int T, int Hq, int Hkv,
+                              int hd, hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  rope_append_kernel<<<T, 256, 0, s>>>(qkv, cs, m, q_hi, q_lo, k_layer, v_layer, Hq, Hkv, hd);
+  rope_append_kernel<<<T, 256, 0, s>>>(qkv, n_parts, part_stride, cs, m, q_hi, q_lo, k_layer, v_layer, Hq, Hkv, hd);
   return hipGetLastError();
 }
 

@@ -611,11 +611,15 @@ __global__ __launch_bounds__(256) void gemm_tall_kernel(GemmArgs g) {
         reinterpret_cast<bf16_t*>(g.c)[at] = (bf16_t)hi;
         reinterpret_cast<bf16_t*>(g.c_lo)[at] = (bf16_t)f2bf(v - bf2f(hi));
       } else {
-        float* c = reinterpret_cast<float*>(g.c) + (size_t)m * g.N + n0 + wave * 64 + l32;
+        const bool defer = g.deferred && g.split_k > 1;
+        float* c = (defer ? g.c_parts + (size_t)blockIdx.z * M * g.N : reinterpret_cast<float*>(g.c)) +
+                   (size_t)m * g.N + n0 + wave * 64 + l32;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
           const float v = acc[i][j][r];
-          if (g.split_k > 1) {
+          if (defer) {
+            c[j * 32] = v;
+          } else if (g.split_k > 1) {
             unsafeAtomicAdd(c + j * 32, v);
           } else if (EPI == GEMM_ADD_F32) {
             c[j * 32] += v;
@@ -698,21 +702,23 @@ static bool variant_fits(const GemmArgs& g, int v) {
 // Tall-tile plan: the row-block count MB (tile = 32 MB rows) and the K split with the least modelled time.
 // Blocks are equal-sized and one runs per compute unit, so a launch takes ceil(blocks / 256) rounds of
 //   K steps per block x (0.30 + 0.14 MB) us        (fit of MI355X timings at M = 300..1030)
-// plus, with K split, the atomic adds of the partial tiles (about 8.5 us per split per 2.2 M outputs).
+// plus, with K split, the merge of the partial tiles (atomic adds, or stores that the consumer kernel sums).
 static int tall_split(const GemmArgs& g, int mb) {
   if (g.epilogue == GEMM_SWIGLU_BF16) return 1;
   const long tiles = (long)((g.M + 32 * mb - 1) / (32 * mb)) * (g.N / 256);
   long split = 256 / tiles;
   const long most = g.K / 32 / 8;               // at least 8 K steps per slice
   split = split < most ? split : most;
+  if (g.deferred && split > SY_MAX_DEFERRED_SPLIT) split = SY_MAX_DEFERRED_SPLIT;
   return split < 1 ? 1 : (int)split;
 }
 static double tall_cost(const GemmArgs& g, int mb, int split) {
   const long tiles = (long)((g.M + 32 * mb - 1) / (32 * mb)) * (g.N / 256);
   const long rounds = (tiles * split + 255) / 256;
   const double steps = (double)(g.K / 32) / split;
-  const double atomics = split > 1 ? 8.5 * split * ((double)g.M * g.N / 2.2e6) : 0.0;
-  return rounds * steps * (0.30 + 0.14 * mb) + atomics;
+  // per K slice and 2.2 M outputs: ~8.5 us of atomic adds, or ~3 us to store the slice and read it back
+  const double merge = split > 1 ? (g.deferred ? 3.0 : 8.5) * split * ((double)g.M * g.N / 2.2e6) : 0.0;
+  return rounds * steps * (0.30 + 0.14 * mb) + merge;
 }
 static int pick_tall(const GemmArgs& g, int* split_out) {
   int best = -1, best_split = 1;
@@ -749,6 +755,8 @@ static int pick_variant(const GemmArgs& g) {
   return 8;
 }
 
+bool gemm_uses_tall_tiles(const GemmArgs& g) { return pick_variant(g) >= kFirstTall; }
+
 int gemm_pick_split(const GemmArgs& g) {
   if (g.epilogue == GEMM_SWIGLU_BF16) return 1;
   const int vi = pick_variant(g);
@@ -772,6 +780,9 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (!variant_fits(g, v) || g.K % 64 != 0 || g.split_k < 1) return hipErrorInvalidValue;
   if (v >= kFirstTall ? g.split_k > g.K / 32 : g.K % (g.split_k * 64) != 0) return hipErrorInvalidValue;
   if (v >= 11 && !g.a_lo) return hipErrorInvalidValue;
+  if (g.deferred && g.split_k > 1 &&
+      (v < kFirstTall || !g.c_parts || g.split_k > SY_MAX_DEFERRED_SPLIT || g.epilogue == GEMM_SWIGLU_BF16))
+    return hipErrorInvalidValue;
   if (g.epilogue == GEMM_SWIGLU_BF16) {
     if (g.split_k != 1 || !g.c_lo) return hipErrorInvalidValue;
   } else {
