@@ -14,8 +14,6 @@
 
 #define SY_VERSION 100
 #define N_STAGE 4              // metadata staging slots (calls may run this far ahead of the GPU)
-#define ATTN_TARGET_BLOCKS 768   // default number of attention blocks a verify aims for (splits long contexts)
-#define ATTN_TARGET_BLOCKS_MAX 8192
 
 #define HIP_TRY(expr)                       \
   do {                                      \
@@ -81,7 +79,8 @@ struct synera_ctx {
   const void* embed;
   const void* final_norm;
   const void* lm_head;
-  int32_t max_batch, max_tokens, max_pages, max_rows, items_cap, rows_per_group_tokens, attn_target_blocks;
+  int32_t max_batch, max_tokens, max_pages, max_rows, rows_per_group_tokens, attn_blocks;
+  size_t pos_cap, unit_cap, part_cap;   // capacities of the attention program, its stream shares, the partial slots
   int device;
   // device scratch (one allocation)
   char* arena;
@@ -180,13 +179,30 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   const int G = m.n_q_heads / m.n_kv_heads;
   c->rows_per_group_tokens = std::max(1, 64 / G);
   const int rg_max = (SYNERA_MAX_CHUNK + c->rows_per_group_tokens - 1) / c->rows_per_group_tokens;
-  c->attn_target_blocks = ATTN_TARGET_BLOCKS;
-  if (const char* env = getenv("SYNERA_ATTN_TARGET_BLOCKS")) {   // tuning knob
-    const long v = strtol(env, nullptr, 10);
-    if (v >= 64 && v <= ATTN_TARGET_BLOCKS_MAX) c->attn_target_blocks = (int32_t)v;
+  // Attention runs as persistent blocks, two per compute unit (80 KB of LDS each at head_dim 128).
+  {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+      (void)hipGetLastError();
+      delete c;
+      return SYNERA_EHIP;
+    }
+    c->attn_blocks = 2 * std::max(1, prop.multiProcessorCount);
+    if (const char* env = getenv("SYNERA_ATTN_BLOCKS")) {   // tuning knob
+      const long v = strtol(env, nullptr, 10);
+      if (v >= 1 && v <= 8192) c->attn_blocks = (int32_t)v;
+    }
   }
-  // key ranges are at most 1024 keys long: a request contributes <= rg_max * (keys / 1024 + 2) items
-  c->items_cap = c->attn_target_blocks + max_batch * rg_max * (max_pages * SYNERA_PAGE_SIZE / 1024 + 2);
+  // Worst case: every request at the full block table.  A stream (row group x KV head) has at most
+  // max_pages / 2 + 1 key tiles; every share of a stream adds two query positions and at most one padding
+  // position; cutting adds at most one share per block.
+  {
+    const size_t streams = (size_t)max_batch * rg_max * m.n_kv_heads;
+    const size_t tiles = (size_t)max_pages / 2 + 2;
+    c->unit_cap = streams + (size_t)c->attn_blocks;
+    c->pos_cap = streams * tiles + c->unit_cap * 4 + 2 * (size_t)c->attn_blocks;
+    c->part_cap = 2 * (size_t)c->attn_blocks;
+  }
 
   const size_t T = (size_t)max_tokens, R = (size_t)c->max_rows;
   const size_t qkv_dim = (size_t)(qd + 2 * kd);
@@ -200,8 +216,8 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   const size_t o_logits = take(R * (size_t)m.vocab * 4);
   const size_t o_ids = take(R * 4), o_p = take(R * 4), o_h = take(R * 4);
   const size_t o_cs = take(T * (m.head_dim / 2) * 8);
-  const size_t o_po = take((size_t)c->items_cap * m.n_kv_heads * 64 * m.head_dim * 4);
-  const size_t o_pml = take((size_t)c->items_cap * m.n_kv_heads * 64 * 2 * 4);
+  const size_t o_po = take(c->part_cap * 64 * m.head_dim * 4);
+  const size_t o_pml = take(c->part_cap * 64 * 2 * 4);
   c->gpart_elems = T * std::max<size_t>(qkv_dim, (size_t)m.d_model);
   const size_t o_gp = take(SY_MAX_DEFERRED_SPLIT * c->gpart_elems * 4);
   if (hipMalloc(reinterpret_cast<void**>(&c->arena), off) != hipSuccess) {
@@ -231,7 +247,8 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   c->gparts = reinterpret_cast<float*>(c->arena + o_gp);
 
   const size_t meta_ints = (size_t)max_batch * 5 + 2 + (size_t)max_tokens + (size_t)c->max_rows +
-                           (size_t)max_batch * max_pages + (size_t)max_tokens * 4 + (size_t)c->items_cap * 8 + 64;
+                           (size_t)max_batch * max_pages + c->pos_cap * 4 + c->unit_cap * 8 + (size_t)c->attn_blocks * 4 +
+                           c->part_cap * 8 + 128;
   c->meta_cap = align_up(meta_ints * 4, 256);
   for (int s = 0; s < N_STAGE; ++s) {
     c->h_meta[s] = nullptr;
@@ -274,11 +291,12 @@ extern "C" int32_t synera_destroy(synera_ctx* c) {
 // ------------------------------------------------------------------------------------ per-call plan
 struct Plan {
   BatchMeta meta;
-  const AttnItem* d_items;
-  const AttnCombine* d_comb;
-  int32_t class_begin[4];
+  const AttnPos* d_prog;
+  const AttnUnit* d_units;
+  const AttnShare* d_shares;
+  const AttnCut* d_cuts;
+  int32_t n_shares, n_cuts;
   int32_t T, R, R_all;      // chunk tokens, draft rows, LM-head rows (drafts + last-uncached rows)
-  bool any_split;
   int slot;
 };
 
@@ -311,10 +329,13 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
   h[o_cud + B] = R;
   const size_t o_bt = region((size_t)B * max_pages);
   std::memcpy(h + o_bt, block_table, (size_t)B * max_pages * sizeof(int32_t));
-  size_t o_req = 0, o_sel = 0, o_comb = 0, o_items = 0;
+  size_t o_req = 0, o_sel = 0;
   int32_t R_all = R;
-  p.any_split = false;
-  p.class_begin[0] = p.class_begin[1] = p.class_begin[2] = p.class_begin[3] = 0;
+  p.n_shares = p.n_cuts = 0;
+  p.d_prog = nullptr;
+  p.d_units = nullptr;
+  p.d_shares = nullptr;
+  p.d_cuts = nullptr;
   if (with_attention) {
     o_req = region(T);
     o_sel = region((size_t)R + B);
@@ -332,75 +353,131 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
         h[o_first + i] = -1;
       }
     }
-    at = (at + 3) & ~(size_t)3;             // 16-byte alignment for the structs
-    o_comb = region((size_t)T * 4);
-    o_items = region((size_t)c->items_cap * 8);
-
-    // Attention work items.  A row group is up to `tg` chunk tokens (x G heads <= 64 rows);
-    // its keys 0 .. L+j_last are cut into ranges of `chunk` keys (a multiple of 128).
-    const int G = c->desc.n_q_heads / c->desc.n_kv_heads;
+    // ---- attention program.  A stream = (row group of up to `tg` chunk tokens x G heads <= 64 rows, KV head)
+    // with the keys 0 .. L + j_last it sees, in 32-key tiles.  Streams of a class (more than 32 rows /
+    // up to 32 rows) are laid end to end and cut into shares of equal modelled time, one per block.
+    const int G = c->desc.n_q_heads / c->desc.n_kv_heads, Hkv = c->desc.n_kv_heads;
     const int tg = c->rows_per_group_tokens;
-    int64_t key_work = 0;
-    for (int i = 0; i < B; ++i) {
-      const int qn = n_unc[i] + n_draft[i];
-      for (int j0 = 0; j0 < qn; j0 += tg) key_work += (int64_t)ctx_len[i] + std::min(qn, j0 + tg);
-    }
-    int64_t chunk = (key_work * c->desc.n_kv_heads + c->attn_target_blocks - 1) / c->attn_target_blocks;
-    chunk = std::max<int64_t>(256, (chunk + 127) / 128 * 128);
-    chunk = std::min<int64_t>(chunk, 1024);        // the attention kernel keeps a range's page ids in 64 lanes
-    std::vector<AttnItem> items[3];
-    AttnCombine* comb = reinterpret_cast<AttnCombine*>(h + o_comb);
-    int32_t n_part = 0;
+    struct Stream { int req, tok0, j0, ntok, keys; };
+    std::vector<Stream> cls[2];                      // [0]: rbn 4, [1]: rbn 2
+    double iters[2] = {0.0, 0.0};                    // iterations of each class (every stream once per KV head)
     for (int i = 0; i < B; ++i) {
       const int qn = n_unc[i] + n_draft[i];
       for (int j0 = 0; j0 < qn; j0 += tg) {
         const int ntok = std::min(tg, qn - j0);
-        const int keys = ctx_len[i] + j0 + ntok;
-        const int nsplit = (int)((keys + chunk - 1) / chunk);
-        const int rows = ntok * G;
-        const int cls = rows <= 16 ? 0 : (rows <= 32 ? 1 : 2);
-        const int part0 = nsplit > 1 ? n_part : -1;
-        for (int s = 0; s < nsplit; ++s) {
-          AttnItem it;
-          it.req = i;
-          it.tok0 = h[o_cu + i] + j0;
-          it.j0 = j0;
-          it.ntok = ntok;
-          it.ctx_len = ctx_len[i];
-          it.key_begin = (int32_t)(s * chunk);
-          it.key_end = (int32_t)std::min<int64_t>(keys, (s + 1) * chunk);
-          it.part = nsplit > 1 ? n_part++ : -1;
-          items[cls].push_back(it);
-        }
-        for (int j = 0; j < ntok; ++j) {
-          AttnCombine& cb = comb[h[o_cu + i] + j0 + j];
-          cb.part0 = part0;
-          cb.nsplit = nsplit;
-          cb.row0 = j * G;
-          cb.pad = 0;
-        }
-        if (nsplit > 1) p.any_split = true;
+        const Stream st{i, h[o_cu + i] + j0, j0, ntok, ctx_len[i] + j0 + ntok};
+        const int k = ntok * G > 32 ? 0 : 1;
+        const int tiles = (st.keys + 31) / 32;
+        cls[k].push_back(st);
+        iters[k] += Hkv * (k == 0 ? 2 + tiles : 1 + (tiles + 1) / 2);
       }
     }
-    const size_t n_items = items[0].size() + items[1].size() + items[2].size();
-    if (n_items > (size_t)c->items_cap) return SYNERA_ENOSPC;   // cannot happen by construction of `chunk`
-    AttnItem* hi = reinterpret_cast<AttnItem*>(h + o_items);
-    size_t w = 0;
-    for (int cls = 0; cls < 3; ++cls) {
-      p.class_begin[cls] = (int32_t)w;
-      for (const AttnItem& it : items[cls]) hi[w++] = it;
+    // Time per iteration, measured on MI355X at head_dim 128 with every block busy: 1.85 us with four row
+    // blocks (one tile), 2.6 us with two row blocks x two key phases (two tiles).
+    const double t_iter[2] = {1.85, 2.6};
+    const double time_all = iters[0] * t_iter[0] + iters[1] * t_iter[1];
+    int nb[2] = {0, 0};
+    for (int k = 0; k < 2; ++k)
+      if (!cls[k].empty()) {
+        nb[k] = (int)std::lround(c->attn_blocks * iters[k] * t_iter[k] / time_all);
+        nb[k] = std::max(1, std::min(nb[k], (int)(iters[k] / 8) + 1));   // at least ~8 iterations per block
+      }
+    if (nb[0] + nb[1] > c->attn_blocks) (nb[0] > nb[1] ? nb[0] : nb[1]) -= nb[0] + nb[1] - c->attn_blocks;
+
+    at = (at + 7) & ~(size_t)7;                      // 32-byte alignment for the structs
+    // the program goes last: only its used part is uploaded
+    const size_t o_units = region(c->unit_cap * 8), o_shares = region((size_t)c->attn_blocks * 4);
+    const size_t o_cuts = region(c->part_cap * 8), o_prog = region(c->pos_cap * 4);
+    AttnPos* prog = reinterpret_cast<AttnPos*>(h + o_prog);
+    AttnUnit* units = reinterpret_cast<AttnUnit*>(h + o_units);
+    AttnShare* shares = reinterpret_cast<AttnShare*>(h + o_shares);
+    AttnCut* cuts = reinterpret_cast<AttnCut*>(h + o_cuts);
+    size_t n_pos = 0, n_units = 0, n_shares = 0, n_cuts = 0, n_part = 0;
+    for (int k = 0; k < 2; ++k) {
+      if (cls[k].empty()) continue;
+      const int rbn = k == 0 ? 4 : 2, KP = 4 / rbn, q_iters = k == 0 ? 2 : 1;
+      // Every share aims at an equal part of what is left (a cut adds the second share's query positions
+      // to the total, so the aim is renewed at each share rather than fixed up front).
+      double rest = iters[k];
+      int blocks_left = nb[k];
+      double target = rest / blocks_left + q_iters;
+      double load = 0.0;
+      size_t share_begin = n_pos;
+      auto close_share = [&]() {
+        if (n_pos > share_begin) {
+          shares[n_shares++] = AttnShare{(int32_t)share_begin, (int32_t)(n_pos - share_begin), rbn, 0};
+          --blocks_left;
+          if (blocks_left > 0) target = std::max(rest, 0.0) / blocks_left + q_iters;
+        }
+        share_begin = n_pos;
+        load = 0.0;
+      };
+      for (const Stream& st : cls[k]) {
+        const int tiles = (st.keys + 31) / 32, pages = (st.keys + SYNERA_PAGE_SIZE - 1) / SYNERA_PAGE_SIZE;
+        const int32_t* bt = block_table + (size_t)st.req * max_pages;
+        for (int kh = 0; kh < Hkv; ++kh) {
+          int t_done = 0, cut = -1;                  // cut: index into cuts[] once the stream is split
+          while (t_done < tiles) {
+            const int t_left = tiles - t_done;
+            const double room = target - load;
+            const int need_all = q_iters + (t_left + KP - 1) / KP;
+            int take = t_left;
+            if (blocks_left > 1 && need_all > room + 3.0) {    // does not fit: cut here, or start in the next block
+              const int fit = ((int)room - q_iters) * KP;
+              if (fit < 4 * KP) {
+                if (load > 0.0) {
+                  close_share();
+                  continue;
+                }
+                take = std::min(t_left, std::max(KP, ((int)target - q_iters) * KP));
+              } else {
+                take = std::min(t_left, fit);
+              }
+            }
+            const bool whole = take == tiles;
+            if (!whole && cut < 0) {
+              if (n_cuts >= c->part_cap) return SYNERA_ENOSPC;
+              cut = (int)n_cuts++;
+              cuts[cut] = AttnCut{(int32_t)n_part, 0, st.tok0, st.ntok * G, kh, {0, 0, 0}};
+            }
+            if (n_units >= c->unit_cap || n_pos + (size_t)take + 4 > c->pos_cap || n_part >= c->part_cap)
+              return SYNERA_ENOSPC;                  // cannot happen: the capacities are worst cases
+            const int t_end = t_done + take;
+            AttnUnit& u = units[n_units];
+            u = AttnUnit{st.tok0, st.ntok * G, ctx_len[st.req] + st.j0, std::min(st.keys, 32 * t_end),
+                         whole ? -1 : (int32_t)n_part, kh, {0, 0}};
+            if (!whole) {
+              ++n_part;
+              ++cuts[cut].nsplit;
+            }
+            // query positions (32 rows each; the two-phase class pads its pair), then the key tiles
+            prog[n_pos++] = AttnPos{ATTN_POS_Q | (int32_t)(n_units << 4), st.tok0, st.ntok * G, 0 | (kh << 8)};
+            if (k == 0) prog[n_pos++] = AttnPos{ATTN_POS_Q | (int32_t)(n_units << 4), st.tok0, st.ntok * G, 32 | (kh << 8)};
+            else prog[n_pos++] = AttnPos{ATTN_POS_PAD, 0, 0, 0};
+            ++n_units;
+            const size_t first_kv = n_pos;
+            for (int t = t_done; t < t_end; ++t) {
+              const int pa = bt[2 * t], pb = 2 * t + 1 < pages ? bt[2 * t + 1] : pa;
+              prog[n_pos++] = AttnPos{ATTN_POS_KV | (kh << 4), pa, pb, 32 * t};
+            }
+            if ((n_pos - first_kv) % KP) prog[n_pos++] = AttnPos{ATTN_POS_PAD, 0, 0, 0};
+            prog[n_pos - KP].tag |= ATTN_POS_LAST_BIT;       // first position of the share's last iteration
+            load += q_iters + (take + KP - 1) / KP;
+            rest -= (t_done == 0 ? q_iters : 0) + (take + KP - 1) / KP;
+            t_done = t_end;
+            if (blocks_left > 1 && load >= target - 0.5) close_share();
+          }
+        }
+      }
+      close_share();
     }
-    p.class_begin[3] = (int32_t)w;
-    // One launch takes them all, most expensive first, so the tail of the grid is short work.  Cost model
-    // (measured block times on MI355X, head_dim 128): a fixed ~9 us plus, per 32-key tile, 1.5 us for
-    // row groups of more than 32 rows (every wavefront walks every tile) and 0.9 us otherwise (two key
-    // phases in parallel).
-    auto cost = [G](const AttnItem& x) {
-      const int tiles = (x.key_end - x.key_begin + 31) / 32;
-      return x.ntok * G > 32 ? 90 + 15 * tiles : 90 + 9 * tiles;
-    };
-    std::stable_sort(hi, hi + w, [&](const AttnItem& x, const AttnItem& y) { return cost(x) > cost(y); });
-    at = o_items + w * 8;
+    p.n_shares = (int32_t)n_shares;
+    p.n_cuts = (int32_t)n_cuts;
+    p.d_prog = reinterpret_cast<const AttnPos*>(d + o_prog);
+    p.d_units = reinterpret_cast<const AttnUnit*>(d + o_units);
+    p.d_shares = reinterpret_cast<const AttnShare*>(d + o_shares);
+    p.d_cuts = reinterpret_cast<const AttnCut*>(d + o_cuts);
+    at = o_prog + n_pos * 4;
   }
   if (at * 4 > c->meta_cap) return SYNERA_ENOSPC;
   HIP_TRY(hipMemcpyAsync(d, h, at * 4, hipMemcpyHostToDevice, stream));
@@ -413,8 +490,6 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
   p.meta.tok_req = d + o_req;
   p.meta.sel_rows = d + o_sel;
   p.meta.max_pages = max_pages;
-  p.d_comb = reinterpret_cast<const AttnCombine*>(d + o_comb);
-  p.d_items = reinterpret_cast<const AttnItem*>(d + o_items);
   p.T = T;
   p.R = R;
   p.R_all = R_all;
@@ -496,11 +571,12 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   al.q = c->q;
   al.q_lo = c->q_lo;
   al.o_lo = c->o_lo;
-  al.block_table = p.meta.block_table;
-  al.max_pages = max_pages;
-  al.items = p.d_items;
-  for (int i = 0; i < 4; ++i) al.class_begin[i] = p.class_begin[i];
-  al.comb = p.d_comb;
+  al.prog = p.d_prog;
+  al.units = p.d_units;
+  al.shares = p.d_shares;
+  al.cuts = p.d_cuts;
+  al.n_shares = p.n_shares;
+  al.n_cuts = p.n_cuts;
   al.part_o = c->part_o;
   al.part_ml = c->part_ml;
   al.o = c->o;
@@ -508,7 +584,6 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   al.Hq = Hq;
   al.Hkv = Hkv;
   al.hd = hd;
-  al.any_split = p.any_split ? 1 : 0;
 
   // K-split projections leave their slices in c->gparts; the kernel that reads the result next adds them
   // (RMSNorm for the two residual projections, RoPE for QKV).  pend = slices waiting to be added to x.

@@ -61,38 +61,50 @@ hipError_t launch_confidence(const void* logits, int dtype, int64_t rows, int64_
                              int32_t* ids, float* p1, float* H, hipStream_t s);
 
 // ---------------------------------------------------------------- attention.hip
-struct AttnItem {      // one (request, row group, key range); uploaded with the metadata
-  int32_t req;         // request index
-  int32_t tok0;        // flattened index of the group's first chunk token
-  int32_t j0;          // its index inside the request's chunk
-  int32_t ntok;        // chunk tokens in the group (rows = ntok * G <= 64)
-  int32_t ctx_len;     // L_i
-  int32_t key_begin;   // multiple of 32
-  int32_t key_end;     // exclusive, <= L_i + j0 + ntok
-  int32_t part;        // partial-result slot, or -1: this item is the only split and writes o
+// The attention work of one call is a flat program of tile positions, cut into one share per persistent block.
+enum { ATTN_POS_PAD = 0, ATTN_POS_KV = 1, ATTN_POS_Q = 2 };
+#define ATTN_POS_KIND_MASK 7
+#define ATTN_POS_LAST_BIT 8     // on the first position of an iteration: the stream's share ends with this iteration
+struct AttnPos {       // 16 bytes, read with one scalar load
+  int32_t tag;         // kind | LAST bit | payload << 4 (KV: KV head; Q: unit index)
+  int32_t a;           // KV: page of keys 0..15 of the tile;  Q: flattened index of the group's first chunk token
+  int32_t b;           // KV: page of keys 16..31 (or `a` again past the end);  Q: rows of the group (tokens x G)
+  int32_t c;           // KV: first key of the tile;  Q: first of the 32 rows this position carries | KV head << 8
 };
-struct AttnCombine {   // per chunk token: where its partials live
-  int32_t part0;       // first partial slot of its row group, -1 if written directly
-  int32_t nsplit;
-  int32_t row0;        // (j - j0) * G: first row of this token inside the group
+struct AttnUnit {      // one stream's share inside one block; 32 bytes, read with one scalar load
+  int32_t tok0;        // flattened index of the group's first chunk token
+  int32_t nrows;       // tokens x G (<= 64)
+  int32_t lim0;        // last key the group's first token may see: L_i + j0 (row r: lim0 + r / G)
+  int32_t key_end;     // exclusive end of this share's keys (the stream's end, or a multiple of 32)
+  int32_t part;        // partial-result slot, or -1: the stream is whole here and writes o
+  int32_t kh;          // KV head
+  int32_t pad[2];
+};
+struct AttnShare {     // what one persistent block executes
+  int32_t pos_begin, n_pos;   // its slice of the program (n_pos a multiple of 4 / rbn)
+  int32_t rbn;                // 4: groups of more than 32 rows, 2: up to 32 rows
   int32_t pad;
+};
+struct AttnCut {       // a stream whose keys were split over several blocks
+  int32_t part0, nsplit;      // its partial slots
+  int32_t tok0, nrows, kh;
+  int32_t pad[3];
 };
 struct AttnLaunch {
   const bf16_t* q;           // [T][Hq][hd], high part of the (hi, lo) bf16 pair
   const bf16_t* q_lo;        // low part
   const bf16_t* k_layer;     // pool of this layer
   const bf16_t* v_layer;
-  const int32_t* block_table;
-  int32_t max_pages;
-  const AttnItem* items;     // device; items of row-block class c are items[class_begin[c] .. class_begin[c+1])
-  int32_t class_begin[4];    // classes: rows <= 16, <= 32, <= 64
-  const AttnCombine* comb;   // [T]
-  float* part_o;             // [slots][Hkv][64][hd]
-  float* part_ml;            // [slots][Hkv][64][2]
+  const AttnPos* prog;       // device
+  const AttnUnit* units;
+  const AttnShare* shares;
+  const AttnCut* cuts;
+  int32_t n_shares, n_cuts;
+  float* part_o;             // [slots][64][hd]
+  float* part_ml;            // [slots][64][2]
   bf16_t* o;                 // [T][Hq][hd], high part of the output pair
   bf16_t* o_lo;              // low part
   int32_t T, Hq, Hkv, hd;
-  int32_t any_split;
 };
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
 
