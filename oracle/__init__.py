@@ -18,12 +18,13 @@ state), widened exactly.
 
 Pins (tests/test_oracle_*.py): chunked == sequential == full prefill, paging and
 batch invariance, accept-rule properties and brute force, softmax/entropy closed
-forms, attention/RoPE/RMSNorm special cases, an independently written dense
+forms, top-k / margin / dispatch-probability closed forms and brute force, attention/RoPE/RMSNorm special cases, an independently written dense
 float64 decoder on the tiny config, and the capped-geometric expected accept
 length.  No function here is "parity unpinned".
 """
 from .numerics import bf16_round, bf16_bits, bf16_from_bits  # noqa: F401
 from .confidence import confidence_row, confidence  # noqa: F401
+from .dispatch import softmax_probs, topk_row, topk, margin_row, p_conf, p_imp, chunk_dispatch  # noqa: F401
 from .decoder import (  # noqa: F401
     OracleModel, PagedKV, rmsnorm, rope, attention_one_query, decode_token, forward_tokens,
     lm_head,

@@ -1,0 +1,87 @@
+"""Pins of the oracle's selective-offloading statistics (top-k compression, margin score, dispatch
+probabilities) against what the paper's equations and the mathematics fix."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+
+
+def test_p_conf_closed_forms_of_the_first_dispatch_equation():
+    # Section 4.2: 1 at or below the threshold; just above it norm = -1/2 -> 1 / (1 + e^-5); at c = 1
+    # norm = +1/2 -> 1 / (1 + e^5); k = 10
+    for c_th in (0.7, 0.8, 0.95):
+        assert oracle.p_conf(c_th, c_th) == 1.0
+        assert oracle.p_conf(0.0, c_th) == 1.0
+        assert oracle.p_conf(c_th + 1e-12, c_th) == pytest.approx(1 / (1 + math.exp(-5)), abs=1e-9)
+        assert oracle.p_conf(1.0, c_th) == pytest.approx(1 / (1 + math.exp(5)), abs=1e-12)
+        mid = (1 + c_th) / 2                       # norm = 0 -> 1/2
+        assert oracle.p_conf(mid, c_th) == pytest.approx(0.5, abs=1e-12)
+    assert 1 / (1 + math.exp(-5)) == pytest.approx(0.99331, abs=1e-5)
+    assert 1 / (1 + math.exp(5)) == pytest.approx(0.00669, abs=1e-5)
+    # monotone non-increasing in c, slope parameter: k = 0 flattens the sigmoid to 1/2
+    cs = np.linspace(0.0, 1.0, 201)
+    v = [oracle.p_conf(c, 0.7) for c in cs]
+    assert all(a >= b - 1e-15 for a, b in zip(v, v[1:]))
+    assert oracle.p_conf(0.9, 0.7, k=0.0) == 0.5
+
+
+def test_p_imp_three_tiers_of_the_second_dispatch_equation():
+    i_th = 0.4
+    assert oracle.p_imp(0.0, i_th) == 0.0 and oracle.p_imp(i_th / 2, i_th) == 0.0
+    assert oracle.p_imp(i_th * 1.0001, i_th) == 1.0 and oracle.p_imp(5.0, i_th) == 1.0
+    # theta = -10: just above i_th/2 norm = -1/2 -> 1 / (1 + e^5); at i_th norm = +1/2 -> 1 / (1 + e^-5)
+    assert oracle.p_imp(i_th / 2 + 1e-12, i_th) == pytest.approx(1 / (1 + math.exp(5)), abs=1e-9)
+    assert oracle.p_imp(i_th, i_th) == pytest.approx(1 / (1 + math.exp(-5)), abs=1e-12)
+    assert oracle.p_imp(0.75 * i_th, i_th) == pytest.approx(0.5, abs=1e-12)
+    v = [oracle.p_imp(i, i_th) for i in np.linspace(0, 1, 301)]
+    assert all(a <= b + 1e-15 for a, b in zip(v, v[1:]))          # non-decreasing in i
+
+
+def test_topk_against_numpy_sort_and_the_plain_confidence_functions():
+    rng = np.random.default_rng(3)
+    for V, k in ((7, 3), (50, 8), (1000, 5), (4096, 1)):
+        x = rng.normal(0, 3, V)
+        ids, p = oracle.topk_row(x, k)
+        order = np.argsort(-x, kind="stable")[:k]
+        assert np.array_equal(ids, order)
+        full = np.exp(x - x.max()); full /= full.sum()
+        assert np.allclose(p, full[order], rtol=1e-13, atol=0)
+        idx, p1, _, _ = oracle.confidence_row(x)
+        assert ids[0] == idx and p[0] == pytest.approx(p1, rel=1e-13)
+        assert np.all(np.diff(p) <= 0)
+    # k = V: the compressed distribution is the whole one
+    x = rng.normal(0, 1, 33)
+    ids, p = oracle.topk_row(x, 33)
+    assert sorted(ids.tolist()) == list(range(33)) and p.sum() == pytest.approx(1.0, abs=1e-13)
+
+
+def test_topk_ties_go_to_the_lower_id_and_margin_closed_forms():
+    ids, p = oracle.topk_row([1.0, 3.0, 3.0, 0.0, 3.0], 4)
+    assert ids.tolist() == [1, 2, 4, 0]
+    assert p[0] == p[1] == p[2]
+    assert oracle.margin_row([1.0, 3.0, 3.0]) == 0.0
+    # two-token vocabulary with logit gap d: p1 - p2 = tanh(d / 2)
+    for d in (0.0, 0.3, 2.0, 9.0):
+        assert oracle.margin_row([0.0, d]) == pytest.approx(math.tanh(d / 2), abs=1e-14)
+    # uniform logits: every probability 1/V, margin 0; one-hot limit: margin -> 1
+    ids, p, mg = oracle.topk(np.zeros((2, 64)), 4)
+    assert np.allclose(p, 1 / 64) and np.all(mg == 0) and ids.tolist() == [[0, 1, 2, 3]] * 2
+    x = np.zeros(100); x[17] = 60.0
+    assert oracle.margin_row(x) == pytest.approx(1.0, abs=1e-20 + 1e-12)
+    # shift invariance
+    y = np.random.default_rng(1).normal(0, 2, 300)
+    a = oracle.topk_row(y, 6); b = oracle.topk_row(y + 77.0, 6)
+    assert np.array_equal(a[0], b[0]) and np.allclose(a[1], b[1], rtol=1e-12)
+
+
+def test_chunk_dispatch_means_and_probabilities():
+    p1 = np.array([0.9, 0.8, 1.0, 0.2, 0.95, 0.95, 0.95, 0.5])
+    cu = np.array([0, 3, 4, 4, 7, 8])
+    mean, pc = oracle.chunk_dispatch(p1, cu, c_th=0.7)
+    assert np.allclose(mean, [0.9, 0.2, 0.0, 0.95, 0.5])
+    want = [oracle.p_conf(0.9, 0.7), 1.0, 1.0, oracle.p_conf(0.95, 0.7), 1.0]
+    assert np.allclose(pc, want, rtol=0, atol=1e-15)
+    # c = 0.9 with c_th = 0.7: norm = 2/3 - 1/2 = 1/6 -> 1 / (1 + e^(10/6))
+    assert pc[0] == pytest.approx(1 / (1 + math.exp(10 / 6)), abs=1e-12)
