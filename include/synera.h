@@ -188,6 +188,33 @@ int32_t synera_confidence(const void* d_logits, int32_t dtype, int64_t rows, int
                           float* d_entropy, void* stream);
 
 /*
+ * The same vocabulary pass, keeping the k <= 8 most probable tokens of each row: the compressed
+ * form of a distribution that is transmitted instead of the full vector (Section 4.2,
+ * "Compression before transmission": top-1 / top-k of the sampling method in use), and the
+ * margin score, top-1 minus top-2 probability, that drives the layer-wise early exit
+ * (Section 4.3).  d_logits / dtype / rows / vocab / row_stride_elems as synera_confidence.
+ * Outputs, device: d_topk_id i32 [rows][k] and d_topk_prob f32 [rows][k], most probable first,
+ * equal logits by the lower token id first; d_margin f32 [rows] (NULL to skip), d_entropy f32
+ * [rows] in nats (NULL to skip).  A row with fewer than k comparable entries (NaN) reports id 0,
+ * probability 0 for the missing ones.  Errors: EINVAL; EUNSUP for k > 8 or k > vocab; EHIP.
+ */
+int32_t synera_confidence_topk(const void* d_logits, int32_t dtype, int64_t rows, int64_t vocab,
+                               int64_t row_stride_elems, int32_t k, int32_t* d_topk_id,
+                               float* d_topk_prob, float* d_margin, float* d_entropy, void* stream);
+
+/*
+ * Dispatch probability of token chunks from their confidence (Section 4.2, first equation):
+ * chunk b owns rows d_cu_rows[b] .. d_cu_rows[b+1]-1 of d_top1_prob (device, i32 [B+1] prefix
+ * sums and f32 per-row top-1 probabilities, e.g. synera_verify's or synera_confidence's
+ * output); c_b = their mean (0 for an empty chunk), P_conf(c) = 1 for c <= c_th, else
+ * 1 / (1 + exp(k_slope * ((c - c_th) / (1 - c_th) - 1/2))); the paper uses k_slope = 10 and
+ * c_th in [0.7, 1).  Outputs device f32 [B].  Errors: EINVAL (c_th outside [0, 1), null
+ * pointers), EHIP.
+ */
+int32_t synera_chunk_dispatch(const float* d_top1_prob, const int32_t* d_cu_rows, int32_t B, float c_th,
+                              float k_slope, float* d_mean_conf, float* d_p_conf, void* stream);
+
+/*
  * Scatter K/V rows of one layer into the paged pools: request i appends n_new_i
  * rows at positions L_i .. L_i+n_new_i-1 (what the partial prefill does for
  * every forwarded token, Section 3.4; exported so a prefill engine or a test

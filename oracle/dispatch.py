@@ -45,7 +45,7 @@ def topk(logits, k, dtype=np.float64):
     mg = np.empty(R, np.float64)
     for r in range(R):
         ids[r], pr[r] = topk_row(logits[r], k, dtype)
-        mg[r] = pr[r, 0] - pr[r, 1] if k > 1 else pr[r, 0]
+        mg[r] = pr[r, 0] - pr[r, 1] if k > 1 else margin_row(logits[r], dtype)   # the margin is p1 - p2 whatever k is
     return ids, pr, mg
 
 

@@ -62,6 +62,10 @@ _lib.synera_verify.argtypes = [_vp, C.c_int32, _i32p, _i32p, _i32p, _vp, _vp, _i
                                _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.synera_confidence.restype = C.c_int32
 _lib.synera_confidence.argtypes = [_vp, C.c_int32, C.c_int64, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp]
+_lib.synera_confidence_topk.restype = C.c_int32
+_lib.synera_confidence_topk.argtypes = [_vp, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _vp, _vp, _vp, _vp, _vp]
+_lib.synera_chunk_dispatch.restype = C.c_int32
+_lib.synera_chunk_dispatch.argtypes = [_vp, _vp, C.c_int32, C.c_float, C.c_float, _vp, _vp, _vp]
 _lib.synera_kv_append.restype = C.c_int32
 _lib.synera_kv_append.argtypes = [_vp, C.c_int32, C.c_int32, _i32p, _i32p, _vp, _vp, _i32p, C.c_int32, C.c_int32,
                                   _vp, _vp, _vp]
@@ -143,6 +147,36 @@ def confidence(logits, want_prob=True, want_entropy=True):
                                 ids.data_ptr(), _dev(p), _dev(h), _stream())
     _check(st, "synera_confidence")
     return ids, p, h
+
+
+def confidence_topk(logits, k, want_margin=True, want_entropy=True):
+    """Per row of a 2-D f32 or bf16 GPU tensor: (top-k ids int32 [rows,k], their probabilities f32 [rows,k],
+    margin p1 - p2 f32 [rows] or None, entropy f32 [rows] or None)."""
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be 2-D with unit column stride")
+    dt = {torch.float32: 0, torch.bfloat16: 1}[logits.dtype]
+    rows, vocab = logits.shape
+    dev = logits.device
+    ids = torch.empty((rows, k), dtype=torch.int32, device=dev)
+    pr = torch.empty((rows, k), dtype=torch.float32, device=dev)
+    mg = torch.empty(rows, dtype=torch.float32, device=dev) if want_margin else None
+    h = torch.empty(rows, dtype=torch.float32, device=dev) if want_entropy else None
+    st = _lib.synera_confidence_topk(logits.data_ptr(), dt, rows, vocab, logits.stride(0) if rows > 1 else vocab, k,
+                                     ids.data_ptr(), pr.data_ptr(), _dev(mg), _dev(h), _stream())
+    _check(st, "synera_confidence_topk")
+    return ids, pr, mg, h
+
+
+def chunk_dispatch(top1_prob, cu_rows, c_th, k_slope=10.0):
+    """(mean confidence f32 [B], P_conf f32 [B]) of the chunks cu_rows[b] .. cu_rows[b+1] of per-row top-1
+    probabilities; both arguments GPU tensors (f32 [rows], int32 [B+1])."""
+    B = cu_rows.numel() - 1
+    mean = torch.empty(max(B, 0), dtype=torch.float32, device=top1_prob.device)
+    pc = torch.empty_like(mean)
+    st = _lib.synera_chunk_dispatch(_dev(top1_prob, torch.float32), _dev(cu_rows, torch.int32), B, float(c_th),
+                                    float(k_slope), mean.data_ptr(), pc.data_ptr(), _stream())
+    _check(st, "synera_chunk_dispatch")
+    return mean, pc
 
 
 def gemm_bf16(a, w, a_lo=None, out=None):

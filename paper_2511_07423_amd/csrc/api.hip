@@ -711,6 +711,31 @@ extern "C" int32_t synera_confidence(const void* d_logits, int32_t dtype, int64_
   return SYNERA_OK;
 }
 
+extern "C" int32_t synera_confidence_topk(const void* d_logits, int32_t dtype, int64_t rows, int64_t vocab,
+                                          int64_t row_stride_elems, int32_t k, int32_t* d_topk_id,
+                                          float* d_topk_prob, float* d_margin, float* d_entropy, void* stream) {
+  if (rows < 0 || vocab < 1 || (dtype != 0 && dtype != 1) || k < 1) return SYNERA_EINVAL;
+  if (k > 8 || k > vocab) return SYNERA_EUNSUP;
+  if (rows == 0) return SYNERA_OK;
+  if (!d_logits || !d_topk_id || !d_topk_prob || row_stride_elems < vocab) return SYNERA_EINVAL;
+  if (rows > 0x7FFFFFFF / 8 || vocab > 0x7FFFFFFF) return SYNERA_EINVAL;
+  const int64_t align = dtype == 1 ? 8 : 4;
+  if (row_stride_elems % align != 0 || (reinterpret_cast<uintptr_t>(d_logits) & 15) != 0) return SYNERA_EINVAL;
+  HIP_TRY(launch_confidence_topk(d_logits, dtype, rows, vocab, row_stride_elems, k, d_topk_id, d_topk_prob, d_margin,
+                                 d_entropy, static_cast<hipStream_t>(stream)));
+  return SYNERA_OK;
+}
+
+extern "C" int32_t synera_chunk_dispatch(const float* d_top1_prob, const int32_t* d_cu_rows, int32_t B, float c_th,
+                                         float k_slope, float* d_mean_conf, float* d_p_conf, void* stream) {
+  if (B < 0 || !(c_th >= 0.0f && c_th < 1.0f)) return SYNERA_EINVAL;
+  if (B == 0) return SYNERA_OK;
+  if (!d_top1_prob || !d_cu_rows || !d_mean_conf || !d_p_conf) return SYNERA_EINVAL;
+  HIP_TRY(launch_chunk_dispatch(d_top1_prob, d_cu_rows, B, c_th, k_slope, d_mean_conf, d_p_conf,
+                                static_cast<hipStream_t>(stream)));
+  return SYNERA_OK;
+}
+
 // ------------------------------------------------------------------------------------ kv append
 extern "C" int32_t synera_kv_append(synera_ctx* c, int32_t layer, int32_t B, const int32_t* h_ctx_len,
                                     const int32_t* h_n_new, const void* d_k, const void* d_v,

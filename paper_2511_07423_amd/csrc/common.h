@@ -60,6 +60,11 @@ hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
 hipError_t launch_confidence(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride,
                              int32_t* ids, float* p1, float* H, hipStream_t s);
 
+hipError_t launch_confidence_topk(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride, int k,
+                                  int32_t* ids, float* probs, float* margin, float* H, hipStream_t s);
+hipError_t launch_chunk_dispatch(const float* p1, const int32_t* cu_rows, int B, float c_th, float k_slope,
+                                 float* mean_conf, float* p_conf, hipStream_t s);
+
 // ---------------------------------------------------------------- attention.hip
 // The attention work of one call is a flat program of tile positions, cut into one share per persistent block.
 enum { ATTN_POS_PAD = 0, ATTN_POS_KV = 1, ATTN_POS_Q = 2 };

@@ -119,6 +119,186 @@ __global__ __launch_bounds__(256) void confidence_kernel(const void* __restrict_
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same pass, keeping the k <= 8 most probable tokens of the row as well: the compressed form of a
+// distribution that is transmitted instead of the full vector (Section 4.2, "Compression before
+// transmission"), and the margin score p_top1 - p_top2 of the layer-wise early exit (Section 4.3).
+// Each WAVEFRONT keeps the 8 best (logit, id) it has seen, sorted (equal logits: lower id first), the
+// same in all its lanes.  An element is looked at more closely only if it is not below the list's last
+// entry: a ballot finds such lanes, their values are broadcast one by one and inserted.  Over a row a
+// wavefront meets about 8 ln(n / 8) such elements, so the common path costs one compare and one ballot
+// per element.  (Per-thread lists cost ten times more: with 64 lanes in lockstep nearly every 16-byte
+// chunk has some lane that must insert.)  After the row the four lists are merged by one thread.
+#define TOPK_MAX 8
+
+struct TopEntry {
+  float v;
+  int id;
+};
+__device__ __forceinline__ bool top_before(float va, int ia, float vb, int ib) { return va > vb || (va == vb && ia < ib); }
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void confidence_topk_kernel(const void* __restrict__ logits, int64_t vocab,
+                                                              int64_t stride, int k, int32_t* __restrict__ ids,
+                                                              float* __restrict__ probs, float* __restrict__ margin,
+                                                              float* __restrict__ H) {
+  constexpr int VEC = BF16 ? 8 : 4;
+  const int64_t row = blockIdx.x;
+  const char* base = reinterpret_cast<const char*>(logits) + row * stride * (BF16 ? 2 : 4);
+  const uint4* src = reinterpret_cast<const uint4*>(base);
+  const int n_vec = (int)(vocab / VEC);
+  ConfState st = {-1e30f, 0.f, 0.f, 0};
+  float tv[TOPK_MAX];                                // wavefront-uniform
+  int ti[TOPK_MAX];
+#pragma unroll
+  for (int i = 0; i < TOPK_MAX; ++i) {
+    tv[i] = -INFINITY;
+    ti[i] = 0x7FFFFFFF;
+  }
+  // v, id: this lane's element; lanes whose element is not below the list's last entry get a closer look
+  auto offer = [&](float v, int id) {
+    unsigned long long mask = __builtin_amdgcn_ballot_w64(v >= tv[TOPK_MAX - 1]);
+    while (mask) {                                   // wavefront-uniform loop
+      const int l = __builtin_ctzll(mask);
+      mask &= mask - 1;
+      const float cv = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), l));
+      const int ci = __builtin_amdgcn_readlane(id, l);
+      if (!top_before(cv, ci, tv[TOPK_MAX - 1], ti[TOPK_MAX - 1])) continue;
+      tv[TOPK_MAX - 1] = cv;
+      ti[TOPK_MAX - 1] = ci;
+#pragma unroll
+      for (int i = TOPK_MAX - 1; i > 0; --i) {
+        if (top_before(tv[i], ti[i], tv[i - 1], ti[i - 1])) {
+          const float fv = tv[i]; tv[i] = tv[i - 1]; tv[i - 1] = fv;
+          const int fi = ti[i]; ti[i] = ti[i - 1]; ti[i - 1] = fi;
+        }
+      }
+    }
+  };
+  auto consume = [&](const uint4& raw, int c) {
+    float v[VEC];
+    if constexpr (BF16) {
+      v[0] = bf2f(raw.x & 0xFFFF); v[1] = bf2f(raw.x >> 16);
+      v[2] = bf2f(raw.y & 0xFFFF); v[3] = bf2f(raw.y >> 16);
+      v[4] = bf2f(raw.z & 0xFFFF); v[5] = bf2f(raw.z >> 16);
+      v[6] = bf2f(raw.w & 0xFFFF); v[7] = bf2f(raw.w >> 16);
+    } else {
+      v[0] = __uint_as_float(raw.x); v[1] = __uint_as_float(raw.y);
+      v[2] = __uint_as_float(raw.z); v[3] = __uint_as_float(raw.w);
+    }
+    float cmax = v[0];
+#pragma unroll
+    for (int i = 1; i < VEC; ++i) cmax = fmaxf(cmax, v[i]);
+    if (__builtin_amdgcn_ballot_w64(cmax >= tv[TOPK_MAX - 1]) != 0) {   // some lane of the wavefront has a candidate
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) offer(v[i], c * VEC + i);
+    }
+    conf_chunk<VEC>(st, v, c * VEC);
+  };
+  // One 16-byte chunk per lane and round, all lanes of a wavefront in the same round: the lanes that hold
+  // data must meet in the same ballot (an unrolled loop whose last trip only some lanes take would split
+  // them).  In the last round the lanes past the end of the row just sit out; lane 0 of a wavefront is
+  // active whenever any of its lanes is, and its list is the one used.
+  for (int c = threadIdx.x; c < n_vec; c += 256) consume(src[c], c);
+  {
+    const int64_t tail0 = (int64_t)n_vec * VEC;
+    const int n_tail = (int)(vocab - tail0);         // < VEC
+    if (n_tail > 0) {                                // block-uniform
+      const int e = threadIdx.x;
+      float v[1] = {-INFINITY};
+      if (e < n_tail)
+        v[0] = BF16 ? bf2f(reinterpret_cast<const bf16_t*>(base)[tail0 + e]) : reinterpret_cast<const float*>(base)[tail0 + e];
+      offer(e < n_tail ? v[0] : -INFINITY, e < n_tail ? (int)(tail0 + e) : 0x7FFFFFFF);
+      if (e < n_tail) conf_chunk<1>(st, v, (int)(tail0 + e));
+    }
+  }
+
+  // row statistics (m, Z, S)
+  for (int o = 1; o < 64; o <<= 1) {
+    ConfState other;
+    other.m = __shfl_xor(st.m, o);
+    other.Z = __shfl_xor(st.Z, o);
+    other.S = __shfl_xor(st.S, o);
+    other.id = __shfl_xor(st.id, o);
+    conf_merge(st, other);
+  }
+  __shared__ ConfState red[4];
+  __shared__ TopEntry cand[4][TOPK_MAX];
+  if ((threadIdx.x & 63) == 0) {
+    red[threadIdx.x >> 6] = st;
+#pragma unroll
+    for (int i = 0; i < TOPK_MAX; ++i) cand[threadIdx.x >> 6][i] = TopEntry{tv[i], ti[i]};
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    ConfState a = red[0];
+    conf_merge(a, red[1]);
+    conf_merge(a, red[2]);
+    conf_merge(a, red[3]);
+    if (H) H[row] = logf(a.Z) - a.S / a.Z;
+    // merge the four sorted lists: k rounds of "best head"
+    int head[4] = {0, 0, 0, 0};
+    float p_first = 0.f, p_second = 0.f;
+    const int rounds = k > 2 ? k : 2;                // the margin needs the two best whatever k is
+    for (int r = 0; r < rounds; ++r) {
+      int best = -1;
+      for (int w = 0; w < 4; ++w) {
+        if (head[w] >= TOPK_MAX) continue;
+        const TopEntry e = cand[w][head[w]];
+        if (best < 0 || top_before(e.v, e.id, cand[best][head[best]].v, cand[best][head[best]].id)) best = w;
+      }
+      const TopEntry wn = best >= 0 ? cand[best][head[best]] : TopEntry{-INFINITY, 0x7FFFFFFF};
+      if (best >= 0) ++head[best];
+      const bool have = wn.id != 0x7FFFFFFF;         // false only for a row with fewer than r+1 comparable entries
+      const float pr = have ? fast_exp2((wn.v - a.m) * LOG2E) / a.Z : 0.f;
+      if (r < k) {
+        ids[row * k + r] = have ? wn.id : 0;
+        probs[row * k + r] = pr;
+      }
+      if (r == 0) p_first = pr;
+      if (r == 1) p_second = pr;
+    }
+    if (margin) margin[row] = p_first - p_second;
+  }
+}
+
+hipError_t launch_confidence_topk(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride, int k,
+                                  int32_t* ids, float* probs, float* margin, float* H, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (dtype == 1)
+    confidence_topk_kernel<true><<<(unsigned)rows, 256, 0, s>>>(logits, vocab, stride, k, ids, probs, margin, H);
+  else
+    confidence_topk_kernel<false><<<(unsigned)rows, 256, 0, s>>>(logits, vocab, stride, k, ids, probs, margin, H);
+  return hipGetLastError();
+}
+
+// Mean confidence of each chunk (rows cu_rows[b] .. cu_rows[b+1]) and its dispatch probability, the scaled
+// sigmoid of Section 4.2: 1 for c <= c_th, else 1 / (1 + exp(k (c - c_th) / (1 - c_th) - k / 2)).
+__global__ void chunk_dispatch_kernel(const float* __restrict__ p1, const int32_t* __restrict__ cu_rows, int B,
+                                      float c_th, float k_slope, float* __restrict__ mean_conf,
+                                      float* __restrict__ p_conf) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int r0 = cu_rows[b], r1 = cu_rows[b + 1];
+  float sum = 0.f;
+  for (int r = r0; r < r1; ++r) sum += p1[r];
+  const float c = r1 > r0 ? sum / (float)(r1 - r0) : 0.f;
+  mean_conf[b] = c;
+  float pc = 1.0f;
+  if (c > c_th) {
+    const float norm = (c - c_th) / (1.0f - c_th) - 0.5f;
+    pc = 1.0f / (1.0f + expf(k_slope * norm));
+  }
+  p_conf[b] = pc;
+}
+
+hipError_t launch_chunk_dispatch(const float* p1, const int32_t* cu_rows, int B, float c_th, float k_slope,
+                                 float* mean_conf, float* p_conf, hipStream_t s) {
+  if (B <= 0) return hipSuccess;
+  chunk_dispatch_kernel<<<(B + 127) / 128, 128, 0, s>>>(p1, cu_rows, B, c_th, k_slope, mean_conf, p_conf);
+  return hipGetLastError();
+}
+
 hipError_t launch_confidence(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride,
                              int32_t* ids, float* p1, float* H, hipStream_t s) {
   if (rows <= 0) return hipSuccess;

@@ -42,6 +42,10 @@ def confidence():
         print(json.dumps({"kernel": "synera_confidence", "rows": shapes.C5B_ROWS, "vocab": shapes.C5B_VOCAB,
                           "dtype": name, "bytes": nbytes, "avg_launch_ms": ms, "bound": "hbm",
                           "achieved_GBs": nbytes / ms / 1e6, "peak_GBs": 8000.0, "frac": nbytes / ms / 1e6 / 8000.0}))
+        ms = _time(lambda: synera.confidence_topk(x, 8))
+        print(json.dumps({"kernel": "synera_confidence_topk (k = 8)", "rows": shapes.C5B_ROWS, "vocab": shapes.C5B_VOCAB,
+                          "dtype": name, "bytes": nbytes, "avg_launch_ms": ms, "bound": "hbm",
+                          "achieved_GBs": nbytes / ms / 1e6, "peak_GBs": 8000.0, "frac": nbytes / ms / 1e6 / 8000.0}))
 
 
 def gemm():

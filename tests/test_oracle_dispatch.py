@@ -70,6 +70,10 @@ def test_topk_ties_go_to_the_lower_id_and_margin_closed_forms():
     assert np.allclose(p, 1 / 64) and np.all(mg == 0) and ids.tolist() == [[0, 1, 2, 3]] * 2
     x = np.zeros(100); x[17] = 60.0
     assert oracle.margin_row(x) == pytest.approx(1.0, abs=1e-20 + 1e-12)
+    # the margin of topk() is top-1 minus top-2 whatever k is
+    z = np.random.default_rng(2).normal(0, 2, (3, 50))
+    assert np.array_equal(oracle.topk(z, 1)[2], oracle.topk(z, 5)[2])
+    assert oracle.topk(z, 1)[2][0] == oracle.margin_row(z[0])
     # shift invariance
     y = np.random.default_rng(1).normal(0, 2, 300)
     a = oracle.topk_row(y, 6); b = oracle.topk_row(y + 77.0, 6)
