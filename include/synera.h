@@ -284,6 +284,17 @@ int32_t synera_debug_gemm_epilogue(const void* d_a, const void* d_a_lo, const vo
                                    void* stream);
 
 /*
+ * Test hook: the store-form projection GEMM (epilogue 0 above) in the mode the decoder layers run it in:
+ * when the tile planner splits K, slice s of the product is stored to d_parts[s][M][N] (f32) for the
+ * consumer kernel to add, in a fixed order and without atomics.  d_parts must hold SYNERA_MAX_GEMM_SLICES
+ * x M x N floats; *h_n_parts (host) receives the number of slices written (1 when K was not split: the
+ * whole product is then in slice 0).  N % 128 == 0, K % 64 == 0, else EUNSUP.
+ */
+#define SYNERA_MAX_GEMM_SLICES 8
+int32_t synera_debug_gemm_deferred(const void* d_a, const void* d_a_lo, const void* d_w, float* d_parts,
+                                   int32_t M, int32_t N, int32_t K, int32_t* h_n_parts, void* stream);
+
+/*
  * Test hook: copy one of the context's intermediate buffers, as the LAST layer of the last
  * verify left it, to caller device memory.  which: 0 residual x (f32 [T][d]; when the last
  * down projection ran K-split, its slices have been added only to the rows the LM head reads), 1/2 rotated q

@@ -79,6 +79,8 @@ _lib.synera_debug_read_scratch.restype = C.c_int32
 _lib.synera_debug_read_scratch.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp]
 _lib.synera_debug_set_gemm_tile.restype = C.c_int32
 _lib.synera_debug_set_gemm_tile.argtypes = [C.c_int32]
+_lib.synera_debug_gemm_deferred.restype = C.c_int32
+_lib.synera_debug_gemm_deferred.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), _vp]
 _lib.synera_debug_gemm_epilogue.restype = C.c_int32
 _lib.synera_debug_gemm_epilogue.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp]
 
@@ -198,6 +200,18 @@ def debug_gemm_epilogue(a, a_lo, w0, w1, c, c_lo, epilogue):
                                          _dev(w1, torch.bfloat16), c.data_ptr(), c_lo.data_ptr() if c_lo is not None else None,
                                          M, N, K, epilogue, _stream())
     _check(st, "synera_debug_gemm_epilogue")
+
+
+def debug_gemm_deferred(a, a_lo, w):
+    """Test hook: the store-form GEMM with K slices stored side by side; returns the f32 slices [n][M][N]."""
+    M, K = a.shape
+    N = w.shape[0]
+    parts = torch.empty((8, M, N), dtype=torch.float32, device=a.device)
+    n = C.c_int32(0)
+    st = _lib.synera_debug_gemm_deferred(_dev(a, torch.bfloat16), _dev(a_lo, torch.bfloat16), _dev(w, torch.bfloat16),
+                                         parts.data_ptr(), M, N, K, C.byref(n), _stream())
+    _check(st, "synera_debug_gemm_deferred")
+    return parts[:n.value]
 
 
 def debug_set_gemm_tile(variant):

@@ -798,6 +798,19 @@ extern "C" int32_t synera_debug_gemm_epilogue(const void* d_a, const void* d_a_l
                   static_cast<hipStream_t>(stream));
 }
 
+static_assert(SYNERA_MAX_GEMM_SLICES == SY_MAX_DEFERRED_SPLIT, "header and planner disagree on the slice limit");
+extern "C" int32_t synera_debug_gemm_deferred(const void* d_a, const void* d_a_lo, const void* d_w, float* d_parts,
+                                              int32_t M, int32_t N, int32_t K, int32_t* h_n_parts, void* stream) {
+  if (!d_a || !d_a_lo || !d_w || !d_parts || !h_n_parts || M < 1 || N < 1 || K < 1) return SYNERA_EINVAL;
+  if (N % 128 != 0 || K % 64 != 0) return SYNERA_EUNSUP;
+  int n_parts = 0;
+  const int32_t st = run_gemm(static_cast<const bf16_t*>(d_a), static_cast<const bf16_t*>(d_a_lo), d_w, N, nullptr, 0,
+                              nullptr, 0, d_parts, nullptr, M, N, K, GEMM_STORE_F32, static_cast<hipStream_t>(stream),
+                              d_parts, &n_parts);
+  *h_n_parts = n_parts > 0 ? n_parts : 1;
+  return st;
+}
+
 extern "C" int32_t synera_gemm_bf16(const void* d_a, const void* d_a_lo, const void* d_w, float* d_c, int32_t M,
                                     int32_t N, int32_t K, void* stream) {
   if (!d_a || !d_w || !d_c || M < 1 || N < 1 || K < 1) return SYNERA_EINVAL;

@@ -528,8 +528,10 @@ __global__ __launch_bounds__(256) void gemm_tall_kernel(GemmArgs g) {
 #define SY_COPY(J_, NXT, STEP) glds16_at(src[J_] + (size_t)(STEP) * BK, NXT + dst[J_]);
 #define SY_ISSUE(NXT, STEP) _Pragma("unroll") for (int j = 0; j < IPW; ++j) SY_COPY(j, NXT, STEP)
 #define SY_MFMA(ACC, FA, FW, I_)                                                                  \
-  if ((I_) < 8) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(FA), "v"(FW)); \
-  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(ACC) : "v"(FA), "v"(FW));
+  {                                                                                               \
+    if ((I_) < 8) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(FA), "v"(FW)); \
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(ACC) : "v"(FA), "v"(FW));  \
+  }
 #define SY_LOAD_A(I_, STAGE)                                                                      \
   if ((I_) < MB) {                                                                                \
     fa[((I_) >> 1) & 1][(I_) & 1][0] = *reinterpret_cast<const bf16x8*>(STAGE + a_off0 + (I_) * 32 * BK);        \
@@ -561,12 +563,13 @@ __global__ __launch_bounds__(256) void gemm_tall_kernel(GemmArgs g) {
                   if (2 * p + b < MB) SY_MFMA(acc[2 * p + b][j], fa[p & 1][b][t], fw[j][t & 1], 2 * p + b) \
     }                                                                                             \
   }
-#define SY_STEP(CUR, NXT, S_)                                                                     \
+#define SY_STEP(CUR, NXT, S_, SETTLE)                                                             \
   {                                                                                               \
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(IPW) : "memory");                         \
     asm volatile("s_barrier" ::: "memory");                                                       \
     const int nxt_ = (S_) + 2 < n_steps ? (S_) + 2 : n_steps - 1;                                 \
     SY_MULT(CUR, NXT, nxt_)                                                                       \
+    if (SETTLE) asm volatile("s_nop 15" ::: "memory");                                            \
   }
 
   const uint32_t l0 = lds_addr_of(st0), l1 = lds_addr_of(st1), l2 = lds_addr_of(st2);
@@ -576,14 +579,18 @@ __global__ __launch_bounds__(256) void gemm_tall_kernel(GemmArgs g) {
     SY_ISSUE(l1, one_)
   }
   int s = 0;
+  // SETTLE: the last step of every basic block ends with wait states that let its final MFMAs finish.  The
+  // compiler does not know that the accumulators are MFMA results (see below) and is free to copy one to
+  // another register where control flow joins -- at the loop's back edge and exits -- where it would read
+  // a result the matrix core has not written yet.
   for (; s + 3 <= n_steps; s += 3) {
-    SY_STEP(st0, l2, s)
-    SY_STEP(st1, l0, s + 1)
-    SY_STEP(st2, l1, s + 2)
+    SY_STEP(st0, l2, s, false)
+    SY_STEP(st1, l0, s + 1, false)
+    SY_STEP(st2, l1, s + 2, true)
   }
   if (s < n_steps) {
-    SY_STEP(st0, l2, s)
-    if (s + 1 < n_steps) SY_STEP(st1, l0, s + 1)
+    SY_STEP(st0, l2, s, true)
+    if (s + 1 < n_steps) SY_STEP(st1, l0, s + 1, true)
   }
 #undef SY_COPY
 #undef SY_ISSUE
@@ -596,6 +603,15 @@ __global__ __launch_bounds__(256) void gemm_tall_kernel(GemmArgs g) {
   // just written by them, so the wait the hardware needs before other instructions read an MFMA result is
   // spelled out here.
   asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+  // (empty statements that "rewrite" each accumulator: every later read of one depends on them, and they
+  // stay behind the wait above, so the compiler cannot hoist an accumulator read over it)
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if (i < 8) asm volatile("" : "+a"(acc[i][j]));
+      else asm volatile("" : "+v"(acc[i][j]));
+    }
 
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
@@ -647,6 +663,226 @@ static hipError_t launch_tall(const GemmArgs& g, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// The same tall tile built from v_mfma_f32_16x16x32_bf16: BM = 16 MT rows, so the tile height moves in
+// steps of 16 rows and two tiles can hug an M that two 32-row-granular tiles overshoot (M = 532: 2 x 272
+// against 2 x 288).  BK = 32 is exactly one MFMA K step: lane l holds row l % 16 and the 8 k values of
+// chunk l / 16 for both operands.  The weight fragment is the MFMA's first operand, so a lane ends up with
+// 4 consecutive output columns of one row and the epilogue stores 16 bytes per lane.  Per K step a
+// wavefront reads its 4 weight fragments once and streams the 2 MT activation fragments (hi, lo) through
+// them; each activation fragment feeds 4 independent accumulators, which is what this 4-pass MFMA needs
+// to issue back to back.  Row blocks 0..15 accumulate in AGPRs, a seventeenth in VGPRs.  Within a 16-row
+// fragment the chunk position only has to vary with the row's bits 1..2 (see swz_mask: bit 4 is constant
+// inside one fragment), so the stage layout uses that plain mask.  K slices are only ever stored for
+// the consumer to add (GemmArgs::deferred): there is no atomic path, whose per-element operands would
+// need every accumulator in a VGPR at once.
+__device__ __forceinline__ int swz16(int row, int chunk) { return (row * 4 + (chunk ^ ((row >> 1) & 3))) * 8; }
+
+template <int MT, int EPI>
+__global__ __launch_bounds__(256) void gemm_tall16_kernel(GemmArgs g) {
+  constexpr int BM = 16 * MT, BN = 256, BK = 32;
+  constexpr int A_INS = 2 * MT;                  // copy instructions (16 tile rows each) for [A_hi | A_lo]
+  constexpr int A_IPW = (A_INS + 3) / 4;         // per wavefront; a surplus one repeats the last group
+  constexpr int W_IPW = BN / 16 / 4;
+  constexpr int IPW = A_IPW + W_IPW;
+  constexpr int R = 2 * BM + BN;
+  static_assert(MT >= 1 && MT <= 17, "accumulators: 16 MT registers per lane, stages: 3 (2 BM + 256) x 64 B of LDS");
+  __shared__ __attribute__((aligned(16))) bf16_t st0[R * BK];
+  __shared__ __attribute__((aligned(16))) bf16_t st1[R * BK];
+  __shared__ __attribute__((aligned(16))) bf16_t st2[R * BK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / BN;
+  const int xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
+  const int n_tile = (within / m_tiles) * 8 + xcd;
+  if (n_tile >= n_tiles) return;
+  const int m0 = (within % m_tiles) * BM, n0 = n_tile * BN;
+  const int K = g.K, M = g.M;
+  const int total_steps = K / BK;
+  const int step_begin = (int)((long)blockIdx.z * total_steps / g.split_k);
+  const int n_steps = (int)((long)(blockIdx.z + 1) * total_steps / g.split_k) - step_begin;
+  if (n_steps <= 0) return;
+
+  const bf16_t* src[IPW];
+  uint32_t dst[IPW];                             // byte offset of the copy's 16 rows inside a stage
+#pragma unroll
+  for (int j = 0; j < IPW; ++j) {
+    int grp;                                     // 16-row group of the stage
+    if (j < A_IPW) {
+      grp = wave + 4 * j;
+      grp = grp < A_INS ? grp : A_INS - 1;       // same bytes to the same place: harmless
+    } else {
+      grp = A_INS + wave * W_IPW + (j - A_IPW);
+    }
+    const int r = grp * 16 + lane / 4;
+    const int ch = (lane % 4) ^ ((r >> 1) & 3);
+    const bf16_t* base;
+    if (r < 2 * BM) {
+      int am = m0 + (r < BM ? r : r - BM);
+      am = am < M ? am : M - 1;                  // rows past M are copied (clamped) and never stored
+      base = (r < BM ? g.a : g.a_lo) + (size_t)am * K;
+    } else {
+      const int col = r - 2 * BM;
+      int wrow;
+      const bf16_t* wbase;
+      if (EPI == GEMM_SWIGLU_BF16) {             // 16-column groups alternate gate, up
+        wrow = (n0 >> 1) + ((col >> 5) << 4) + (col & 15);
+        wbase = ((col >> 4) & 1) ? g.w[1] : g.w[0];
+      } else {
+        wrow = n0 + col;
+        wbase = g.w[0];
+        if (wrow >= g.w_rows[0]) {
+          wrow -= g.w_rows[0];
+          wbase = g.w[1];
+          if (wrow >= g.w_rows[1]) {
+            wrow -= g.w_rows[1];
+            wbase = g.w[2];
+          }
+        }
+      }
+      base = wbase + (size_t)wrow * K;
+    }
+    src[j] = base + (size_t)step_begin * BK + ch * 8;
+    dst[j] = grp * 16 * BK * 2;
+  }
+
+  f32x4 acc[MT][4];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int l16 = lane & 15, kc = lane >> 4;
+  const int a_off = swz16(l16, kc);                               // + i * 16 rows; + BM rows: lo
+  const int w_off = 2 * BM * BK + swz16(wave * 64 + l16, kc);     // + j * 16 rows
+#define SY_COPY(J_, NXT, STEP) glds16_at(src[J_] + (size_t)(STEP) * BK, NXT + dst[J_]);
+#define SY_ISSUE(NXT, STEP) _Pragma("unroll") for (int j = 0; j < IPW; ++j) SY_COPY(j, NXT, STEP)
+#define SY_MFMA(ACC, FW, FA, I_)                                                                  \
+  {                                                                                               \
+    if ((I_) < 16) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(FW), "v"(FA)); \
+    else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(ACC) : "v"(FW), "v"(FA)); \
+  }
+// The copies of K step s+2 are spread over the row blocks of step s, one per block (see gemm_tall_kernel).
+#define SY_MULT(STAGE, NXT, NSTEP)                                                                \
+  {                                                                                               \
+    bf16x8 fw[4];                                                                                 \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                 \
+        fw[j] = *reinterpret_cast<const bf16x8*>(STAGE + w_off + j * 16 * BK);                    \
+    bf16x8 fa[MT + 2], fl[MT + 2];                                                                \
+    _Pragma("unroll") for (int i = 0; i < 2 && i < MT; ++i) {                                     \
+      fa[i] = *reinterpret_cast<const bf16x8*>(STAGE + a_off + i * 16 * BK);                      \
+      fl[i] = *reinterpret_cast<const bf16x8*>(STAGE + a_off + (BM + i * 16) * BK);               \
+    }                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                              \
+      if (i + 2 < MT) {                                                                           \
+        fa[i + 2] = *reinterpret_cast<const bf16x8*>(STAGE + a_off + (i + 2) * 16 * BK);          \
+        fl[i + 2] = *reinterpret_cast<const bf16x8*>(STAGE + a_off + (BM + (i + 2) * 16) * BK);   \
+      }                                                                                           \
+      if (i < IPW) SY_COPY(i, NXT, NSTEP)                                                         \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) SY_MFMA(acc[i][j], fw[j], fa[i], i)           \
+      _Pragma("unroll") for (int j = 0; j < 4; ++j) SY_MFMA(acc[i][j], fw[j], fl[i], i)           \
+    }                                                                                             \
+    _Pragma("unroll") for (int j = MT; j < IPW; ++j) SY_COPY(j, NXT, NSTEP)                       \
+  }
+#define SY_STEP(CUR, NXT, S_, SETTLE)                                                             \
+  {                                                                                               \
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(IPW) : "memory");                         \
+    asm volatile("s_barrier" ::: "memory");                                                       \
+    const int nxt_ = (S_) + 2 < n_steps ? (S_) + 2 : n_steps - 1;                                 \
+    SY_MULT(CUR, NXT, nxt_)                                                                       \
+    if (SETTLE) asm volatile("s_nop 15" ::: "memory");                                            \
+  }
+
+  const uint32_t l0 = lds_addr_of(st0), l1 = lds_addr_of(st1), l2 = lds_addr_of(st2);
+  SY_ISSUE(l0, 0)
+  {
+    const int one_ = n_steps > 1 ? 1 : 0;
+    SY_ISSUE(l1, one_)
+  }
+  int s = 0;
+  // SETTLE: the last step of every basic block ends with wait states that let its final MFMAs finish.  The
+  // compiler does not know that the accumulators are MFMA results (see below) and is free to copy one to
+  // another register where control flow joins -- at the loop's back edge and exits -- where it would read
+  // a result the matrix core has not written yet.
+  for (; s + 3 <= n_steps; s += 3) {
+    SY_STEP(st0, l2, s, false)
+    SY_STEP(st1, l0, s + 1, false)
+    SY_STEP(st2, l1, s + 2, true)
+  }
+  if (s < n_steps) {
+    SY_STEP(st0, l2, s, true)
+    if (s + 1 < n_steps) SY_STEP(st1, l0, s + 1, true)
+  }
+#undef SY_COPY
+#undef SY_ISSUE
+#undef SY_MFMA
+#undef SY_MULT
+#undef SY_STEP
+  // surplus copies land before the LDS is released; MFMA results settle before they are read (see above)
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (i < 16) asm volatile("" : "+a"(acc[i][j]));
+      else asm volatile("" : "+v"(acc[i][j]));
+    }
+
+  const int nq = kc * 4;                         // this lane's 4 consecutive columns inside a 16-column fragment
+  const bool defer = g.deferred && g.split_k > 1;
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int m = m0 + i * 16 + l16;
+    if (m >= M) continue;
+    if (EPI == GEMM_SWIGLU_BF16) {
+#pragma unroll
+      for (int j = 0; j < 4; j += 2) {
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float gate = acc[i][j][r], up = acc[i][j + 1][r];
+          const float v = gate / (1.0f + __expf(-gate)) * up;
+          hi[r] = f2bf(v);
+          lo[r] = f2bf(v - bf2f(hi[r]));
+        }
+        const size_t at = (size_t)m * (g.N >> 1) + (n0 >> 1) + (wave * 2 + (j >> 1)) * 16 + nq;
+        *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.c) + at) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
+        *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.c_lo) + at) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
+      }
+    } else {
+      float* c = (defer ? g.c_parts + (size_t)blockIdx.z * M * g.N : reinterpret_cast<float*>(g.c)) +
+                 (size_t)m * g.N + n0 + wave * 64 + nq;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (EPI == GEMM_ADD_F32 && !defer) {
+          float4 o = *reinterpret_cast<float4*>(c + j * 16);
+          o.x += acc[i][j][0];
+          o.y += acc[i][j][1];
+          o.z += acc[i][j][2];
+          o.w += acc[i][j][3];
+          *reinterpret_cast<float4*>(c + j * 16) = o;
+        } else {
+          *reinterpret_cast<float4*>(c + j * 16) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+        }
+      }
+    }
+  }
+}
+
+template <int MT>
+static hipError_t launch_tall16(const GemmArgs& g, hipStream_t s) {
+  constexpr int BM = 16 * MT;
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / 256;
+  const dim3 grid(8 * ((n_tiles + 7) / 8) * m_tiles, 1, g.split_k);
+  switch (g.epilogue) {
+    case GEMM_STORE_F32: gemm_tall16_kernel<MT, GEMM_STORE_F32><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_ADD_F32: gemm_tall16_kernel<MT, GEMM_ADD_F32><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_SWIGLU_BF16: gemm_tall16_kernel<MT, GEMM_SWIGLU_BF16><<<grid, 256, 0, s>>>(g); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // Tile configurations.  N tile 256 halves the weight re-reads from L2 per MFMA; the 128-wide
 // one serves outputs whose N is not a multiple of 256 and small problems.
 template <int BM, int BN, int BK, int WGM, int WGN, bool SPLIT>
@@ -686,8 +922,10 @@ static const Variant kVariants[] = {{128, 128}, {128, 256}, {256, 128}, {256, 25
                                    {128, 256}, {64, 128}, {128, 128}, {64, 256},
                                    {128, 128}, {128, 256}, {128, 256}, {64, 256},    // 11..: async-copy kernels
                                    {64, 256}, {128, 128}, {64, 128},
-                                   {128, 256}, {160, 256}, {192, 256}, {224, 256}, {256, 256}, {288, 256}};   // 18..: tall tiles
-static const int kFirstTall = 18;
+                                   {128, 256}, {160, 256}, {192, 256}, {224, 256}, {256, 256}, {288, 256},   // 18..: tall tiles, 32-row blocks
+                                   {144, 256}, {176, 256}, {208, 256}, {240, 256}, {272, 256},   // 24..: tall tiles, 16-row blocks
+                                   {128, 256}, {160, 256}, {192, 256}, {224, 256}, {256, 256}};
+static const int kFirstTall = 18, kFirstTall16 = 24;
 static const int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 static bool variant_fits(const GemmArgs& g, int v) {
@@ -699,43 +937,53 @@ static bool variant_fits(const GemmArgs& g, int v) {
   return true;
 }
 
-// Tall-tile plan: the row-block count MB (tile = 32 MB rows) and the K split with the least modelled time.
+// Tall-tile plan: the tile (variants kFirstTall.., BM rows) and the K split with the least modelled time.
 // Blocks are equal-sized and one runs per compute unit, so a launch takes ceil(blocks / 256) rounds of
-//   K steps per block x (0.30 + 0.14 MB) us        (fit of MI355X timings at M = 300..1030)
+//   K steps per block x t_step(BM) us              (fits of MI355X timings at M = 200..1030: 0.12 us plus
+//                                                    0.19 us per 32-row block, or 0.0825 us per 16-row block:
+//                                                    at equal height the 16-row form is ~13 % faster, the
+//                                                    32-row form is the only one that reaches 288 rows)
 // plus, with K split, the merge of the partial tiles (atomic adds, or stores that the consumer kernel sums).
-static int tall_split(const GemmArgs& g, int mb) {
+static double tall_step_us(int v) {
+  const int bm = kVariants[v].bm;
+  return v < kFirstTall16 ? 0.12 + 0.19 * (bm / 32) : 0.12 + 0.0825 * (bm / 16);
+}
+static int tall_split(const GemmArgs& g, int v) {
   if (g.epilogue == GEMM_SWIGLU_BF16) return 1;
-  const long tiles = (long)((g.M + 32 * mb - 1) / (32 * mb)) * (g.N / 256);
+  if (v >= kFirstTall16 && !g.deferred) return 1;   // these tiles split K only into stored slices
+  const int bm = kVariants[v].bm;
+  const long tiles = (long)((g.M + bm - 1) / bm) * (g.N / 256);
   long split = 256 / tiles;
   const long most = g.K / 32 / 8;               // at least 8 K steps per slice
   split = split < most ? split : most;
   if (g.deferred && split > SY_MAX_DEFERRED_SPLIT) split = SY_MAX_DEFERRED_SPLIT;
   return split < 1 ? 1 : (int)split;
 }
-static double tall_cost(const GemmArgs& g, int mb, int split) {
-  const long tiles = (long)((g.M + 32 * mb - 1) / (32 * mb)) * (g.N / 256);
+static double tall_cost(const GemmArgs& g, int v, int split) {
+  const int bm = kVariants[v].bm;
+  const long tiles = (long)((g.M + bm - 1) / bm) * (g.N / 256);
   const long rounds = (tiles * split + 255) / 256;
   const double steps = (double)(g.K / 32) / split;
   // per K slice and 2.2 M outputs: ~8.5 us of atomic adds, or ~3 us to store the slice and read it back
   const double merge = split > 1 ? (g.deferred ? 3.0 : 8.5) * split * ((double)g.M * g.N / 2.2e6) : 0.0;
-  return rounds * steps * (0.30 + 0.14 * mb) + merge;
+  return rounds * steps * tall_step_us(v) + merge;
 }
 static int pick_tall(const GemmArgs& g, int* split_out) {
   int best = -1, best_split = 1;
   double best_cost = 0.0;
-  for (int mb = 4; mb <= 9; ++mb) {
-    const int tile_split = tall_split(g, mb);
-    for (int split = 1; split <= tile_split; ++split) {    // fewer slices than fit can win: fewer atomics
-      const double c = tall_cost(g, mb, split);
+  for (int v = kFirstTall; v < kNumVariants; ++v) {
+    const int tile_split = tall_split(g, v);
+    for (int split = 1; split <= tile_split; ++split) {    // fewer slices than fit can win: less to merge
+      const double c = tall_cost(g, v, split);
       if (best < 0 || c < best_cost) {
-        best = mb;
+        best = v;
         best_cost = c;
         best_split = split;
       }
     }
   }
   if (split_out) *split_out = best_split;
-  return kFirstTall + (best - 4);
+  return best;
 }
 
 static int pick_variant(const GemmArgs& g) {
@@ -762,7 +1010,7 @@ int gemm_pick_split(const GemmArgs& g) {
   const int vi = pick_variant(g);
   if (vi >= kFirstTall) {
     int split = 1;
-    if (g_gemm_variant >= 0) return tall_split(g, vi - kFirstTall + 4);   // forced tile: as many slices as fit
+    if (g_gemm_variant >= 0) return tall_split(g, vi);   // forced tile: as many slices as fit
     pick_tall(g, &split);
     return split;
   }
@@ -780,6 +1028,7 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (!variant_fits(g, v) || g.K % 64 != 0 || g.split_k < 1) return hipErrorInvalidValue;
   if (v >= kFirstTall ? g.split_k > g.K / 32 : g.K % (g.split_k * 64) != 0) return hipErrorInvalidValue;
   if (v >= 11 && !g.a_lo) return hipErrorInvalidValue;
+  if (v >= kFirstTall16 && g.split_k > 1 && !g.deferred) return hipErrorInvalidValue;
   if (g.deferred && g.split_k > 1 &&
       (v < kFirstTall || !g.c_parts || g.split_k > SY_MAX_DEFERRED_SPLIT || g.epilogue == GEMM_SWIGLU_BF16))
     return hipErrorInvalidValue;
@@ -818,6 +1067,16 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     case 21: return launch_tall<7>(g, s);
     case 22: return launch_tall<8>(g, s);
     case 23: return launch_tall<9>(g, s);
+    case 24: return launch_tall16<9>(g, s);
+    case 25: return launch_tall16<11>(g, s);
+    case 26: return launch_tall16<13>(g, s);
+    case 27: return launch_tall16<15>(g, s);
+    case 28: return launch_tall16<17>(g, s);
+    case 29: return launch_tall16<8>(g, s);
+    case 30: return launch_tall16<10>(g, s);
+    case 31: return launch_tall16<12>(g, s);
+    case 32: return launch_tall16<14>(g, s);
+    case 33: return launch_tall16<16>(g, s);
     default: return hipErrorInvalidValue;
   }
 #undef SY_VARIANT
