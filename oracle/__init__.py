@@ -19,8 +19,10 @@ state), widened exactly.
 Pins (tests/test_oracle_*.py): chunked == sequential == full prefill, paging and
 batch invariance, accept-rule properties and brute force, softmax/entropy closed
 forms, top-k / margin / dispatch-probability closed forms and brute force, attention/RoPE/RMSNorm special cases, an independently written dense
-float64 decoder on the tiny config, and the capped-geometric expected accept
-length.  No function here is "parity unpinned".
+float64 decoder on the tiny config, the capped-geometric expected accept
+length, and for the scheduler (Algorithm 1) hand-worked iteration traces, the chunk
+count in closed form and conservation invariants on seeded random arrival traces.
+No function here is "parity unpinned".
 """
 from .numerics import bf16_round, bf16_bits, bf16_from_bits  # noqa: F401
 from .confidence import confidence_row, confidence  # noqa: F401
@@ -30,3 +32,4 @@ from .decoder import (  # noqa: F401
     lm_head,
 )
 from .verify import accept_prefix, verify_chunks, draft_chain, prefill_context  # noqa: F401
+from .scheduler import SchedulerOracle, EngineItem  # noqa: F401
