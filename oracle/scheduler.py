@@ -51,11 +51,22 @@ class _Request:
     cached: int = 0                    # L
     pages: list = field(default_factory=list)
     completed: bool = False
-    # the request waiting in a queue or being executed
-    n_prompt: int = 0
-    u: int = 0
-    k: int = 0
-    done: int = 0                      # tokens of the current submission already forwarded
+    waiting: object = None             # the submission waiting in a queue: _Work, or None
+    running: bool = False              # a submission of this request is being executed
+
+
+@dataclass
+class _Work:
+    """One submission of a request: a prompt (u = n_prompt, k = 0) or a verification (u uncached, k drafts)."""
+    r: _Request
+    u: int
+    k: int
+    verify: bool
+    done: int = 0                      # tokens already forwarded
+
+    @property
+    def total(self):
+        return self.u + self.k
 
 
 class SchedulerOracle:
@@ -79,95 +90,84 @@ class SchedulerOracle:
             raise ValueError("bad prefill request")
         if self._pages_for(n_prompt) > min(self.max_pages_per_request, self.n_pages):
             raise MemoryError("prompt can never fit")
-        r = _Request(request_id, n_prompt=n_prompt)
+        r = _Request(request_id)
+        r.waiting = _Work(r, n_prompt, 0, verify=False)
         self.requests[request_id] = r
-        self.prefill_queue.append(r)
+        self.prefill_queue.append(r.waiting)
 
     def submit_verify(self, request_id, u, k):
         r = self.requests.get(request_id)
         if r is None or request_id not in self.B or r.completed or u < 0 or k < 1 or k > self.chunk:
             raise ValueError("bad verification request")
-        if r in self.verify_queue or r.k:
+        if r.waiting is not None or r.running:
             raise ValueError("request already has a verification pending")
         if self._pages_for(r.cached + u + k) > min(self.max_pages_per_request, self.n_pages):
             raise MemoryError("request can never fit")
-        r.u, r.k, r.done = u, k, 0
-        self.verify_queue.append(r)
+        r.waiting = _Work(r, u, k, verify=True)
+        self.verify_queue.append(r.waiting)
 
     def finish(self, request_id):
         r = self.requests[request_id]
-        if r.k or r.n_prompt:
+        if request_id not in self.B or r.waiting is not None or r.running:
             raise ValueError("request still has work pending")
         r.completed = True
 
     # ---- the two fetch operations of the algorithm, with the admission rule ---------------------
-    def _admit(self, r, n_new_tokens, batch, first_call_tokens):
-        """Pages for the request's whole new length, if batch, token and page limits allow."""
+    def _get_next(self, queue, batch):
+        """Head of the queue if batch, token and page limits allow it (it then gets the pages for the
+        request's whole new length), else nothing: no overtaking."""
+        if not queue:
+            return None
+        w = queue[0]
         if len(batch) + 1 > self.max_batch:
-            return False
-        if first_call_tokens + min(self.chunk, n_new_tokens) > self.max_tokens:
-            return False
-        need = self._pages_for(r.cached + n_new_tokens) - len(r.pages)
+            return None
+        if sum(min(self.chunk, q.total) for q in batch) + min(self.chunk, w.total) > self.max_tokens:
+            return None
+        need = self._pages_for(w.r.cached + w.total) - len(w.r.pages)
         if need > len(self.free_pages):
-            return False
+            return None
         for _ in range(max(need, 0)):
-            r.pages.append(self.free_pages.pop(0))
-        return True
+            w.r.pages.append(self.free_pages.pop(0))
+        w.r.waiting, w.r.running = None, True
+        return queue.popleft()
 
     def get_next_prefill_request(self, B_prefill):
-        if not self.prefill_queue:
-            return None
-        r = self.prefill_queue[0]
-        tokens = sum(min(self.chunk, q.n_prompt) for q in B_prefill)
-        if not self._admit(r, r.n_prompt, B_prefill, tokens):
-            return None
-        return self.prefill_queue.popleft()
+        return self._get_next(self.prefill_queue, B_prefill)
 
     def get_next_verification_request(self, B_verify):
-        if not self.verify_queue:
-            return None
-        r = self.verify_queue[0]
-        tokens = sum(min(self.chunk, q.u + q.k) for q in B_verify)
-        if not self._admit(r, r.u + r.k, B_verify, tokens):
-            return None
-        return self.verify_queue.popleft()
+        return self._get_next(self.verify_queue, B_verify)
 
     # ---- execution: fixed chunks through the engine ---------------------------------------------
-    def _engine_calls(self, batch, total_of, engine, verify):
-        while any(r.done < total_of(r) for r in batch):
+    def _engine_calls(self, batch, engine):
+        while any(w.done < w.total for w in batch):
             call = []
-            for r in batch:
-                total = total_of(r)
-                if r.done >= total:
+            for w in batch:
+                remaining = w.total - w.done
+                if remaining == 0:
                     continue
-                remaining = total - r.done
-                if verify and remaining <= self.chunk:     # the rest of the uncached tokens and all drafts
-                    n, k, last = remaining, r.k, True
+                if w.verify and remaining <= self.chunk:   # the rest of the uncached tokens and all drafts
+                    n, k, last = remaining, w.k, True
                 else:                                      # tokens forwarded for their KV only
-                    n, k, last = min(self.chunk, remaining - (r.k if verify else 0)), 1, False
-                call.append(EngineItem(r.request_id, r.cached + r.done, n - k, k, r.done, last, tuple(r.pages)))
-            accept = engine(call)
-            for item, a in zip(call, accept):
-                r = self.requests[item.request_id]
-                n = item.n_uncached + item.n_draft
-                if item.final_verify:
-                    assert 0 <= a <= item.n_draft
-                    r.cached += r.done + item.n_uncached + a
-                    r.done = total_of(r)                   # submission consumed
-                else:
-                    r.done += n
-            for r in batch:
-                if r.done >= total_of(r) and (r.n_prompt or r.k):
-                    if not verify:
-                        r.cached += r.n_prompt
-                    r.n_prompt = r.u = r.k = r.done = 0
+                    n, k, last = min(self.chunk, remaining - w.k), 1, False
+                call.append((w, EngineItem(w.r.request_id, w.r.cached + w.done, n - k, k, w.done, last,
+                                           tuple(w.r.pages))))
+            accept = engine([item for _, item in call])
+            for (w, item), a in zip(call, accept):
+                w.done += item.n_uncached + item.n_draft
+                if w.done == w.total:                      # submission consumed
+                    if item.final_verify:
+                        assert 0 <= a <= w.k
+                        w.r.cached += w.u + a
+                    else:
+                        w.r.cached += w.u
+                    w.r.running = False
 
     def execute_prefill(self, B_prefill, engine):
-        self._engine_calls(B_prefill, lambda r: r.n_prompt, engine, verify=False)
+        self._engine_calls(B_prefill, engine)
 
     def execute_partialprefill(self, B_verify, L_uncached, engine):
-        assert L_uncached == [r.u for r in B_verify]
-        self._engine_calls(B_verify, lambda r: r.u + r.k, engine, verify=True)
+        assert L_uncached == [w.u for w in B_verify]
+        self._engine_calls(B_verify, engine)
 
     def remove_completed(self, B):
         keep = []
@@ -191,7 +191,7 @@ class SchedulerOracle:
             R_new = self.get_next_prefill_request(B_prefill)
 
         if B_prefill:
-            ids = [r.request_id for r in B_prefill]
+            ids = [w.r.request_id for w in B_prefill]
             self.log.append(("prefill", ids, None))
             self.execute_prefill(B_prefill, engine)
             self.B = ids + self.B
@@ -206,7 +206,7 @@ class SchedulerOracle:
 
         kind = "idle"
         if B_verify:
-            ids = [r.request_id for r in B_verify]
+            ids = [w.r.request_id for w in B_verify]
             self.log.append(("verify", ids, list(L_uncached)))
             self.execute_partialprefill(B_verify, L_uncached, engine)
             self.B = self.B + [i for i in ids if i not in self.B]

@@ -311,3 +311,100 @@ class Verifier:
                                    _dev(v, torch.bfloat16), bt.ctypes.data_as(_i32p), bt.shape[1], n_pages_in_pool,
                                    _dev(k_pool, torch.bfloat16), _dev(v_pool, torch.bfloat16), _stream())
         _check(st, "synera_kv_append")
+
+
+# ---------------------------------------------------------------------------------- scheduler (host only)
+class _SchedStats(C.Structure):
+    _fields_ = [("iterations_prefill", C.c_int64), ("iterations_verify", C.c_int64), ("iterations_idle", C.c_int64),
+                ("engine_calls", C.c_int64), ("tokens_forwarded", C.c_int64), ("host_ns", C.c_int64),
+                ("active_requests", C.c_int32), ("waiting_prefill", C.c_int32), ("waiting_verify", C.c_int32),
+                ("free_pages", C.c_int32)]
+
+
+_i32p, _i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
+_lib.synera_sched_create.restype = C.c_int32
+_lib.synera_sched_create.argtypes = [C.POINTER(_vp), C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+_lib.synera_sched_destroy.restype = C.c_int32
+_lib.synera_sched_destroy.argtypes = [_vp]
+_lib.synera_sched_submit_prefill.restype = C.c_int32
+_lib.synera_sched_submit_prefill.argtypes = [_vp, C.c_int64, C.c_int32]
+_lib.synera_sched_submit_verify.restype = C.c_int32
+_lib.synera_sched_submit_verify.argtypes = [_vp, C.c_int64, C.c_int32, C.c_int32]
+_lib.synera_sched_finish.restype = C.c_int32
+_lib.synera_sched_finish.argtypes = [_vp, C.c_int64]
+_lib.synera_sched_next.restype = C.c_int32
+_lib.synera_sched_next.argtypes = [_vp, _i32p, _i32p, _i64p, _i32p, _i32p, _i32p, _i32p, _i32p, _i32p]
+_lib.synera_sched_commit.restype = C.c_int32
+_lib.synera_sched_commit.argtypes = [_vp, _i32p]
+_lib.synera_sched_cached_len.restype = C.c_int64
+_lib.synera_sched_cached_len.argtypes = [_vp, C.c_int64]
+_lib.synera_sched_get_stats.restype = C.c_int32
+_lib.synera_sched_get_stats.argtypes = [_vp, C.POINTER(_SchedStats)]
+
+SCHED_IDLE, SCHED_PREFILL, SCHED_VERIFY = 0, 1, 2
+
+
+class Scheduler:
+    """Owns a synera_sched.  `next()` returns the host arrays of one engine call as numpy views that stay
+    valid until the following `next()`; `commit(accept_len)` reports its result."""
+
+    def __init__(self, n_pages_in_pool, max_pages, max_batch, max_tokens):
+        import numpy as np
+        self._h = _vp()
+        _check(_lib.synera_sched_create(C.byref(self._h), n_pages_in_pool, max_pages, max_batch, max_tokens),
+               "synera_sched_create")
+        self.max_pages, self.max_batch = max_pages, max_batch
+        self._ids = np.zeros(max_batch, dtype=np.int64)
+        self._i32 = {n: np.zeros(max_batch, dtype=np.int32)
+                     for n in ("ctx_len", "n_uncached", "n_draft", "token_begin", "final_verify")}
+        self._bt = np.zeros((max_batch, max_pages), dtype=np.int32)
+
+    def close(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.synera_sched_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:      # interpreter shutdown: the library handle may already be gone
+            pass
+
+    def submit_prefill(self, request_id, n_prompt):
+        _check(_lib.synera_sched_submit_prefill(self._h, request_id, n_prompt), "synera_sched_submit_prefill")
+
+    def submit_verify(self, request_id, n_uncached, n_draft):
+        _check(_lib.synera_sched_submit_verify(self._h, request_id, n_uncached, n_draft), "synera_sched_submit_verify")
+
+    def finish(self, request_id):
+        _check(_lib.synera_sched_finish(self._h, request_id), "synera_sched_finish")
+
+    def next(self):
+        """-> (kind, dict of arrays cut to the call's B entries)"""
+        kind, B = C.c_int32(0), C.c_int32(0)
+        p = lambda a: a.ctypes.data_as(_i32p)
+        _check(_lib.synera_sched_next(self._h, C.byref(kind), C.byref(B), self._ids.ctypes.data_as(_i64p),
+                                      p(self._i32["ctx_len"]), p(self._i32["n_uncached"]), p(self._i32["n_draft"]),
+                                      p(self._i32["token_begin"]), p(self._i32["final_verify"]), p(self._bt)),
+               "synera_sched_next")
+        b = B.value
+        out = {n: a[:b] for n, a in self._i32.items()}
+        out["request_id"] = self._ids[:b]
+        out["block_table"] = self._bt[:b]
+        return kind.value, out
+
+    def commit(self, accept_len=None):
+        import numpy as np
+        ptr = None
+        if accept_len is not None:
+            self._acc = np.ascontiguousarray(accept_len, dtype=np.int32)
+            ptr = self._acc.ctypes.data_as(_i32p)
+        _check(_lib.synera_sched_commit(self._h, ptr), "synera_sched_commit")
+
+    def cached_len(self, request_id):
+        return _lib.synera_sched_cached_len(self._h, request_id)
+
+    def stats(self):
+        st = _SchedStats()
+        _check(_lib.synera_sched_get_stats(self._h, C.byref(st)), "synera_sched_get_stats")
+        return {n: getattr(st, n) for n, _ in _SchedStats._fields_}

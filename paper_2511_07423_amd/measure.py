@@ -3,6 +3,7 @@ bench.py at the repository root):
 
     python -m paper_2511_07423_amd.measure confidence   # synera_confidence on a 2048 x 128256 logits block
     python -m paper_2511_07423_amd.measure gemm         # the four projection shapes of the 8B decoder at M = 532
+    python -m paper_2511_07423_amd.measure sched        # host time of the scheduler per iteration (no GPU needed)
 
 Each line gives the average launch time over HIP events on the launch stream and the achieved rate
 against MI355X's peak (HBM 8 TB/s; dense bf16 MFMA 2.5 PFLOP/s, algorithmic FLOPs).  Inputs are seeded
@@ -68,6 +69,42 @@ def gemm():
                           "peak_TFLOPs": 2500.0, "frac": fl / ms / 1e9 / 2500.0}))
 
 
+def sched():
+    """Host cost of the verification-aware scheduler on the headline batch shape: 64 active requests with the
+    context lengths of that workload; every round all 64 submit a verification (1 uncached token + their
+    drafts), one iteration forms the batch and its block tables, and the commit books the accept lengths.
+    Reported per iteration, wall clock around the Python calls and the module's own counter (C++ only)."""
+    import time
+    import numpy as np
+    import paper_2511_07423_amd as synera
+    import workloads as wl
+    b = wl.draw_batch(wl.config(3))
+    B = len(b["ctx_len"])
+    max_pages = int(b["max_pages"]) + 8
+    s = synera.Scheduler(B * max_pages, max_pages, B, 64 * B)
+    for i in range(B):
+        s.submit_prefill(i, int(b["ctx_len"][i]))
+    while True:                                   # register the contexts (no engine behind it)
+        kind, out = s.next()
+        if kind == synera.SCHED_IDLE:
+            break
+        s.commit()
+    rng = np.random.default_rng(0)
+    base = s.stats()["host_ns"]
+    rounds, t0 = 50, time.perf_counter()
+    for _ in range(rounds):
+        for i in range(B):
+            s.submit_verify(i, 1, int(b["n_draft"][i]))
+        kind, out = s.next()
+        assert kind == synera.SCHED_VERIFY and len(out["request_id"]) == B
+        s.commit(rng.integers(0, 2, B).astype(np.int32))
+    wall = (time.perf_counter() - t0) / rounds
+    inner = (s.stats()["host_ns"] - base) / rounds
+    print(json.dumps({"what": "synera_sched iteration, 64 verification requests", "requests": B,
+                      "block_table_columns": max_pages, "python_wall_us_per_iteration": wall * 1e6,
+                      "module_us_per_iteration": inner / 1e3}))
+
+
 if __name__ == "__main__":
     which = sys.argv[1] if len(sys.argv) > 1 else "confidence"
-    {"confidence": confidence, "gemm": gemm}[which]()
+    {"confidence": confidence, "gemm": gemm, "sched": sched}[which]()

@@ -10,9 +10,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "synera.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(synera_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(synera_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():
@@ -20,7 +25,8 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(synera.lib_path())
     names = _declared_symbols()
     assert {"synera_verify", "synera_confidence", "synera_kv_append", "synera_create", "synera_destroy",
-            "synera_validate_batch", "synera_gemm_bf16", "synera_version", "synera_strerror"} <= set(names)
+            "synera_validate_batch", "synera_gemm_bf16", "synera_version", "synera_strerror",
+            "synera_sched_create", "synera_sched_next", "synera_sched_commit"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None, n
     assert synera.version() == 100

@@ -209,3 +209,29 @@ def test_random_traces_conserve_tokens_pages_and_kinds():
             assert len(set(live)) == len(live) and not set(live) & set(s.free_pages)
             assert len(live) + len(s.free_pages) == s.n_pages
         assert e.calls
+
+
+def test_a_submission_arriving_while_the_iteration_still_runs_waits_for_the_next_one():
+    """Request 1 finishes its single chunk while request 2 still has chunks to go; its next verification
+    arrives in between.  It must not be swept into the running iteration (Algorithm 1 gathers only at the
+    start of an iteration), and it gets the page its longer context needs."""
+    s = make()
+    s.submit_prefill(1, 204)
+    s.submit_prefill(2, 10)
+    s.iteration(Recorder())
+    calls = []
+
+    def engine(call):
+        calls.append(call)
+        if len(calls) == 2:
+            s.submit_verify(1, 1, 6)                 # request 1's first verification ended with call 1
+        return [it.n_draft if it.final_verify else None for it in call]
+
+    s.submit_verify(1, 0, 2)                         # one chunk: 204 -> 206 cached
+    s.submit_verify(2, 70, 4)                        # three chunks
+    assert s.iteration(engine) == "verify"
+    assert [[it.request_id for it in c] for c in calls] == [[1, 2], [2], [2]]
+    assert s.iteration(engine) == "verify"
+    it = calls[-1][0]
+    assert (it.request_id, it.ctx_len, it.n_uncached, it.n_draft) == (1, 206, 1, 6)
+    assert len(it.pages) == 14                       # 213 tokens
