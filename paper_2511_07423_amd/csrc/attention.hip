@@ -418,10 +418,15 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
 
 // Merge the partial results of a stream that was cut across blocks:
 //   o = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// (Merging inside attn_kernel -- the block that publishes a stream's last partial does it, found with an
+// arrival counter -- was tried: correct, but the device-scope release and acquire it needs write back and
+// invalidate the whole L2 of the block's XCD, once per block, and the kernel took twice as long.)
+// Grid: (cuts, 8); a thread merges at most one 16-byte piece of one row, so all its loads are in flight
+// together (the kernel is latency, not bandwidth).
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnLaunch a) {
   const AttnCut c = a.cuts[blockIdx.x];
   const int HD = a.hd, Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
-  for (int e = threadIdx.x; e < c.nrows * (HD / 4); e += 256) {
+  for (int e = blockIdx.y * 256 + threadIdx.x; e < c.nrows * (HD / 4); e += 256 * gridDim.y) {
     const int row = e / (HD / 4), d4 = (e % (HD / 4)) * 4;
     float M = NEG_BIG;
     for (int s = 0; s < c.nsplit; ++s) M = fmaxf(M, a.part_ml[((size_t)(c.part0 + s) * 64 + row) * 2]);
@@ -469,7 +474,7 @@ static hipError_t launch_hd(const AttnLaunch& a, hipStream_t s) {
     if (e != hipSuccess) return e;
   }
   if (a.n_cuts > 0) {
-    attn_combine_kernel<<<a.n_cuts, 256, 0, s>>>(a);
+    attn_combine_kernel<<<dim3(a.n_cuts, 8), 256, 0, s>>>(a);
     return hipGetLastError();
   }
   return hipSuccess;
