@@ -21,7 +21,9 @@ batch invariance, accept-rule properties and brute force, softmax/entropy closed
 forms, top-k / margin / dispatch-probability closed forms and brute force, attention/RoPE/RMSNorm special cases, an independently written dense
 float64 decoder on the tiny config, the capped-geometric expected accept
 length, and for the scheduler (Algorithm 1) hand-worked iteration traces, the chunk
-count in closed form and conservation invariants on seeded random arrival traces.
+count in closed form and conservation invariants on seeded random arrival traces;
+for the importance score the harmonic closed form under uniform attention, the row-sum
+invariant and a literal recomputation of the first layer's attention matrix.
 No function here is "parity unpinned".
 """
 from .numerics import bf16_round, bf16_bits, bf16_from_bits  # noqa: F401
@@ -33,3 +35,4 @@ from .decoder import (  # noqa: F401
 )
 from .verify import accept_prefix, verify_chunks, draft_chain, prefill_context  # noqa: F401
 from .scheduler import SchedulerOracle, EngineItem  # noqa: F401
+from .importance import importance_from_attention, importance_scores, mean_draft_importance  # noqa: F401

@@ -178,7 +178,7 @@ def decode_token(model, kv, block_table_row, pos, token):
     return x
 
 
-def forward_tokens(model, kv, items):
+def forward_tokens(model, kv, items, attn_probe=None):
     """Partial prefill of a flattened ragged batch, layer by layer.
 
     items: list of (block_table_row, start_pos, tokens) - request i forwards
@@ -186,6 +186,9 @@ def forward_tokens(model, kv, items):
     0..start_pos-1.  Chunk row j sees keys 0..start_pos+j (full prefix, causal
     inside the chunk).  K/V of every forwarded token are appended.  Returns the
     final hidden states [T, d] in flattened order.
+
+    attn_probe: optional (layer, list); the attention matrices softmax(Q K^T / sqrt(h)) of that layer are
+    appended to the list, one array [Hq, n, keys] per item (zero where a key is not visible).
     """
     dt = model.dtype
     Hq, Hkv, h = model.n_q_heads, model.n_kv_heads, model.head_dim
@@ -211,12 +214,17 @@ def forward_tokens(model, kv, items):
             K, V = np.asarray(K, dt), np.asarray(V, dt)
             key_pos = np.arange(start + n)
             visible = key_pos[None, :] <= (start + np.arange(n))[:, None]      # [n, keys]
+            probed = np.empty((Hq, n, start + n), dt) if attn_probe is not None and attn_probe[0] == l else None
             for hq in range(Hq):
                 s = (q[r0:r0 + n, hq, :] @ K[:, hq // G, :].T) / math.sqrt(h)
                 s = np.where(visible, s, -np.inf)
                 e = np.exp(s - s.max(axis=1, keepdims=True))
                 p = e / e.sum(axis=1, keepdims=True, dtype=dt)
                 o[r0:r0 + n, hq, :] = p @ V[:, hq // G, :]
+                if probed is not None:
+                    probed[hq] = p
+            if probed is not None:
+                attn_probe[1].append(probed)
             r0 += n
         x = x + o.reshape(T, Hq * h) @ np.asarray(w["wo"], dt).T
         y = rmsnorm(x, w["mlp_norm"], model.rms_eps, dt)
