@@ -215,6 +215,25 @@ int32_t synera_chunk_dispatch(const float* d_top1_prob, const int32_t* d_cu_rows
                               float k_slope, float* d_mean_conf, float* d_p_conf, void* stream);
 
 /*
+ * Importance scores of the batch that the LAST synera_verify on this context forwarded (Section 3.2:
+ * the column-wise sum of the attention matrix softmax(Q K^T / sqrt(d_k)); the paper names neither layer
+ * nor head handling: these are the last decoder layer's, averaged over the query heads).  For request i
+ * with cached length L_i and chunk length c_i = u_i + k_i the call writes L_i + c_i scores, one per key
+ * position, request after request: score_j = (1/Hq) sum_heads sum_{rows r: L_i + r >= j} p(r, j), so
+ * the scores of a request sum to c_i.  It reads the rotated queries and the per-row softmax statistics
+ * that verify left in the context, and the last layer's K pages (d_k_pool / n_pages_in_pool as given
+ * to that verify, whose block tables are reused).  n_scores must equal sum_i (L_i + c_i).
+ * Optional outputs, device f32 [B]: d_mean_importance = mean score of the request's k_i draft
+ * positions; d_p_imp = the probability of offloading by importance (Section 4.2, second equation):
+ * 0 for i <= i_th/2, 1 for i > i_th, else 1 / (1 + exp(theta ((i - i_th/2) / (i_th/2) - 1/2))); the paper
+ * uses theta = -10.  Errors: EINVAL (null pointers, no verify since the last kv_append / verify error,
+ * n_scores mismatch, i_th <= 0 with d_p_imp), EHIP.
+ */
+int32_t synera_importance(synera_ctx* ctx, int32_t n_pages_in_pool, const void* d_k_pool, int64_t n_scores,
+                          float* d_importance, float i_th, float theta, float* d_mean_importance,
+                          float* d_p_imp, void* stream);
+
+/*
  * Scatter K/V rows of one layer into the paged pools: request i appends n_new_i
  * rows at positions L_i .. L_i+n_new_i-1 (what the partial prefill does for
  * every forwarded token, Section 3.4; exported so a prefill engine or a test

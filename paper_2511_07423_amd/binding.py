@@ -79,6 +79,8 @@ _lib.synera_debug_read_scratch.restype = C.c_int32
 _lib.synera_debug_read_scratch.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp]
 _lib.synera_debug_set_gemm_tile.restype = C.c_int32
 _lib.synera_debug_set_gemm_tile.argtypes = [C.c_int32]
+_lib.synera_importance.restype = C.c_int32
+_lib.synera_importance.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp, C.c_float, C.c_float, _vp, _vp, _vp]
 _lib.synera_debug_gemm_deferred.restype = C.c_int32
 _lib.synera_debug_gemm_deferred.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), _vp]
 _lib.synera_debug_gemm_epilogue.restype = C.c_int32
@@ -285,6 +287,22 @@ class Verifier:
             _dev(out["top1_prob"]), _dev(out["entropy"]), _dev(out["accept_len"]), _dev(out["correction"]),
             _stream())
         _check(st, "synera_verify")
+
+    def importance(self, ctx_len, n_uncached, n_draft, n_pages_in_pool, k_pool, i_th=None, theta=-10.0):
+        """Importance scores of the batch the last verify() forwarded (same ctx_len / n_uncached / n_draft):
+        -> dict with "scores" (f32 [sum L_i + c_i], request-major), "offsets" (numpy prefix sums [B+1]),
+        "mean" (f32 [B], mean over the draft positions) and, with i_th, "p_imp" (f32 [B])."""
+        n = np.asarray(ctx_len, np.int64) + np.asarray(n_uncached, np.int64) + np.asarray(n_draft, np.int64)
+        offsets = np.concatenate([[0], np.cumsum(n)])
+        dev = k_pool.device
+        out = {"scores": torch.empty(int(offsets[-1]), dtype=torch.float32, device=dev), "offsets": offsets,
+               "mean": torch.empty(len(n), dtype=torch.float32, device=dev),
+               "p_imp": torch.empty(len(n), dtype=torch.float32, device=dev) if i_th is not None else None}
+        st = _lib.synera_importance(self._ctx, n_pages_in_pool, _dev(k_pool, torch.bfloat16), int(offsets[-1]),
+                                    _dev(out["scores"]), float(i_th if i_th is not None else 0.0), float(theta),
+                                    _dev(out["mean"]), _dev(out["p_imp"]), _stream())
+        _check(st, "synera_importance")
+        return out
 
     def debug_read_scratch(self, which, out):
         """Test hook: copy an intermediate buffer of the last layer of the last verify into `out`."""

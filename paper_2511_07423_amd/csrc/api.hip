@@ -103,6 +103,13 @@ struct synera_ctx {
   float2* cs;
   float* part_o;
   float* part_ml;
+  float2* row_ml;              // [max_tokens][Hq] softmax statistics of the last layer's attention rows
+  // batch of the last synera_verify, for synera_importance: device pointers into that call's metadata slot
+  struct {
+    const int32_t *ctx_len, *cu_tok, *block_table, *cu_keys, *items, *n_unc, *cu_draft;
+    int32_t B, T, n_items, max_pages, total_keys;
+    bool valid;
+  } last;
   float* gparts;               // K-split slices of one projection: [SY_MAX_DEFERRED_SPLIT][max_tokens][max(d, q+2kv)]
   size_t gpart_elems;          // elements of one slice slot
   // metadata staging ring
@@ -218,6 +225,7 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   const size_t o_cs = take(T * (m.head_dim / 2) * 8);
   const size_t o_po = take(c->part_cap * 64 * m.head_dim * 4);
   const size_t o_pml = take(c->part_cap * 64 * 2 * 4);
+  const size_t o_rml = take(T * (size_t)m.n_q_heads * 8);
   c->gpart_elems = T * std::max<size_t>(qkv_dim, (size_t)m.d_model);
   const size_t o_gp = take(SY_MAX_DEFERRED_SPLIT * c->gpart_elems * 4);
   if (hipMalloc(reinterpret_cast<void**>(&c->arena), off) != hipSuccess) {
@@ -244,11 +252,14 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   c->cs = reinterpret_cast<float2*>(c->arena + o_cs);
   c->part_o = reinterpret_cast<float*>(c->arena + o_po);
   c->part_ml = reinterpret_cast<float*>(c->arena + o_pml);
+  c->row_ml = reinterpret_cast<float2*>(c->arena + o_rml);
+  c->last.valid = false;
   c->gparts = reinterpret_cast<float*>(c->arena + o_gp);
 
   const size_t meta_ints = (size_t)max_batch * 5 + 2 + (size_t)max_tokens + (size_t)c->max_rows +
                            (size_t)max_batch * max_pages + c->pos_cap * 4 + c->unit_cap * 8 + (size_t)c->attn_blocks * 4 +
-                           c->part_cap * 8 + 128;
+                           c->part_cap * 8 + 128 +
+                           ((size_t)max_batch + 1) + 2 * (size_t)max_batch * ((size_t)max_pages / 16 + 2);
   c->meta_cap = align_up(meta_ints * 4, 256);
   for (int s = 0; s < N_STAGE; ++s) {
     c->h_meta[s] = nullptr;
@@ -297,6 +308,8 @@ struct Plan {
   const AttnCut* d_cuts;
   int32_t n_shares, n_cuts;
   int32_t T, R, R_all;      // chunk tokens, draft rows, LM-head rows (drafts + last-uncached rows)
+  const int32_t *d_cu_keys, *d_imp_items;   // importance-score blocks: prefix sums of L_i + chunk_i; (request, first key)
+  int32_t n_imp_items, total_keys;
   int slot;
 };
 
@@ -305,6 +318,7 @@ struct Plan {
 static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, const int32_t* n_unc,
                           const int32_t* n_draft, const int32_t* block_table, int32_t max_pages, bool with_attention,
                           hipStream_t stream, Plan& p) {
+  c->last.valid = false;       // the metadata slots rotate: what synera_importance reads belongs to the newest verify only
   const int slot = (int)(c->calls % N_STAGE);
   if (c->pending[slot]) {
     HIP_TRY(hipEventSynchronize(c->done[slot]));
@@ -352,6 +366,27 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
       } else {
         h[o_first + i] = -1;
       }
+    }
+    // ---- blocks of the optional importance-score pass: 256 consecutive keys of one request each
+    {
+      const size_t o_cuk = region((size_t)B + 1);
+      int32_t keys = 0, n_items = 0;
+      for (int i = 0; i < B; ++i) {
+        h[o_cuk + i] = keys;
+        keys += ctx_len[i] + n_unc[i] + n_draft[i];
+      }
+      h[o_cuk + B] = keys;
+      const size_t o_items = region(2 * (size_t)B * ((size_t)max_pages / 16 + 2));
+      for (int i = 0; i < B; ++i)
+        for (int k0 = 0; k0 < ctx_len[i] + n_unc[i] + n_draft[i]; k0 += 256) {
+          h[o_items + 2 * n_items] = i;
+          h[o_items + 2 * n_items + 1] = k0;
+          ++n_items;
+        }
+      p.d_cu_keys = d + o_cuk;
+      p.d_imp_items = d + o_items;
+      p.n_imp_items = n_items;
+      p.total_keys = keys;
     }
     // ---- attention program.  A stream = (row group of up to `tg` chunk tokens x G heads <= 64 rows, KV head)
     // with the keys 0 .. L + j_last it sees, in 32-key tiles.  Streams of a class (more than 32 rows /
@@ -613,6 +648,7 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
     }
     al.k_layer = k_layer;
     al.v_layer = v_layer;
+    al.row_ml = l == m.n_layers - 1 ? c->row_ml : nullptr;   // kept for synera_importance
     {
       StageTimer t(c, SYNERA_STAGE_ATTENTION, s);
       HIP_TRY(launch_attention(al, s));
@@ -668,7 +704,56 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
     if (d_entropy) HIP_TRY(hipMemcpyAsync(d_entropy, c->lm_h, (size_t)p.R * 4, hipMemcpyDeviceToDevice, s));
   }
   HIP_TRY(launch_accept(d_tokens, d_anchor, c->lm_ids, p.meta, B, p.R, d_argmax, d_accept_len, d_correction, s));
+  c->last.ctx_len = p.meta.ctx_len;
+  c->last.cu_tok = p.meta.cu_tok;
+  c->last.block_table = p.meta.block_table;
+  c->last.n_unc = p.meta.n_unc;
+  c->last.cu_draft = p.meta.cu_draft;
+  c->last.cu_keys = p.d_cu_keys;
+  c->last.items = p.d_imp_items;
+  c->last.B = B;
+  c->last.T = T;
+  c->last.n_items = p.n_imp_items;
+  c->last.max_pages = max_pages;
+  c->last.total_keys = p.total_keys;
+  c->last.valid = true;
   return finish_call(c, p, s);
+}
+
+// ------------------------------------------------------------------------------------ importance scores
+extern "C" int32_t synera_importance(synera_ctx* c, int32_t n_pages_in_pool, const void* d_k_pool,
+                                     int64_t n_scores, float* d_importance, float i_th, float theta,
+                                     float* d_mean_importance, float* d_p_imp, void* stream_) {
+  if (!c || !d_k_pool || !d_importance || n_pages_in_pool < 1) return SYNERA_EINVAL;
+  if (!c->last.valid) return SYNERA_EINVAL;                  // no verification to take the scores from
+  if (n_scores != c->last.total_keys) return SYNERA_EINVAL;
+  if (d_p_imp && !(i_th > 0.0f)) return SYNERA_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream_);
+  const synera_model_desc& m = c->desc;
+  const size_t layer_elems = (size_t)n_pages_in_pool * m.n_kv_heads * SY_PAGE * m.head_dim;
+  ImportanceLaunch a;
+  a.q = c->q;
+  a.q_lo = c->q_lo;
+  a.qf = c->qkv;                 // the QKV projection's fp32 buffer is free between verifies
+  a.T = c->last.T;
+  a.total_keys = c->last.total_keys;
+  a.k_layer = static_cast<const bf16_t*>(d_k_pool) + (size_t)(m.n_layers - 1) * layer_elems;
+  a.row_ml = c->row_ml;
+  a.ctx_len = c->last.ctx_len;
+  a.cu_tok = c->last.cu_tok;
+  a.block_table = c->last.block_table;
+  a.cu_keys = c->last.cu_keys;
+  a.items = c->last.items;
+  a.n_items = c->last.n_items;
+  a.max_pages = c->last.max_pages;
+  a.Hq = m.n_q_heads;
+  a.Hkv = m.n_kv_heads;
+  a.hd = m.head_dim;
+  a.importance = d_importance;
+  HIP_TRY(launch_importance(a, s));
+  HIP_TRY(launch_importance_dispatch(d_importance, c->last.cu_keys, c->last.ctx_len, c->last.n_unc, c->last.cu_draft,
+                                     c->last.B, i_th, theta, d_mean_importance, d_p_imp, s));
+  return SYNERA_OK;
 }
 
 // ------------------------------------------------------------------------------------ stage timing

@@ -402,6 +402,8 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
         for (int db = 0; db < DB; ++db)
           store_pair(a.o + at + db * 16, a.o_lo + at + db * 16, acc[db][0] * inv, acc[db][1] * inv,
                      acc[db][2] * inv, acc[db][3] * inv);
+        if (a.row_ml && g == 0)
+          a.row_ml[(size_t)(u_tok0 + row / G) * Hq + u_kh * G + row % G] = make_float2(m_fin, l_run);
       } else {
         const size_t base = (size_t)u_part * 64 + row;
 #pragma unroll
@@ -443,6 +445,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnLaunch a) {
     const float inv = 1.0f / l;
     const size_t at = ((size_t)(c.tok0 + row / G) * Hq + c.kh * G + row % G) * HD + d4;
     store_pair(a.o + at, a.o_lo + at, sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
+    if (a.row_ml && d4 == 0) a.row_ml[(size_t)(c.tok0 + row / G) * Hq + c.kh * G + row % G] = make_float2(M, l);
   }
 }
 

@@ -109,9 +109,33 @@ struct AttnLaunch {
   float* part_ml;            // [slots][64][2]
   bf16_t* o;                 // [T][Hq][hd], high part of the output pair
   bf16_t* o_lo;              // low part
+  float2* row_ml;            // optional [T][Hq]: per query row the softmax reference m (exponent-2 domain) and
+                             // the sum l of 2^(s - m) over its keys, i.e. p(key) = 2^(s scale log2e - m) / l
   int32_t T, Hq, Hkv, hd;
 };
 hipError_t launch_attention(const AttnLaunch& a, hipStream_t s);
+
+// Importance scores (column sums of the attention matrix, mean over query heads) of one layer, from the
+// rotated queries, the K pool and the per-row softmax statistics the attention kernel left.
+struct ImportanceLaunch {
+  const bf16_t* q;           // [T][Hq][hd] (hi, lo)
+  const bf16_t* q_lo;
+  float* qf;                 // scratch [T][Hq][hd]: the queries recombined to fp32
+  const bf16_t* k_layer;
+  const float2* row_ml;      // [T][Hq]
+  const int32_t* ctx_len;    // device [B]
+  const int32_t* cu_tok;     // device [B+1]
+  const int32_t* block_table;// device [B][max_pages]
+  const int32_t* cu_keys;    // device [B+1]: prefix sums of L_i + chunk_i (output offsets)
+  const int32_t* items;      // device [n_items][2]: request, first key of the block's 256 keys
+  int32_t n_items, max_pages, T, Hq, Hkv, hd, total_keys;
+  float* importance;         // [cu_keys[B]]
+};
+hipError_t launch_importance(const ImportanceLaunch& a, hipStream_t s);
+// mean score of each request's draft positions and P_imp of it (Section 4.2, second equation)
+hipError_t launch_importance_dispatch(const float* importance, const int32_t* cu_keys, const int32_t* ctx_len,
+                                      const int32_t* n_unc, const int32_t* cu_draft, int B, float i_th, float theta,
+                                      float* mean_imp, float* p_imp, hipStream_t s);
 
 // ---------------------------------------------------------------- gemm.hip
 enum GemmEpilogue { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };

@@ -12,6 +12,7 @@ import pytest
 import torch
 
 import gpu_harness as gh
+import oracle
 import workloads as wl
 
 pytestmark = pytest.mark.gpu
@@ -26,7 +27,7 @@ def weights_8b():
     torch.cuda.empty_cache()
 
 
-def _run(n, n_oracle, weights):
+def _run(n, n_oracle, weights, importance=False):
     case = gh.build_case(wl.config(n), DEV, n_oracle=n_oracle, weights=weights, verbose=True)
     out = gh.run_verify(case)
     rep = gh.compare_with_oracle(case, out)
@@ -36,10 +37,38 @@ def _run(n, n_oracle, weights):
           f"max rel dp={rep['max_prob_rel']:.3e} exempt rows/requests={rep['exempt_rows']}/{rep['exempt_requests']} "
           f"max|dKV|={kv['max_kv_err']:.3e} accept_len mean={out['accept_len'].mean():.2f} "
           f"oracle chain {case.timing['oracle_chain_s']:.1f}s", flush=True)
+    if importance:
+        _check_importance(case)
     case.verifier.close()
     assert rep["ok"], rep["fail"]
     assert kv["ok"], kv["fail"]
     return case, out, rep
+
+
+def _check_importance(case, n_sample=3):
+    """Importance scores of the batch just verified (last layer, mean over heads) against the oracle's, for
+    a few of the requests the oracle follows; the row-sum property for all."""
+    b = case.batch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    imp = case.verifier.importance(b["ctx_len"], case.n_uncached, b["n_draft"], b["n_pages"], case.k_pool, i_th=0.05)
+    e0.record()                                   # timed on a repeat: the first launch also loads the kernel
+    imp = case.verifier.importance(b["ctx_len"], case.n_uncached, b["n_draft"], b["n_pages"], case.k_pool, i_th=0.05)
+    e1.record()
+    torch.cuda.synchronize()
+    got, off = imp["scores"].cpu().numpy().astype(np.float64), imp["offsets"]
+    assert np.isfinite(got).all() and (got >= 0).all()
+    for i in range(len(b["ctx_len"])):
+        assert abs(got[off[i]:off[i + 1]].sum() - b["n_draft"][i]) < 2e-3 * b["n_draft"][i]
+    sample = case.sampled[:n_sample]
+    want = oracle.importance_scores(case.model, case.okv, [(b["block_table"][i], int(b["ctx_len"][i]), case.drafts[i])
+                                                           for i in sample])
+    worst = 0.0
+    for i, w in zip(sample, want):
+        g = got[off[i]:off[i + 1]]
+        worst = max(worst, float(np.max(np.abs(g - w) / (w + 1e-4))))
+        assert np.all(np.abs(g - w) <= 3e-2 * w + 1e-5), i
+    print(f"[importance] {e0.elapsed_time(e1) * 1e3:.0f} us for {off[-1]} scores, worst relative deviation "
+          f"{worst:.2e} on requests {sample}", flush=True)
 
 
 def test_config2_8b_batch16(weights_8b):
@@ -48,7 +77,7 @@ def test_config2_8b_batch16(weights_8b):
 
 
 def test_config3_8b_ragged_batch64(weights_8b):
-    case, out, rep = _run(3, 10, weights_8b)
+    case, out, rep = _run(3, 10, weights_8b, importance=True)
     k = case.batch["n_draft"]
     assert k.min() == 1 and k.max() == 16
 
