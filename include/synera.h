@@ -203,6 +203,16 @@ int32_t synera_confidence_topk(const void* d_logits, int32_t dtype, int64_t rows
                                float* d_topk_prob, float* d_margin, float* d_entropy, void* stream);
 
 /*
+ * Top-p (nucleus) cut of compressed distributions ("Compression before transmission", Section 4.2:
+ * top-1 / top-k / top-p of the sampling method in use).  d_topk_prob: device f32 [rows][k], each row most
+ * probable first (synera_confidence_topk's output).  d_count[r] = the smallest n whose float32 running
+ * sum p_0 + ... + p_{n-1}, taken in that order, reaches top_p; all k if the window never does.
+ * d_mass[r] (NULL to skip) = that sum.  Errors: EINVAL (top_p outside (0, 1], k < 1, null pointers), EHIP.
+ */
+int32_t synera_topp_count(const float* d_topk_prob, int64_t rows, int32_t k, float top_p, int32_t* d_count,
+                          float* d_mass, void* stream);
+
+/*
  * Dispatch probability of token chunks from their confidence (Section 4.2, first equation):
  * chunk b owns rows d_cu_rows[b] .. d_cu_rows[b+1]-1 of d_top1_prob (device, i32 [B+1] prefix
  * sums and f32 per-row top-1 probabilities, e.g. synera_verify's or synera_confidence's

@@ -49,6 +49,22 @@ def topk(logits, k, dtype=np.float64):
     return ids, pr, mg
 
 
+def topp_count(probs_desc, top_p, dtype=np.float32):
+    """Top-p (nucleus) truncation of a distribution whose entries are given most probable first: the
+    smallest n with probs_desc[0] + ... + probs_desc[n-1] >= top_p, and that sum.  If the given entries
+    do not reach top_p (the list is itself a truncation, e.g. the top-k window a device transmits) all of
+    them are kept.  The running sum is taken in `dtype`, in list order: the decision is an integer, so the
+    precision is part of the definition (float32, as the transmitted probabilities are)."""
+    acc = dtype(0.0)
+    n = 0
+    for v in probs_desc:
+        acc = dtype(acc + dtype(v))
+        n += 1
+        if acc >= dtype(top_p):
+            break
+    return n, float(acc)
+
+
 def p_conf(c, c_th, k=10.0):
     """Dispatch probability of a chunk whose mean confidence is c (Section 4.2, first equation):
     1 for c <= c_th, else 1 / (1 + exp(k * norm(c))) with norm(c) = (c - c_th) / (1 - c_th) - 1/2."""

@@ -79,6 +79,8 @@ _lib.synera_debug_read_scratch.restype = C.c_int32
 _lib.synera_debug_read_scratch.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp]
 _lib.synera_debug_set_gemm_tile.restype = C.c_int32
 _lib.synera_debug_set_gemm_tile.argtypes = [C.c_int32]
+_lib.synera_topp_count.restype = C.c_int32
+_lib.synera_topp_count.argtypes = [_vp, C.c_int64, C.c_int32, C.c_float, _vp, _vp, _vp]
 _lib.synera_importance.restype = C.c_int32
 _lib.synera_importance.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp, C.c_float, C.c_float, _vp, _vp, _vp]
 _lib.synera_debug_gemm_deferred.restype = C.c_int32
@@ -202,6 +204,16 @@ def debug_gemm_epilogue(a, a_lo, w0, w1, c, c_lo, epilogue):
                                          _dev(w1, torch.bfloat16), c.data_ptr(), c_lo.data_ptr() if c_lo is not None else None,
                                          M, N, K, epilogue, _stream())
     _check(st, "synera_debug_gemm_epilogue")
+
+
+def topp_count(topk_prob, top_p):
+    """Nucleus size within each row's top-k window (probabilities most probable first) -> (count i32, mass f32)."""
+    rows, k = topk_prob.shape
+    n = torch.empty(rows, dtype=torch.int32, device=topk_prob.device)
+    mass = torch.empty(rows, dtype=torch.float32, device=topk_prob.device)
+    st = _lib.synera_topp_count(_dev(topk_prob, torch.float32), rows, k, float(top_p), _dev(n), _dev(mass), _stream())
+    _check(st, "synera_topp_count")
+    return n, mass
 
 
 def debug_gemm_deferred(a, a_lo, w):

@@ -811,6 +811,15 @@ extern "C" int32_t synera_confidence_topk(const void* d_logits, int32_t dtype, i
   return SYNERA_OK;
 }
 
+extern "C" int32_t synera_topp_count(const float* d_topk_prob, int64_t rows, int32_t k, float top_p, int32_t* d_count,
+                                     float* d_mass, void* stream) {
+  if (rows < 0 || k < 1 || !(top_p > 0.0f && top_p <= 1.0f)) return SYNERA_EINVAL;
+  if (rows == 0) return SYNERA_OK;
+  if (!d_topk_prob || !d_count) return SYNERA_EINVAL;
+  HIP_TRY(launch_topp_count(d_topk_prob, rows, k, top_p, d_count, d_mass, static_cast<hipStream_t>(stream)));
+  return SYNERA_OK;
+}
+
 extern "C" int32_t synera_chunk_dispatch(const float* d_top1_prob, const int32_t* d_cu_rows, int32_t B, float c_th,
                                          float k_slope, float* d_mean_conf, float* d_p_conf, void* stream) {
   if (B < 0 || !(c_th >= 0.0f && c_th < 1.0f)) return SYNERA_EINVAL;

@@ -62,6 +62,8 @@ hipError_t launch_confidence(const void* logits, int dtype, int64_t rows, int64_
 
 hipError_t launch_confidence_topk(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride, int k,
                                   int32_t* ids, float* probs, float* margin, float* H, hipStream_t s);
+hipError_t launch_topp_count(const float* probs, int64_t rows, int k, float top_p, int32_t* n, float* mass,
+                             hipStream_t s);
 hipError_t launch_chunk_dispatch(const float* p1, const int32_t* cu_rows, int B, float c_th, float k_slope,
                                  float* mean_conf, float* p_conf, hipStream_t s);
 

@@ -299,6 +299,31 @@ hipError_t launch_chunk_dispatch(const float* p1, const int32_t* cu_rows, int B,
   return hipGetLastError();
 }
 
+// Top-p (nucleus) cut of compressed distributions: row r holds k probabilities, most probable first (the
+// output of confidence_topk_kernel); n[r] = the smallest count whose float32 running sum, in list order,
+// reaches top_p (all k if it never does), mass[r] = that sum.
+__global__ void topp_count_kernel(const float* __restrict__ probs, int64_t rows, int k, float top_p,
+                                  int32_t* __restrict__ n, float* __restrict__ mass) {
+  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= rows) return;
+  float acc = 0.f;
+  int kept = 0;
+  for (int i = 0; i < k; ++i) {
+    acc += probs[r * k + i];
+    kept = i + 1;
+    if (acc >= top_p) break;
+  }
+  n[r] = kept;
+  if (mass) mass[r] = acc;
+}
+
+hipError_t launch_topp_count(const float* probs, int64_t rows, int k, float top_p, int32_t* n, float* mass,
+                             hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  topp_count_kernel<<<(unsigned)((rows + 127) / 128), 128, 0, s>>>(probs, rows, k, top_p, n, mass);
+  return hipGetLastError();
+}
+
 hipError_t launch_confidence(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride,
                              int32_t* ids, float* p1, float* H, hipStream_t s) {
   if (rows <= 0) return hipSuccess;

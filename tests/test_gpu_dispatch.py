@@ -115,3 +115,24 @@ def test_chunk_dispatch_matches_oracle():
         assert np.all((got == 1.0) | (got < 0.9934))
     with pytest.raises(synera.SyneraError):
         synera.chunk_dispatch(torch.from_numpy(p1).to(DEV), torch.from_numpy(cu).to(DEV), 1.0)
+
+
+@pytest.mark.parametrize("top_p", [0.1, 0.5, 0.9, 0.999, 1.0])
+def test_topp_count_is_bit_exact_with_the_oracle(top_p):
+    """Nucleus size inside the transmitted top-k window: the count is an integer decided by a float32 running
+    sum in list order on both sides, so it must agree exactly; the mass to float32 rounding."""
+    import paper_2511_07423_amd as synera
+    x = wl.draw_confidence_logits(300, 4096, 3.0, 6.0, 77, DEV, torch.float32)
+    x[7] = 0.0                                                   # uniform row: the window never reaches top_p
+    x[8, 5] = 80.0                                               # one-hot row
+    ids, pr, _, _ = synera.confidence_topk(x, 8)
+    n, mass = synera.topp_count(pr, top_p)
+    torch.cuda.synchronize()
+    prh = pr.cpu().numpy()
+    for r in range(x.shape[0]):
+        want_n, want_mass = oracle.topp_count(prh[r], top_p)
+        assert int(n[r]) == want_n, r
+        assert abs(float(mass[r]) - want_mass) <= 1e-6
+    assert int(n[7]) == 8 and int(n[8]) == 1
+    with pytest.raises(synera.SyneraError):
+        synera.topp_count(pr, 0.0)

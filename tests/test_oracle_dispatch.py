@@ -89,3 +89,27 @@ def test_chunk_dispatch_means_and_probabilities():
     assert np.allclose(pc, want, rtol=0, atol=1e-15)
     # c = 0.9 with c_th = 0.7: norm = 2/3 - 1/2 = 1/6 -> 1 / (1 + e^(10/6))
     assert pc[0] == pytest.approx(1 / (1 + math.exp(10 / 6)), abs=1e-12)
+
+
+def test_topp_count_closed_forms_and_brute_force():
+    """Nucleus size: uniform over V -> ceil(p V) (binary fractions, exact in float32); one-hot -> 1; a list
+    that never reaches p is kept whole; and against sorting + cumulative sums of a random distribution."""
+    import math
+    import oracle
+    V = 64
+    for p in (0.25, 0.5, 0.515625, 1.0):
+        n, mass = oracle.topp_count([1.0 / V] * V, p)
+        assert n == math.ceil(p * V) and abs(mass - n / V) < 1e-7
+    assert oracle.topp_count([1.0, 0.0, 0.0], 0.9) == (1, 1.0)
+    assert oracle.topp_count([0.5, 0.25], 0.9) == (2, 0.75)            # a top-2 window that holds 75 %: keep both
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        x = rng.normal(0, 3, 200)
+        ids, pr = oracle.topk_row(x, 200)
+        pr32 = pr.astype(np.float32)
+        p = float(rng.uniform(0.05, 0.999))
+        n, mass = oracle.topp_count(pr32, p)
+        cum = np.cumsum(np.sort(oracle.softmax_probs(x))[::-1])       # float64 reference of the definition
+        n_ref = int(np.searchsorted(cum, p, side="left")) + 1
+        assert abs(n - n_ref) <= (1 if np.min(np.abs(cum - p)) < 1e-5 else 0)
+        assert mass >= p - 1e-6 and (n == 1 or mass - float(pr32[n - 1]) < p + 1e-6)
