@@ -23,7 +23,8 @@ float64 decoder on the tiny config, the capped-geometric expected accept
 length, and for the scheduler (Algorithm 1) hand-worked iteration traces, the chunk
 count in closed form and conservation invariants on seeded random arrival traces;
 for the importance score the harmonic closed form under uniform attention, the row-sum
-invariant and a literal recomputation of the first layer's attention matrix.
+invariant and a literal recomputation of the first layer's attention matrix; for
+speculative sampling the exact output distribution on a tiny vocabulary (it must equal q).
 No function here is "parity unpinned".
 """
 from .numerics import bf16_round, bf16_bits, bf16_from_bits  # noqa: F401
@@ -35,4 +36,5 @@ from .decoder import (  # noqa: F401
 )
 from .verify import accept_prefix, verify_chunks, draft_chain, prefill_context  # noqa: F401
 from .scheduler import SchedulerOracle, EngineItem  # noqa: F401
+from .sampling import inverse_cdf, compressed_to_dense, speculative_accept  # noqa: F401
 from .importance import importance_from_attention, importance_scores, mean_draft_importance  # noqa: F401
