@@ -225,6 +225,28 @@ int32_t synera_chunk_dispatch(const float* d_top1_prob, const int32_t* d_cu_rows
                               float k_slope, float* d_mean_conf, float* d_p_conf, void* stream);
 
 /*
+ * Stochastic verification of the batch that the LAST synera_verify on this context forwarded: speculative
+ * sampling against the LLM distributions that call computed (Section 4.5 verifies with q(x | prefix), ...,
+ * q(x | prefix, x_1..x_k) under top-k / top-p sampling and Section 4.2 transmits the SLM distributions p in
+ * compressed form; the acceptance rule itself is the published speculative-sampling rule the paper cites).
+ * Per request: draft j is accepted with probability min(1, q_j(x_j) / p_j(x_j)); at the first rejection the
+ * emitted token is drawn from norm(max(0, q_j - p_j)); after k_i acceptances from the distribution that
+ * follows the last draft.  q = softmax of the LM-head rows (temperature 1); p_j = the transmitted top-k list
+ * of draft row j, renormalised to sum 1 (0 outside the list; a draft absent from its list is rejected).
+ *   d_tokens    dev [T]            as given to synera_verify
+ *   d_p_id / d_p_prob  dev [R][k_list], 1 <= k_list <= 8 (EUNSUP above): the lists, row order = draft rows
+ *   d_u_accept  dev f32 [R]        uniform numbers in [0, 1), one per draft row
+ *   d_u_sample  dev f32 [B]        one per request, for the emitted token (smallest id whose inclusive
+ *                                   cumulative weight, in id order, exceeds u * total)
+ *   d_accept_len dev i32 [B], d_token dev i32 [B]
+ * Every request of that verify must have had u_i >= 1 (the row of its last uncached token supplies the
+ * first distribution): EUNSUP otherwise.  Errors: EINVAL (null pointers, k_list < 1, no verify to read), EHIP.
+ */
+int32_t synera_stochastic_accept(synera_ctx* ctx, const int32_t* d_tokens, int32_t k_list, const int32_t* d_p_id,
+                                 const float* d_p_prob, const float* d_u_accept, const float* d_u_sample,
+                                 int32_t* d_accept_len, int32_t* d_token, void* stream);
+
+/*
  * Importance scores of the batch that the LAST synera_verify on this context forwarded (Section 3.2:
  * the column-wise sum of the attention matrix softmax(Q K^T / sqrt(d_k)); the paper names neither layer
  * nor head handling: these are the last decoder layer's, averaged over the query heads).  For request i

@@ -79,6 +79,8 @@ _lib.synera_debug_read_scratch.restype = C.c_int32
 _lib.synera_debug_read_scratch.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp]
 _lib.synera_debug_set_gemm_tile.restype = C.c_int32
 _lib.synera_debug_set_gemm_tile.argtypes = [C.c_int32]
+_lib.synera_stochastic_accept.restype = C.c_int32
+_lib.synera_stochastic_accept.argtypes = [_vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.synera_topp_count.restype = C.c_int32
 _lib.synera_topp_count.argtypes = [_vp, C.c_int64, C.c_int32, C.c_float, _vp, _vp, _vp]
 _lib.synera_importance.restype = C.c_int32
@@ -315,6 +317,18 @@ class Verifier:
                                     _dev(out["mean"]), _dev(out["p_imp"]), _stream())
         _check(st, "synera_importance")
         return out
+
+    def stochastic_accept(self, tokens, p_id, p_prob, u_accept, u_sample):
+        """Speculative sampling on the batch the last verify() forwarded -> (accept_len i32 [B], token i32 [B])."""
+        R, k_list = p_id.shape
+        B = u_sample.numel()
+        acc = torch.empty(B, dtype=torch.int32, device=tokens.device)
+        tok = torch.empty(B, dtype=torch.int32, device=tokens.device)
+        st = _lib.synera_stochastic_accept(self._ctx, _dev(tokens, torch.int32), k_list, _dev(p_id, torch.int32),
+                                           _dev(p_prob, torch.float32), _dev(u_accept, torch.float32),
+                                           _dev(u_sample, torch.float32), _dev(acc), _dev(tok), _stream())
+        _check(st, "synera_stochastic_accept")
+        return acc, tok
 
     def debug_read_scratch(self, which, out):
         """Test hook: copy an intermediate buffer of the last layer of the last verify into `out`."""

@@ -107,8 +107,10 @@ struct synera_ctx {
   // batch of the last synera_verify, for synera_importance: device pointers into that call's metadata slot
   struct {
     const int32_t *ctx_len, *cu_tok, *block_table, *cu_keys, *items, *n_unc, *cu_draft;
-    int32_t B, T, n_items, max_pages, total_keys;
+    BatchMeta meta;
+    int32_t B, T, R, n_items, max_pages, total_keys;
     bool valid;
+    bool all_rows_kept;          // every request had an uncached token: c->logits / lm_ids / lm_p hold all LM-head rows
   } last;
   float* gparts;               // K-split slices of one projection: [SY_MAX_DEFERRED_SPLIT][max_tokens][max(d, q+2kv)]
   size_t gpart_elems;          // elements of one slice slot
@@ -713,11 +715,31 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   c->last.items = p.d_imp_items;
   c->last.B = B;
   c->last.T = T;
+  c->last.R = p.R;
+  c->last.meta = p.meta;
+  c->last.all_rows_kept = p.R_all == p.R + B;
   c->last.n_items = p.n_imp_items;
   c->last.max_pages = max_pages;
   c->last.total_keys = p.total_keys;
   c->last.valid = true;
   return finish_call(c, p, s);
+}
+
+// ------------------------------------------------------------------------------------ stochastic verification
+extern "C" int32_t synera_stochastic_accept(synera_ctx* c, const int32_t* d_tokens, int32_t k_list,
+                                            const int32_t* d_p_id, const float* d_p_prob, const float* d_u_accept,
+                                            const float* d_u_sample, int32_t* d_accept_len, int32_t* d_token,
+                                            void* stream_) {
+  if (!c || !d_tokens || !d_p_id || !d_p_prob || !d_u_accept || !d_u_sample || !d_accept_len || !d_token)
+    return SYNERA_EINVAL;
+  if (k_list < 1) return SYNERA_EINVAL;
+  if (k_list > 8) return SYNERA_EUNSUP;
+  if (!c->last.valid) return SYNERA_EINVAL;                  // no verification to take the distributions from
+  if (!c->last.all_rows_kept) return SYNERA_EUNSUP;          // a request without an uncached token has no q(x | prefix)
+  HIP_TRY(launch_stochastic_accept(c->logits, c->desc.vocab, c->lm_ids, c->lm_p, d_tokens, c->last.meta, c->last.B,
+                                   k_list, d_p_id, d_p_prob, d_u_accept, d_u_sample, d_accept_len, d_token,
+                                   static_cast<hipStream_t>(stream_)));
+  return SYNERA_OK;
 }
 
 // ------------------------------------------------------------------------------------ importance scores

@@ -64,6 +64,10 @@ hipError_t launch_confidence_topk(const void* logits, int dtype, int64_t rows, i
                                   int32_t* ids, float* probs, float* margin, float* H, hipStream_t s);
 hipError_t launch_topp_count(const float* probs, int64_t rows, int k, float top_p, int32_t* n, float* mass,
                              hipStream_t s);
+hipError_t launch_stochastic_accept(const float* logits, int vocab, const int32_t* lm_ids, const float* lm_p,
+                                    const int32_t* tokens, const BatchMeta& m, int B, int k_list, const int32_t* p_id,
+                                    const float* p_prob, const float* u_accept, const float* u_sample,
+                                    int32_t* accept_len, int32_t* out_token, hipStream_t s);
 hipError_t launch_chunk_dispatch(const float* p1, const int32_t* cu_rows, int B, float c_th, float k_slope,
                                  float* mean_conf, float* p_conf, hipStream_t s);
 

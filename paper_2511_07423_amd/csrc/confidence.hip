@@ -324,6 +324,133 @@ hipError_t launch_topp_count(const float* probs, int64_t rows, int k, float top_
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ stochastic verification
+// Speculative sampling of one request per block (the rule the paper cites for its "draft & verify" under
+// top-k / top-p sampling): draft j is accepted with probability min(1, q_j(x_j) / p_j(x_j)); at the first
+// rejection a token is drawn from norm(max(0, q_j - p_j)), after k acceptances from q_{k+1}.  q_j is the softmax
+// of an LM-head row that the verify call left behind (row of the last uncached token for j = 0, of draft
+// j-1 after that; its maximum and normaliser come from the confidence pass: q_v = exp(l_v - l_max) p_top1);
+// p_j is the device's transmitted top-k list renormalised to 1.  The uniforms are inputs.
+// Thread 0 walks the drafts; the draw is block-wide: every thread sums a contiguous slice of the vocabulary
+// (fp64 accumulators), the slices are scanned, and the thread whose slice holds the target walks it.
+__global__ __launch_bounds__(256) void stochastic_accept_kernel(
+    const float* __restrict__ logits, int vocab, const int32_t* __restrict__ lm_ids, const float* __restrict__ lm_p,
+    const int32_t* __restrict__ tokens, BatchMeta m, int k_list, const int32_t* __restrict__ p_id,
+    const float* __restrict__ p_prob, const float* __restrict__ u_accept, const float* __restrict__ u_sample,
+    int32_t* __restrict__ accept_len, int32_t* __restrict__ out_token) {
+  __shared__ int sh_n, sh_slice, sh_token;
+  __shared__ double sh_sum[256];
+  __shared__ double sh_before;
+  const int i = blockIdx.x, tid = threadIdx.x;
+  const int r0 = m.cu_draft[i], k = m.cu_draft[i + 1] - r0;
+  const int32_t* d = tokens + m.cu_tok[i] + m.n_unc[i];
+  if (tid == 0) {
+    int n = 0;
+    for (; n < k; ++n) {
+      const int row = n == 0 ? m.first_row[i] : r0 + n - 1;
+      const float* l = logits + (size_t)row * vocab;
+      int x = d[n];
+      x = x < 0 ? 0 : (x >= vocab ? vocab - 1 : x);
+      const float q_x = __expf(l[x] - l[lm_ids[row]]) * lm_p[row];
+      float sum = 0.f, p_x = 0.f;
+      for (int e = 0; e < k_list; ++e) {
+        const float pe = p_prob[(size_t)(r0 + n) * k_list + e];
+        sum += pe;
+        if (p_id[(size_t)(r0 + n) * k_list + e] == x) p_x += pe;
+      }
+      const float ratio = p_x > 0.f ? fminf(1.0f, q_x * sum / p_x) : 0.f;
+      if (!(u_accept[r0 + n] < ratio)) break;
+    }
+    sh_n = n;
+    sh_token = -1;
+  }
+  __syncthreads();
+  const int n = sh_n;
+  const int row = (n == 0) ? m.first_row[i] : r0 + n - 1;      // n == k: the row after the last draft
+  const float* l = logits + (size_t)row * vocab;
+  const float l_max = l[lm_ids[row]], p_top = lm_p[row];
+  // the list to subtract (none after a full accept)
+  int ids[8];
+  float pr[8];
+  float list_sum = 0.f;
+  const int n_list = n < k ? k_list : 0;
+  for (int e = 0; e < 8; ++e) {
+    ids[e] = -1;
+    pr[e] = 0.f;
+    if (e < n_list) {
+      ids[e] = p_id[(size_t)(r0 + n) * k_list + e];
+      pr[e] = p_prob[(size_t)(r0 + n) * k_list + e];
+      list_sum += pr[e];
+    }
+  }
+  const float list_inv = list_sum > 0.f ? 1.0f / list_sum : 0.f;   // an all-zero list subtracts nothing
+  auto weight = [&](int v) {
+    float w = __expf(l[v] - l_max) * p_top;
+    for (int e = 0; e < 8; ++e)
+      if (ids[e] == v) w -= pr[e] * list_inv;
+    return w > 0.f ? w : 0.f;
+  };
+  const int seg = (vocab + 255) / 256;
+  const int v0 = tid * seg, v1 = min(vocab, v0 + seg);
+  double mine = 0.0;
+  for (int v = v0; v < v1; ++v) mine += (double)weight(v);
+  sh_sum[tid] = mine;
+  __syncthreads();
+  if (tid == 0) {
+    double total = 0.0;
+    for (int t = 0; t < 256; ++t) total += sh_sum[t];
+    const double target = (double)u_sample[i] * total;
+    double c = 0.0;
+    int slice = 255;
+    for (int t = 0; t < 256; ++t) {
+      if (c + sh_sum[t] > target) {
+        slice = t;
+        break;
+      }
+      c += sh_sum[t];
+    }
+    if (slice == 255 && !(c + sh_sum[255] > target)) {          // rounding put the target at the very end
+      c = 0.0;
+      for (int t = 0; t < 255; ++t) c += sh_sum[t];
+    }
+    sh_slice = slice;
+    sh_before = c;
+  }
+  __syncthreads();
+  if (tid == sh_slice) {
+    double total = 0.0;
+    for (int t = 0; t < 256; ++t) total += sh_sum[t];
+    const double target = (double)u_sample[i] * total;
+    double c = sh_before;
+    int token = -1, last_positive = -1;
+    for (int v = v0; v < v1; ++v) {
+      const float w = weight(v);
+      if (w > 0.f) last_positive = v;
+      c += (double)w;
+      if (c > target && w > 0.f) {
+        token = v;
+        break;
+      }
+    }
+    sh_token = token >= 0 ? token : last_positive;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    accept_len[i] = n;
+    out_token[i] = sh_token >= 0 ? sh_token : lm_ids[row];      // degenerate residual (p == q): the row's mode
+  }
+}
+
+hipError_t launch_stochastic_accept(const float* logits, int vocab, const int32_t* lm_ids, const float* lm_p,
+                                    const int32_t* tokens, const BatchMeta& m, int B, int k_list, const int32_t* p_id,
+                                    const float* p_prob, const float* u_accept, const float* u_sample,
+                                    int32_t* accept_len, int32_t* out_token, hipStream_t s) {
+  if (B <= 0) return hipSuccess;
+  stochastic_accept_kernel<<<B, 256, 0, s>>>(logits, vocab, lm_ids, lm_p, tokens, m, k_list, p_id, p_prob, u_accept,
+                                             u_sample, accept_len, out_token);
+  return hipGetLastError();
+}
+
 hipError_t launch_confidence(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride,
                              int32_t* ids, float* p1, float* H, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
