@@ -113,3 +113,19 @@ def test_topp_count_closed_forms_and_brute_force():
         n_ref = int(np.searchsorted(cum, p, side="left")) + 1
         assert abs(n - n_ref) <= (1 if np.min(np.abs(cum - p)) < 1e-5 else 0)
         assert mass >= p - 1e-6 and (n == 1 or mass - float(pr32[n - 1]) < p + 1e-6)
+
+
+def test_golden_points_of_the_dispatch_curves():
+    """tests/golden/dispatch_probabilities.txt: values worked by hand from the two printed equations."""
+    import os
+    import oracle
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "dispatch_probabilities.txt")
+    n = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        fn, x, th, slope, want, tol = line.split()
+        got = {"p_conf": oracle.p_conf, "p_imp": oracle.p_imp}[fn](float(x), float(th), float(slope))
+        assert abs(got - float(want)) <= float(tol), line
+        n += 1
+    assert n == 13
