@@ -675,6 +675,10 @@ static hipError_t launch_tall(const GemmArgs& g, hipStream_t s) {
 // inside one fragment), so the stage layout uses that plain mask.  K slices are only ever stored for
 // the consumer to add (GemmArgs::deferred): there is no atomic path, whose per-element operands would
 // need every accumulator in a VGPR at once.
+// (Tried on top of this: the four wavefronts as 2 x 2 -- each owning half the rows of half the columns --
+// with 224-column tiles, which halves the activation-fragment reads from LDS and gives the 8B gate/up
+// projection 256 tiles instead of 224.  Correct, and exactly as fast: the launch is limited by how much MFMA
+// work the chip sustains on real data, not by LDS traffic or idle compute units.)
 __device__ __forceinline__ int swz16(int row, int chunk) { return (row * 4 + (chunk ^ ((row >> 1) & 3))) * 8; }
 
 template <int MT, int EPI>
@@ -952,7 +956,7 @@ static int tall_split(const GemmArgs& g, int v) {
   if (g.epilogue == GEMM_SWIGLU_BF16) return 1;
   if (v >= kFirstTall16 && !g.deferred) return 1;   // these tiles split K only into stored slices
   const int bm = kVariants[v].bm;
-  const long tiles = (long)((g.M + bm - 1) / bm) * (g.N / 256);
+  const long tiles = (long)((g.M + bm - 1) / bm) * (g.N / kVariants[v].bn);
   long split = 256 / tiles;
   const long most = g.K / 32 / 8;               // at least 8 K steps per slice
   split = split < most ? split : most;
@@ -961,7 +965,7 @@ static int tall_split(const GemmArgs& g, int v) {
 }
 static double tall_cost(const GemmArgs& g, int v, int split) {
   const int bm = kVariants[v].bm;
-  const long tiles = (long)((g.M + bm - 1) / bm) * (g.N / 256);
+  const long tiles = (long)((g.M + bm - 1) / bm) * (g.N / kVariants[v].bn);
   const long rounds = (tiles * split + 255) / 256;
   const double steps = (double)(g.K / 32) / split;
   // per K slice and 2.2 M outputs: ~8.5 us of atomic adds, or ~3 us to store the slice and read it back
@@ -972,6 +976,7 @@ static int pick_tall(const GemmArgs& g, int* split_out) {
   int best = -1, best_split = 1;
   double best_cost = 0.0;
   for (int v = kFirstTall; v < kNumVariants; ++v) {
+    if (!variant_fits(g, v)) continue;
     const int tile_split = tall_split(g, v);
     for (int split = 1; split <= tile_split; ++split) {    // fewer slices than fit can win: less to merge
       const double c = tall_cost(g, v, split);

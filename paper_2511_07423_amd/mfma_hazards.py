@@ -101,14 +101,15 @@ def check_kernel(name, lines):
 
 
 def check_file(path, name_filter="gemm_tall"):
-    """Check every kernel of the assembly file whose symbol contains `name_filter`.
+    """Check every kernel of the assembly file whose symbol contains `name_filter` (a string or several).
     -> (number of kernels checked, number of inline MFMAs seen, hazard messages)"""
     with open(path) as f:
         lines = f.read().splitlines()
+    filters = (name_filter,) if isinstance(name_filter, str) else tuple(name_filter)
     kernels, cur, name = [], None, None
     for no, line in enumerate(lines):
         m = re.match(r"^(_Z\w+):", line)
-        if m and cur is None and name_filter in m.group(1):
+        if m and cur is None and any(f in m.group(1) for f in filters):
             name, cur = m.group(1), []
         elif cur is not None:
             if line.startswith(".Lfunc_end"):

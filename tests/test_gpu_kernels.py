@@ -161,7 +161,8 @@ def _split_pair(x):
 
 # tile configurations: 11, 13, 14 = 128x128 / 128x256 / 64x256 asynchronous-copy kernels, 18..23 = tall tiles of 128..288 rows (32-row blocks), 24..28 = 144..272 rows and 29..33 = 128..256 rows (16-row blocks)
 @pytest.mark.parametrize("variant", [-1, 11, 13, 14] + list(range(18, 34)))
-@pytest.mark.parametrize("M,N,K", [(1, 256, 64), (97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (600, 4096, 1792)])
+@pytest.mark.parametrize("M,N,K", [(1, 256, 64), (97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (600, 4096, 1792),
+                                   (532, 1792, 1024), (97, 1792, 320), (545, 1792, 512)])
 def test_gemm_pair_activations_every_tile_and_epilogue(variant, M, N, K):
     """(hi, lo) activations through each tile configuration: store (K split included), residual add,
     SwiGLU; compared with the float64 product of the same bf16 operands."""
@@ -199,7 +200,7 @@ def test_gemm_pair_activations_every_tile_and_epilogue(variant, M, N, K):
 
 
 @pytest.mark.parametrize("variant", [-1, 18, 21, 23] + list(range(24, 34)))
-@pytest.mark.parametrize("M,N,K", [(97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (545, 4096, 1792)])
+@pytest.mark.parametrize("M,N,K", [(97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (545, 4096, 1792), (532, 1792, 2048)])
 def test_gemm_stored_k_slices_sum_to_the_product(variant, M, N, K):
     """K split into stored slices (the mode the decoder layers use on tall tiles): the slices, added in
     order, give the product; a planner that does not split returns it whole."""
