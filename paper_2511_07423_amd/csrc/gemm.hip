@@ -678,7 +678,11 @@ static hipError_t launch_tall(const GemmArgs& g, hipStream_t s) {
 // (Tried on top of this: the four wavefronts as 2 x 2 -- each owning half the rows of half the columns --
 // with 224-column tiles, which halves the activation-fragment reads from LDS and gives the 8B gate/up
 // projection 256 tiles instead of 224.  Correct, and exactly as fast: the launch is limited by how much MFMA
-// work the chip sustains on real data, not by LDS traffic or idle compute units.)
+// work the chip sustains on real data, not by LDS traffic or idle compute units.  Likewise a software-
+// pipelined K loop that issues each step's last 16 MFMAs behind the next step's barrier, over the LDS round
+// trip of its first fragment reads: correct, same speed.  The shader clock reads 2.08 GHz instead of
+// 2.4 GHz while this kernel runs on random operands; on all-zero operands it stays at 2.4 GHz and the same
+// launch takes 157 us instead of 199.)
 __device__ __forceinline__ int swz16(int row, int chunk) { return (row * 4 + (chunk ^ ((row >> 1) & 3))) * 8; }
 
 template <int MT, int EPI>
@@ -885,6 +889,7 @@ static hipError_t launch_tall16(const GemmArgs& g, hipStream_t s) {
   }
   return hipGetLastError();
 }
+
 
 // ---------------------------------------------------------------------------------------------
 // Tile configurations.  N tile 256 halves the weight re-reads from L2 per MFMA; the 128-wide
