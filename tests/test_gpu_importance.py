@@ -79,4 +79,10 @@ def test_importance_scores_match_the_oracle(shape):
     assert 0 < (p > 0).sum() and (p < 1).sum() > 0                 # the threshold splits this batch
     with pytest.raises(synera.SyneraError):
         ver.importance(ctx, unc, k + 1, n_pages, kp)             # not the batch that was verified
+    # any later call that re-plans the batch metadata (here a raw K/V append) retires the verify's state
+    rows = torch.zeros((1, shape.n_kv_heads, shape.head_dim), dtype=torch.bfloat16, device=DEV)
+    ver.kv_append(0, ctx[:1] + unc[:1] + k[:1] - 1, np.ones(1, np.int32), rows, rows, bt[:1], n_pages, kp, vp)
+    with pytest.raises(synera.SyneraError) as e:
+        ver.importance(ctx, unc, k, n_pages, kp)
+    assert e.value.status == synera.EINVAL
     ver.close()

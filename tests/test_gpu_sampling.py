@@ -98,6 +98,11 @@ def test_stochastic_accept_matches_the_oracle(vocab, k_list):
         checked += 1
     assert checked >= B * 3 // 4
     assert 0 < np.mean(np.asarray(lens) == k) < 1 and min(lens) == 0      # full accepts and early rejections both occur
+    with pytest.raises(synera.SyneraError) as e:               # lists longer than 8 entries are not supported
+        ver.stochastic_accept(tokens, torch.zeros((R, 9), dtype=torch.int32, device=DEV),
+                              torch.ones((R, 9), dtype=torch.float32, device=DEV), torch.from_numpy(u_acc).to(DEV),
+                              torch.from_numpy(u_smp).to(DEV))
+    assert e.value.status == synera.EUNSUP
     # a request without an uncached token has no first distribution: refused
     ver.verify(ctx, zeros, k, tokens[:int(k.sum())], anchor, bt, n_pages, kp, vp)
     with pytest.raises(synera.SyneraError) as e:
