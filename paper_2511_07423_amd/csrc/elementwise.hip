@@ -80,11 +80,74 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
   }
 }
 
+// The same for rows of at most 8192 values: the row stays in registers between the two passes (no re-read of
+// x), and all loads of a pass are issued before anything is stored, so they are in flight together.
+__global__ __launch_bounds__(256) void rmsnorm_row_in_registers_kernel(
+    float* __restrict__ x, const float* __restrict__ parts, int n_parts, size_t part_stride,
+    const bf16_t* __restrict__ gain, const int32_t* __restrict__ rows, bf16_t* __restrict__ y,
+    bf16_t* __restrict__ y_lo, int d, float eps) {
+  constexpr int IT = 8;                                  // 8 x 256 threads x 4 values
+  const int r = blockIdx.x;
+  const size_t row_at = (size_t)(rows ? rows[r] : r) * d;
+  float* src = x + row_at;
+  float4 v[IT];
+#pragma unroll
+  for (int k = 0; k < IT; ++k) {
+    const int c = threadIdx.x * 4 + k * 1024;
+    v[k] = c < d ? *reinterpret_cast<const float4*>(src + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  for (int s = 0; s < n_parts; ++s) {
+    const float* ps = parts + (size_t)s * part_stride + row_at;
+    float4 pv[IT];
+#pragma unroll
+    for (int k = 0; k < IT; ++k) {
+      const int c = threadIdx.x * 4 + k * 1024;
+      pv[k] = c < d ? *reinterpret_cast<const float4*>(ps + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int k = 0; k < IT; ++k) {
+      v[k].x += pv[k].x; v[k].y += pv[k].y; v[k].z += pv[k].z; v[k].w += pv[k].w;
+    }
+  }
+  float ss = 0.f;
+#pragma unroll
+  for (int k = 0; k < IT; ++k) {
+    const int c = threadIdx.x * 4 + k * 1024;
+    if (n_parts > 0 && c < d) *reinterpret_cast<float4*>(src + c) = v[k];
+    ss += v[k].x * v[k].x + v[k].y * v[k].y + v[k].z * v[k].z + v[k].w * v[k].w;
+  }
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  __shared__ float red[4];
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
+  bf16_t* dst = y + (size_t)r * d;
+  bf16_t* dst_lo = y_lo + (size_t)r * d;
+#pragma unroll
+  for (int k = 0; k < IT; ++k) {
+    const int c = threadIdx.x * 4 + k * 1024;
+    if (c >= d) continue;
+    const uint2 g = *reinterpret_cast<const uint2*>(gain + c);
+    const float o0 = v[k].x * inv * bf2f(g.x & 0xFFFF), o1 = v[k].y * inv * bf2f(g.x >> 16);
+    const float o2 = v[k].z * inv * bf2f(g.y & 0xFFFF), o3 = v[k].w * inv * bf2f(g.y >> 16);
+    uint2 hi, lo;
+    hi.x = pack_bf2(o0, o1);
+    hi.y = pack_bf2(o2, o3);
+    lo.x = pack_bf2(o0 - bf2f(hi.x & 0xFFFF), o1 - bf2f(hi.x >> 16));
+    lo.y = pack_bf2(o2 - bf2f(hi.y & 0xFFFF), o3 - bf2f(hi.y >> 16));
+    *reinterpret_cast<uint2*>(dst + c) = hi;
+    *reinterpret_cast<uint2*>(dst_lo + c) = lo;
+  }
+}
+
 hipError_t launch_rmsnorm(float* x, const float* parts, int n_parts, size_t part_stride, const bf16_t* gain,
                           const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo, int n_rows, int d, float eps,
                           hipStream_t s) {
   if (n_rows <= 0) return hipSuccess;
-  rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
+  if (d <= 8192)
+    rmsnorm_row_in_registers_kernel<<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
+  else
+    rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
   return hipGetLastError();
 }
 
@@ -128,7 +191,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
   const int half = hd / 2;
   const int n_pairs = (Hq + 2 * Hkv) * half;
   const float* row = qkv + (size_t)t * (Hq + 2 * Hkv) * hd;
-  for (int p = threadIdx.x; p < n_pairs; p += 256) {
+  // the token's pairs are spread over gridDim.y blocks: few iterations per thread, all loads in flight at once
+  for (int p = blockIdx.y * 256 + threadIdx.x; p < n_pairs; p += 256 * gridDim.y) {
     const int head = p / half, i = p % half;
     float2 v = *reinterpret_cast<const float2*>(row + (size_t)head * hd + 2 * i);
     for (int s = 1; s < n_parts; ++s) {         // the projection arrives as K-split slices: add them
@@ -163,7 +227,7 @@ hipError_t launch_rope_append(const float* qkv, int n_parts, size_t part_stride,
                               bf16_t* q_hi, bf16_t* q_lo, bf16_t* k_layer, bf16_t* v_layer, int T, int Hq, int Hkv,
                               int hd, hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  rope_append_kernel<<<T, 256, 0, s>>>(qkv, n_parts, part_stride, cs, m, q_hi, q_lo, k_layer, v_layer, Hq, Hkv, hd);
+  rope_append_kernel<<<dim3(T, 4), 256, 0, s>>>(qkv, n_parts, part_stride, cs, m, q_hi, q_lo, k_layer, v_layer, Hq, Hkv, hd);
   return hipGetLastError();
 }
 

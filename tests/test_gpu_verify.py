@@ -166,3 +166,39 @@ def test_out_of_range_token_ids_are_clamped_not_followed():
         outs.append(o["logits"].cpu().numpy())
     assert np.isfinite(outs[0]).all()
     assert np.allclose(outs[0], outs[1], rtol=0, atol=1e-5)
+
+
+def test_model_wider_than_the_register_resident_rmsnorm():
+    """d_model = 8320 > 8192: RMSNorm takes its two-pass form (the row no longer fits the registers of one
+    block); a one-layer decoder, two requests, compared with the oracle."""
+    import paper_2511_07423_amd as synera
+    shape = wl.ModelShape("wide", 1, 8320, 2, 2, 64, 256, 256)
+    head = wl.draw_head_weights(shape, 51, DEV)
+    layers = [wl.draw_layer_weights(shape, 51, 0, DEV)]
+    model = oracle_model(shape, head, layers, np.float64)
+    rng = np.random.default_rng(52)
+    ctx, unc, k = np.array([0, 21], np.int32), np.array([2, 0], np.int32), np.array([3, 5], np.int32)
+    bt = np.array([[0, 1, -1], [2, 3, 4]], np.int32)
+    n_pages = 5
+    okv = oracle.PagedKV(1, n_pages, 2, 64)
+    anchors = np.array([0, oracle.prefill_context(model, okv, bt[1], rng.integers(0, 256, 21))], np.int32)
+    kp, vp = gh.nan_pool(shape, n_pages, DEV, False), gh.nan_pool(shape, n_pages, DEV, True)
+    kd, vd = gh._oracle_pool_to_device(okv, DEV)
+    for t0 in range(0, 21, 16):
+        m = min(16, 21 - t0)
+        kp[:, bt[1, t0 // 16], :, :m, :] = kd[:, bt[1, t0 // 16], :, :m, :]
+        vp[:, bt[1, t0 // 16], :, :, :m] = vd[:, bt[1, t0 // 16], :, :, :m]
+    toks = [rng.integers(0, 256, int(unc[i] + k[i])) for i in range(2)]
+    reqs = [{"block_table": bt[i], "ctx_len": int(ctx[i]), "uncached": toks[i][:unc[i]], "drafts": toks[i][unc[i]:],
+             "anchor": int(anchors[i])} for i in range(2)]
+    want = oracle.verify_chunks(model, okv, reqs)
+    ver = synera.Verifier(shape, head, layers, max_batch=2, max_tokens=16, max_pages=3)
+    out = ver.verify(ctx, unc, k, torch.from_numpy(np.concatenate(toks).astype(np.int32)).to(DEV),
+                     torch.from_numpy(anchors).to(DEV), bt, n_pages, kp, vp)
+    torch.cuda.synchronize()
+    err = np.abs(out["logits"].double().cpu().numpy() - want["logits"]).max()
+    print(f"\n[wide d=8320] max|dlogit|={err:.3e}", flush=True)
+    assert err <= gh.LOGIT_TOL
+    safe = want["margin"] >= gh.MARGIN
+    assert np.array_equal(out["argmax"].cpu().numpy()[safe], want["argmax"][safe])
+    ver.close()
