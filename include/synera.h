@@ -259,7 +259,7 @@ int32_t synera_stochastic_accept(synera_ctx* ctx, const int32_t* d_tokens, int32
  * positions; d_p_imp = the probability of offloading by importance (Section 4.2, second equation):
  * 0 for i <= i_th/2, 1 for i > i_th, else 1 / (1 + exp(theta ((i - i_th/2) / (i_th/2) - 1/2))); the paper
  * uses theta = -10.  Errors: EINVAL (null pointers, no verify since the last kv_append / verify error,
- * n_scores mismatch, i_th <= 0 with d_p_imp), EHIP.
+ * a pool or n_scores other than that verify's, i_th <= 0 with d_p_imp), EHIP.
  */
 int32_t synera_importance(synera_ctx* ctx, int32_t n_pages_in_pool, const void* d_k_pool, int64_t n_scores,
                           float* d_importance, float i_th, float theta, float* d_mean_importance,

@@ -108,7 +108,8 @@ struct synera_ctx {
   struct {
     const int32_t *ctx_len, *cu_tok, *block_table, *cu_keys, *items, *n_unc, *cu_draft;
     BatchMeta meta;
-    int32_t B, T, R, n_items, max_pages, total_keys;
+    int32_t B, T, R, n_items, max_pages, total_keys, n_pages_in_pool;
+    const void* k_pool;
     bool valid;
     bool all_rows_kept;          // every request had an uncached token: c->logits / lm_ids / lm_p hold all LM-head rows
   } last;
@@ -715,6 +716,8 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   c->last.items = p.d_imp_items;
   c->last.B = B;
   c->last.T = T;
+  c->last.n_pages_in_pool = n_pages_in_pool;
+  c->last.k_pool = d_k_pool;
   c->last.R = p.R;
   c->last.meta = p.meta;
   c->last.all_rows_kept = p.R_all == p.R + B;
@@ -749,6 +752,8 @@ extern "C" int32_t synera_importance(synera_ctx* c, int32_t n_pages_in_pool, con
   if (!c || !d_k_pool || !d_importance || n_pages_in_pool < 1) return SYNERA_EINVAL;
   if (!c->last.valid) return SYNERA_EINVAL;                  // no verification to take the scores from
   if (n_scores != c->last.total_keys) return SYNERA_EINVAL;
+  // the block tables kept from that verify index this pool and no other
+  if (d_k_pool != c->last.k_pool || n_pages_in_pool != c->last.n_pages_in_pool) return SYNERA_EINVAL;
   if (d_p_imp && !(i_th > 0.0f)) return SYNERA_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream_);
   const synera_model_desc& m = c->desc;
