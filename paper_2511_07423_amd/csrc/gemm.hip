@@ -685,9 +685,10 @@ static hipError_t launch_tall(const GemmArgs& g, hipStream_t s) {
 // launch takes 157 us instead of 199.)
 __device__ __forceinline__ int swz16(int row, int chunk) { return (row * 4 + (chunk ^ ((row >> 1) & 3))) * 8; }
 
-template <int MT, int EPI>
+template <int MT, int NF, int EPI>
 __global__ __launch_bounds__(256) void gemm_tall16_kernel(GemmArgs g) {
-  constexpr int BM = 16 * MT, BN = 256, BK = 32;
+  constexpr int BM = 16 * MT, BN = 64 * NF, BK = 32;   // NF column fragments of 16 per wavefront
+  static_assert(NF == 2 || NF == 4, "SwiGLU pairs the fragments (gate, up): NF must be even");
   constexpr int A_INS = 2 * MT;                  // copy instructions (16 tile rows each) for [A_hi | A_lo]
   constexpr int A_IPW = (A_INS + 3) / 4;         // per wavefront; a surplus one repeats the last group
   constexpr int W_IPW = BN / 16 / 4;
@@ -753,27 +754,27 @@ __global__ __launch_bounds__(256) void gemm_tall16_kernel(GemmArgs g) {
     dst[j] = grp * 16 * BK * 2;
   }
 
-  f32x4 acc[MT][4];
+  f32x4 acc[MT][NF];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NF; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int l16 = lane & 15, kc = lane >> 4;
   const int a_off = swz16(l16, kc);                               // + i * 16 rows; + BM rows: lo
-  const int w_off = 2 * BM * BK + swz16(wave * 64 + l16, kc);     // + j * 16 rows
+  const int w_off = 2 * BM * BK + swz16(wave * 16 * NF + l16, kc);   // + j * 16 rows
 #define SY_COPY(J_, NXT, STEP) glds16_at(src[J_] + (size_t)(STEP) * BK, NXT + dst[J_]);
 #define SY_ISSUE(NXT, STEP) _Pragma("unroll") for (int j = 0; j < IPW; ++j) SY_COPY(j, NXT, STEP)
 #define SY_MFMA(ACC, FW, FA, I_)                                                                  \
   {                                                                                               \
-    if ((I_) < 16) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(FW), "v"(FA)); \
+    if ((I_) * NF < 64) asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(FW), "v"(FA)); \
     else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(ACC) : "v"(FW), "v"(FA)); \
   }
 // The copies of K step s+2 are spread over the row blocks of step s, one per block (see gemm_tall_kernel).
 #define SY_MULT(STAGE, NXT, NSTEP)                                                                \
   {                                                                                               \
-    bf16x8 fw[4];                                                                                 \
-    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                                 \
+    bf16x8 fw[NF];                                                                                \
+    _Pragma("unroll") for (int j = 0; j < NF; ++j)                                                \
         fw[j] = *reinterpret_cast<const bf16x8*>(STAGE + w_off + j * 16 * BK);                    \
     bf16x8 fa[MT + 2], fl[MT + 2];                                                                \
     _Pragma("unroll") for (int i = 0; i < 2 && i < MT; ++i) {                                     \
@@ -786,8 +787,8 @@ __global__ __launch_bounds__(256) void gemm_tall16_kernel(GemmArgs g) {
         fl[i + 2] = *reinterpret_cast<const bf16x8*>(STAGE + a_off + (BM + (i + 2) * 16) * BK);   \
       }                                                                                           \
       if (i < IPW) SY_COPY(i, NXT, NSTEP)                                                         \
-      _Pragma("unroll") for (int j = 0; j < 4; ++j) SY_MFMA(acc[i][j], fw[j], fa[i], i)           \
-      _Pragma("unroll") for (int j = 0; j < 4; ++j) SY_MFMA(acc[i][j], fw[j], fl[i], i)           \
+      _Pragma("unroll") for (int j = 0; j < NF; ++j) SY_MFMA(acc[i][j], fw[j], fa[i], i)          \
+      _Pragma("unroll") for (int j = 0; j < NF; ++j) SY_MFMA(acc[i][j], fw[j], fl[i], i)          \
     }                                                                                             \
     _Pragma("unroll") for (int j = MT; j < IPW; ++j) SY_COPY(j, NXT, NSTEP)                       \
   }
@@ -830,8 +831,8 @@ __global__ __launch_bounds__(256) void gemm_tall16_kernel(GemmArgs g) {
 #pragma unroll
   for (int i = 0; i < MT; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (i < 16) asm volatile("" : "+a"(acc[i][j]));
+    for (int j = 0; j < NF; ++j) {
+      if (i * NF < 64) asm volatile("" : "+a"(acc[i][j]));
       else asm volatile("" : "+v"(acc[i][j]));
     }
 
@@ -843,7 +844,7 @@ __global__ __launch_bounds__(256) void gemm_tall16_kernel(GemmArgs g) {
     if (m >= M) continue;
     if (EPI == GEMM_SWIGLU_BF16) {
 #pragma unroll
-      for (int j = 0; j < 4; j += 2) {
+      for (int j = 0; j < NF; j += 2) {
         uint32_t hi[4], lo[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -852,15 +853,15 @@ __global__ __launch_bounds__(256) void gemm_tall16_kernel(GemmArgs g) {
           hi[r] = f2bf(v);
           lo[r] = f2bf(v - bf2f(hi[r]));
         }
-        const size_t at = (size_t)m * (g.N >> 1) + (n0 >> 1) + (wave * 2 + (j >> 1)) * 16 + nq;
+        const size_t at = (size_t)m * (g.N >> 1) + (n0 >> 1) + (wave * (NF / 2) + (j >> 1)) * 16 + nq;
         *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.c) + at) = make_uint2(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16));
         *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(g.c_lo) + at) = make_uint2(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16));
       }
     } else {
       float* c = (defer ? g.c_parts + (size_t)blockIdx.z * M * g.N : reinterpret_cast<float*>(g.c)) +
-                 (size_t)m * g.N + n0 + wave * 64 + nq;
+                 (size_t)m * g.N + n0 + wave * 16 * NF + nq;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
+      for (int j = 0; j < NF; ++j) {
         if (EPI == GEMM_ADD_F32 && !defer) {
           float4 o = *reinterpret_cast<float4*>(c + j * 16);
           o.x += acc[i][j][0];
@@ -876,15 +877,15 @@ __global__ __launch_bounds__(256) void gemm_tall16_kernel(GemmArgs g) {
   }
 }
 
-template <int MT>
+template <int MT, int NF = 4>
 static hipError_t launch_tall16(const GemmArgs& g, hipStream_t s) {
   constexpr int BM = 16 * MT;
-  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / 256;
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / (64 * NF);
   const dim3 grid(8 * ((n_tiles + 7) / 8) * m_tiles, 1, g.split_k);
   switch (g.epilogue) {
-    case GEMM_STORE_F32: gemm_tall16_kernel<MT, GEMM_STORE_F32><<<grid, 256, 0, s>>>(g); break;
-    case GEMM_ADD_F32: gemm_tall16_kernel<MT, GEMM_ADD_F32><<<grid, 256, 0, s>>>(g); break;
-    case GEMM_SWIGLU_BF16: gemm_tall16_kernel<MT, GEMM_SWIGLU_BF16><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_STORE_F32: gemm_tall16_kernel<MT, NF, GEMM_STORE_F32><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_ADD_F32: gemm_tall16_kernel<MT, NF, GEMM_ADD_F32><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_SWIGLU_BF16: gemm_tall16_kernel<MT, NF, GEMM_SWIGLU_BF16><<<grid, 256, 0, s>>>(g); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -933,7 +934,8 @@ static const Variant kVariants[] = {{128, 128}, {128, 256}, {256, 128}, {256, 25
                                    {64, 256}, {128, 128}, {64, 128},
                                    {128, 256}, {160, 256}, {192, 256}, {224, 256}, {256, 256}, {288, 256},   // 18..: tall tiles, 32-row blocks
                                    {144, 256}, {176, 256}, {208, 256}, {240, 256}, {272, 256},   // 24..: tall tiles, 16-row blocks
-                                   {128, 256}, {160, 256}, {192, 256}, {224, 256}, {256, 256}};
+                                   {128, 256}, {160, 256}, {192, 256}, {224, 256}, {256, 256},
+                                   {128, 128}, {144, 128}, {160, 128}, {176, 128}, {192, 128}};   // 34..: the same, 128 columns
 static const int kFirstTall = 18, kFirstTall16 = 24;
 static const int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -951,11 +953,17 @@ static bool variant_fits(const GemmArgs& g, int v) {
 //   K steps per block x t_step(BM) us              (fits of MI355X timings at M = 200..1030: 0.12 us plus
 //                                                    0.19 us per 32-row block, or 0.0825 us per 16-row block:
 //                                                    at equal height the 16-row form is ~13 % faster, the
-//                                                    32-row form is the only one that reaches 288 rows)
+//                                                    32-row form is the only one that reaches 288 rows;
+//                                                    128-column tiles scale the MFMA part by 1/2)
 // plus, with K split, the merge of the partial tiles (atomic adds, or stores that the consumer kernel sums).
 static double tall_step_us(int v) {
-  const int bm = kVariants[v].bm;
-  return v < kFirstTall16 ? 0.12 + 0.19 * (bm / 32) : 0.12 + 0.0825 * (bm / 16);
+  const int bm = kVariants[v].bm, bn = kVariants[v].bn;
+  if (v < kFirstTall16) return 0.12 + 0.19 * (bm / 32);
+  const double mfma = 0.12 + 0.0825 * (bm / 16) * (bn / 256.0);
+  // a short tile is bound by its weight stream instead: BN rows x 64 bytes per K step at the ~24 GB/s one compute
+  // unit pulls from HBM (which is why small batches want 128-column tiles: twice the blocks, all CUs streaming)
+  const double stream = bn * 64 / 24e3;
+  return mfma > stream ? mfma : stream;
 }
 static int tall_split(const GemmArgs& g, int v) {
   if (g.epilogue == GEMM_SWIGLU_BF16) return 1;
@@ -1004,7 +1012,10 @@ static int pick_variant(const GemmArgs& g) {
   // (verification batches), the 64-row asynchronous-copy kernel below that (decode steps), 128x128 where N
   // is not a multiple of 256.
   if (g.a_lo) {
-    if (g.M > 96 && variant_fits(g, kFirstTall)) return pick_tall(g, nullptr);
+    if (g.M > 96) {
+      const int v = pick_tall(g, nullptr);
+      if (v >= 0) return v;
+    }
     if (variant_fits(g, 14)) return 14;
     return 11;
   }
@@ -1087,6 +1098,11 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     case 31: return launch_tall16<12>(g, s);
     case 32: return launch_tall16<14>(g, s);
     case 33: return launch_tall16<16>(g, s);
+    case 34: return launch_tall16<8, 2>(g, s);
+    case 35: return launch_tall16<9, 2>(g, s);
+    case 36: return launch_tall16<10, 2>(g, s);
+    case 37: return launch_tall16<11, 2>(g, s);
+    case 38: return launch_tall16<12, 2>(g, s);
     default: return hipErrorInvalidValue;
   }
 #undef SY_VARIANT
