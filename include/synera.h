@@ -323,6 +323,16 @@ int32_t synera_gemm_bf16(const void* d_a, const void* d_a_lo, const void* d_w, f
 int32_t synera_debug_set_gemm_tile(int32_t variant);
 
 /*
+ * Test hook, host only (no GPU call): the tile (rows x columns) and the number of K slices the planner
+ * gives a projection of M rows with (hi, lo) activations -- the form every projection of Section 3.4's
+ * partial prefill takes.  epilogue as in synera_debug_gemm_epilogue; stored_slices != 0 plans the decoder
+ * layers' mode (K slices stored for the consumer kernel), 0 the stand-alone mode (slices meet through
+ * atomic adds).  Outputs are host pointers.  Errors: EINVAL, EUNSUP (N % 128, 256 for SwiGLU, K % 64).
+ */
+int32_t synera_debug_gemm_plan(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices,
+                               int32_t* h_tile_rows, int32_t* h_tile_cols, int32_t* h_k_slices);
+
+/*
  * Test hook: one launch of the projection GEMM with the epilogue the decoder layers use
  * (Section 3.4's partial prefill runs these three forms per layer).  Activations are the
  * bf16 pair d_a + d_a_lo ([M][K] each).  epilogue 0: d_c f32 [M][N] = A W0^T; 1: d_c += A W0^T

@@ -87,6 +87,8 @@ _lib.synera_importance.restype = C.c_int32
 _lib.synera_importance.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp, C.c_float, C.c_float, _vp, _vp, _vp]
 _lib.synera_debug_gemm_deferred.restype = C.c_int32
 _lib.synera_debug_gemm_deferred.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), _vp]
+_lib.synera_debug_gemm_plan.restype = C.c_int32
+_lib.synera_debug_gemm_plan.argtypes = [C.c_int32] * 5 + [C.POINTER(C.c_int32)] * 3
 _lib.synera_debug_gemm_epilogue.restype = C.c_int32
 _lib.synera_debug_gemm_epilogue.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp]
 
@@ -228,6 +230,14 @@ def debug_gemm_deferred(a, a_lo, w):
                                          parts.data_ptr(), M, N, K, C.byref(n), _stream())
     _check(st, "synera_debug_gemm_deferred")
     return parts[:n.value]
+
+
+def debug_gemm_plan(M, N, K, epilogue=0, stored_slices=True):
+    """Test hook (host only): (tile rows, tile columns, K slices) the planner gives this projection."""
+    bm, bn, split = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    st = _lib.synera_debug_gemm_plan(M, N, K, epilogue, 1 if stored_slices else 0, C.byref(bm), C.byref(bn), C.byref(split))
+    _check(st, "synera_debug_gemm_plan")
+    return bm.value, bn.value, split.value
 
 
 def debug_set_gemm_tile(variant):

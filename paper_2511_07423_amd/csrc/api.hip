@@ -907,6 +907,29 @@ extern "C" int32_t synera_debug_set_gemm_tile(int32_t variant) {
   return SYNERA_OK;
 }
 
+extern "C" int32_t synera_debug_gemm_plan(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices,
+                                          int32_t* h_tile_rows, int32_t* h_tile_cols, int32_t* h_k_slices) {
+  if (!h_tile_rows || !h_tile_cols || !h_k_slices || M < 1 || N < 1 || K < 1 || epilogue < 0 || epilogue > 2)
+    return SYNERA_EINVAL;
+  if (N % (epilogue == GEMM_SWIGLU_BF16 ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
+  GemmArgs g{};
+  g.a_lo = reinterpret_cast<const bf16_t*>(uintptr_t(64));   // the planner only asks whether there is a low part
+  g.w_rows[0] = epilogue == GEMM_SWIGLU_BF16 ? N / 2 : N;
+  g.w_rows[1] = epilogue == GEMM_SWIGLU_BF16 ? N / 2 : 0;
+  g.M = M;
+  g.N = N;
+  g.K = K;
+  g.epilogue = epilogue;
+  g.split_k = 1;
+  g.deferred = stored_slices && epilogue != GEMM_SWIGLU_BF16 && gemm_uses_tall_tiles(g) ? 1 : 0;   // as run_gemm decides
+  int bm = 0, bn = 0, split = 1;
+  gemm_plan(g, &bm, &bn, &split);
+  *h_tile_rows = bm;
+  *h_tile_cols = bn;
+  *h_k_slices = split;
+  return SYNERA_OK;
+}
+
 extern "C" int32_t synera_debug_gemm_epilogue(const void* d_a, const void* d_a_lo, const void* d_w0, const void* d_w1,
                                               void* d_c, void* d_c_lo, int32_t M, int32_t N, int32_t K,
                                               int32_t epilogue, void* stream) {

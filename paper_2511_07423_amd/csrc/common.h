@@ -163,5 +163,6 @@ struct GemmArgs {
 #define SY_MAX_DEFERRED_SPLIT 8
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 int gemm_pick_split(const GemmArgs& g);
+void gemm_plan(const GemmArgs& g, int* bm, int* bn, int* split);   // tile and K slices launch_gemm would use (host only)
 bool gemm_uses_tall_tiles(const GemmArgs& g);   // the tile family that can defer the K-split merge
 void gemm_force_variant(int v);   // tuning hook: -1 automatic, else a tile configuration index

@@ -954,12 +954,14 @@ static bool variant_fits(const GemmArgs& g, int v) {
 //                                                    0.19 us per 32-row block, or 0.0825 us per 16-row block:
 //                                                    at equal height the 16-row form is ~13 % faster, the
 //                                                    32-row form is the only one that reaches 288 rows;
-//                                                    128-column tiles scale the MFMA part by 1/2)
+//                                                    128-column tiles scale the MFMA part by 0.6)
 // plus, with K split, the merge of the partial tiles (atomic adds, or stores that the consumer kernel sums).
 static double tall_step_us(int v) {
   const int bm = kVariants[v].bm, bn = kVariants[v].bn;
   if (v < kFirstTall16) return 0.12 + 0.19 * (bm / 32);
-  const double mfma = 0.12 + 0.0825 * (bm / 16) * (bn / 256.0);
+  // a 128-column tile pays the activation-fragment reads of a 256-column one for half the MFMAs: 0.6x, not 0.5x
+  // (M = 532: QKV 64.7 us on 128 x 128 tiles against 58.9 us on 128 x 256 with two K slices)
+  const double mfma = 0.12 + 0.0825 * (bm / 16) * (bn == 256 ? 1.0 : 0.6);
   // a short tile is bound by its weight stream instead: BN rows x 64 bytes per K step at the ~24 GB/s one compute
   // unit pulls from HBM (which is why small batches want 128-column tiles: twice the blocks, all CUs streaming)
   const double stream = bn * 64 / 24e3;
@@ -1025,6 +1027,13 @@ static int pick_variant(const GemmArgs& g) {
 }
 
 bool gemm_uses_tall_tiles(const GemmArgs& g) { return pick_variant(g) >= kFirstTall; }
+
+void gemm_plan(const GemmArgs& g, int* bm, int* bn, int* split) {   // host only: what launch_gemm would run
+  const int v = pick_variant(g);
+  *bm = kVariants[v].bm;
+  *bn = kVariants[v].bn;
+  *split = gemm_pick_split(g);
+}
 
 int gemm_pick_split(const GemmArgs& g) {
   if (g.epilogue == GEMM_SWIGLU_BF16) return 1;

@@ -1,0 +1,50 @@
+"""Host logic of the projection GEMM's tile planner (no GPU call): the plans of the headline batch, and
+properties every plan must have for the launch to be valid."""
+import pytest
+
+import paper_2511_07423_amd as synera
+
+STORE, ADD, SWIGLU = 0, 1, 2
+# the projections of one decoder layer and the LM head at the 8B shape (Section 6.1's cloud model class)
+D, F, QKV, VOCAB = 4096, 14336, 6144, 32000
+
+
+def test_headline_batch_plans():
+    """532 draft rows: every projection on 256-column tall tiles; the two long-K / few-tile ones split K."""
+    T = 532
+    assert synera.debug_gemm_plan(T, QKV, D, STORE) == (128, 256, 2)
+    assert synera.debug_gemm_plan(T, D, D, ADD) == (144, 256, 4)
+    assert synera.debug_gemm_plan(T, 2 * F, D, SWIGLU) == (272, 256, 1)
+    assert synera.debug_gemm_plan(T, D, F, ADD) == (144, 256, 4)
+    assert synera.debug_gemm_plan(T, VOCAB, D, STORE) == (272, 256, 1)
+
+
+def test_small_batches_take_the_narrow_tiles():
+    """About 140 rows: 128-column tiles double the blocks that stream the weights."""
+    for n, k, e in ((QKV, D, STORE), (D, D, ADD), (2 * F, D, SWIGLU), (D, F, ADD)):
+        assert synera.debug_gemm_plan(144, n, k, e)[1] == 128
+
+
+@pytest.mark.parametrize("stored", [True, False])
+@pytest.mark.parametrize("M", [1, 17, 96, 97, 130, 200, 333, 532, 777, 1030, 2048])
+@pytest.mark.parametrize("N,K,epi", [(QKV, D, STORE), (D, D, ADD), (2 * F, D, SWIGLU), (D, F, ADD), (VOCAB, D, STORE),
+                                     (128, 64, STORE), (1792, 4096, ADD), (8320, 8320, STORE)])
+def test_plans_are_launchable(M, N, K, epi, stored):
+    bm, bn, split = synera.debug_gemm_plan(M, N, K, epi, stored)
+    assert bm % 16 == 0 and bn in (128, 256) and N % bn == 0
+    assert 1 <= split <= K // 32
+    if epi == SWIGLU:
+        assert split == 1
+    if stored and bm >= 128:                    # tall tiles store their K slices: SYNERA_MAX_GEMM_SLICES
+        assert split <= 8
+
+
+def test_plan_rejects_bad_shapes():
+    with pytest.raises(synera.SyneraError):
+        synera.debug_gemm_plan(0, 128, 64)
+    with pytest.raises(synera.SyneraError):
+        synera.debug_gemm_plan(16, 192, 64)     # N % 128
+    with pytest.raises(synera.SyneraError):
+        synera.debug_gemm_plan(16, 384, 64, SWIGLU)   # N % 256 for SwiGLU
+    with pytest.raises(synera.SyneraError):
+        synera.debug_gemm_plan(16, 128, 96)     # K % 64
