@@ -316,6 +316,34 @@ int32_t synera_gemm_bf16(const void* d_a, const void* d_a_lo, const void* d_w, f
                          int32_t M, int32_t N, int32_t K, void* stream);
 
 /*
+ * Measured ceilings, for the measurement tools (not part of the verification path): what this GPU gives the
+ * kernels above, taken in the same process as their timings.  The caller times the launches (HIP events on
+ * `stream`).
+ *
+ * synera_measure_hbm_copy: one plain device copy d_dst[0 .. bytes) = d_src[0 .. bytes) by a kernel of
+ * 16-byte accesses; HBM moves 2 x bytes.  bytes a positive multiple of 16, both pointers 16-byte aligned device
+ * memory that does not overlap (else EINVAL).
+ *
+ * synera_measure_hbm_read: a read-only stream over d_src[0 .. bytes) by SYNERA_MEASURE_READ_BLOCKS blocks of
+ * 256 lanes; with seg = ceil(bytes / 16 / blocks), lane t of block b reads the 16-byte pieces b * seg + t + 256 j
+ * (j = 0, 1, ... while below (b + 1) * seg and the end), and stores the xor of all their 32-bit words to
+ * d_out[b * 256 + t] (device, SYNERA_MEASURE_READ_BLOCKS x 256
+ * words).  HBM moves `bytes`.  Same conditions on bytes and d_src.
+ *
+ * synera_measure_mfma_bf16: `blocks` blocks of four wavefronts, each issuing iters x 16
+ * v_mfma_f32_32x32x16_bf16 on register-resident operands (no memory traffic inside the loop);
+ * random_operands != 0 fills the operand registers with random signs and mantissas (the rate real data gets:
+ * the clock drops under the switching activity), 0 with constants.  d_out (device, blocks x 256 floats)
+ * receives one accumulator sum per lane -- with constant operands exactly 2 x iters.  *h_flops (host, may be
+ * NULL) receives the FLOPs of the launch.  1 <= blocks <= 4096, 1 <= iters <= 200000, else EINVAL.
+ */
+#define SYNERA_MEASURE_READ_BLOCKS 4096
+int32_t synera_measure_hbm_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream);
+int32_t synera_measure_hbm_read(uint32_t* d_out, const void* d_src, int64_t bytes, void* stream);
+int32_t synera_measure_mfma_bf16(float* d_out, int32_t blocks, int32_t iters, int32_t random_operands,
+                                 int64_t* h_flops, void* stream);
+
+/*
  * Tuning hook for the GEMM sweep: force tile configuration `variant` for every
  * later contraction whose shape it fits (-1 restores the automatic choice).
  * Process-wide; not for production callers.

@@ -87,6 +87,12 @@ _lib.synera_importance.restype = C.c_int32
 _lib.synera_importance.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp, C.c_float, C.c_float, _vp, _vp, _vp]
 _lib.synera_debug_gemm_deferred.restype = C.c_int32
 _lib.synera_debug_gemm_deferred.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), _vp]
+_lib.synera_measure_hbm_copy.restype = C.c_int32
+_lib.synera_measure_hbm_copy.argtypes = [_vp, _vp, C.c_int64, _vp]
+_lib.synera_measure_hbm_read.restype = C.c_int32
+_lib.synera_measure_hbm_read.argtypes = [_vp, _vp, C.c_int64, _vp]
+_lib.synera_measure_mfma_bf16.restype = C.c_int32
+_lib.synera_measure_mfma_bf16.argtypes = [_vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int64), _vp]
 _lib.synera_debug_gemm_plan.restype = C.c_int32
 _lib.synera_debug_gemm_plan.argtypes = [C.c_int32] * 5 + [C.POINTER(C.c_int32)] * 3
 _lib.synera_debug_gemm_epilogue.restype = C.c_int32
@@ -230,6 +236,40 @@ def debug_gemm_deferred(a, a_lo, w):
                                          parts.data_ptr(), M, N, K, C.byref(n), _stream())
     _check(st, "synera_debug_gemm_deferred")
     return parts[:n.value]
+
+
+def measure_hbm_copy(dst, src):
+    """Measurement tool: one plain device copy dst <- src (same size, 16-byte multiple); HBM moves 2 x the bytes."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("measure_hbm_copy: sizes differ")
+    st = _lib.synera_measure_hbm_copy(_dev(dst), _dev(src), nbytes, _stream())
+    _check(st, "synera_measure_hbm_copy")
+    return 2 * nbytes
+
+
+MEASURE_READ_BLOCKS = 4096
+
+
+def measure_hbm_read(out, src):
+    """Measurement tool: read-only stream over src; out (int32, 4096 x 256) gets each lane's xor. Returns the bytes read."""
+    nbytes = src.numel() * src.element_size()
+    if out.numel() < MEASURE_READ_BLOCKS * 256:
+        raise ValueError("measure_hbm_read: out needs 4096 x 256 words")
+    st = _lib.synera_measure_hbm_read(_dev(out, torch.int32), _dev(src), nbytes, _stream())
+    _check(st, "synera_measure_hbm_read")
+    return nbytes
+
+
+def measure_mfma_bf16(out, blocks, iters, random_operands=True):
+    """Measurement tool: register-resident bf16 MFMA loop; returns the FLOPs of the launch."""
+    if out.numel() < blocks * 256:
+        raise ValueError("measure_mfma_bf16: out needs blocks x 256 floats")
+    flops = C.c_int64(0)
+    st = _lib.synera_measure_mfma_bf16(_dev(out, torch.float32), blocks, iters, 1 if random_operands else 0,
+                                       C.byref(flops), _stream())
+    _check(st, "synera_measure_mfma_bf16")
+    return flops.value
 
 
 def debug_gemm_plan(M, N, K, epilogue=0, stored_slices=True):

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsynera.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "elementwise.hip", "confidence.hip", "attention.hip", "importance.hip", "gemm.hip", "scheduler.cpp"]
+SOURCES = ["api.hip", "elementwise.hip", "confidence.hip", "attention.hip", "importance.hip", "gemm.hip", "ceilings.hip", "scheduler.cpp"]
 # sources whose kernels issue MFMAs from inline assembly: their device assembly is kept and checked
 ASM_CHECKED = {"gemm.hip": "gemm_tall"}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

@@ -4,6 +4,7 @@ bench.py at the repository root):
     python -m paper_2511_07423_amd.measure confidence   # synera_confidence on a 2048 x 128256 logits block
     python -m paper_2511_07423_amd.measure gemm         # the four projection shapes of the 8B decoder at M = 532
     python -m paper_2511_07423_amd.measure sched        # host time of the scheduler per iteration (no GPU needed)
+    python -m paper_2511_07423_amd.measure ceilings     # what this GPU gives: device copy (HBM), register-resident MFMA loop
 
 Each line gives the average launch time over HIP events on the launch stream and the achieved rate
 against MI355X's peak (HBM 8 TB/s; dense bf16 MFMA 2.5 PFLOP/s, algorithmic FLOPs).  Inputs are seeded
@@ -69,6 +70,45 @@ def gemm():
                           "peak_TFLOPs": 2500.0, "frac": fl / ms / 1e9 / 2500.0}))
 
 
+def measured_ceilings(copy_bytes=1 << 30, mfma_iters=20000):
+    """The chip's measured rates next to the published ones: a 1 GiB device copy (HBM moves 2 GiB) and the
+    register-resident bf16 MFMA loop on 256 blocks, with constant and with random operands."""
+    import torch
+    import paper_2511_07423_amd as synera
+    src = torch.zeros(copy_bytes // 4, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    moved = [0]
+
+    def copy():
+        moved[0] = synera.measure_hbm_copy(dst, src)
+    ms = _time(copy, n=10)
+    res = {"hbm_copy_GBs": moved[0] / ms / 1e6}
+    del dst
+    words = torch.empty(synera.MEASURE_READ_BLOCKS * 256, dtype=torch.int32, device="cuda:0")
+
+    def read():
+        moved[0] = synera.measure_hbm_read(words, src)
+    ms = _time(read, n=10)
+    res["hbm_read_GBs"] = moved[0] / ms / 1e6
+    res["hbm_peak_GBs"] = 8000.0
+    del src, words
+    out = torch.empty(256 * 256, dtype=torch.float32, device="cuda:0")
+    for key, rnd in (("mfma_bf16_constant_operands_TFLOPs", False), ("mfma_bf16_random_operands_TFLOPs", True)):
+        flops = [0]
+
+        def loop():
+            flops[0] = synera.measure_mfma_bf16(out, 256, mfma_iters, rnd)
+        ms = _time(loop, n=5, warm=2)
+        res[key] = flops[0] / ms / 1e9
+    res["mfma_bf16_peak_TFLOPs"] = 2500.0
+    return res
+
+
+def ceilings():
+    print(json.dumps({"what": "measured ceilings (device copy and read-only stream of 1 GiB; 256 blocks x 4 wavefronts x 20000 x 16 MFMA 32x32x16 bf16)",
+                      **measured_ceilings()}))
+
+
 def sched():
     """Host cost of the verification-aware scheduler on the headline batch shape: 64 active requests with the
     context lengths of that workload; every round all 64 submit a verification (1 uncached token + their
@@ -107,4 +147,4 @@ def sched():
 
 if __name__ == "__main__":
     which = sys.argv[1] if len(sys.argv) > 1 else "confidence"
-    {"confidence": confidence, "gemm": gemm, "sched": sched}[which]()
+    {"confidence": confidence, "gemm": gemm, "sched": sched, "ceilings": ceilings}[which]()
