@@ -295,7 +295,8 @@ def compare_kv(case, atol=0.02):
     the normalised activations to bf16 before the projection, the oracle does not), every other slot
     of their pages still untouched."""
     b = case.batch
-    rep = {"ok": True, "fail": [], "max_kv_err": 0.0}
+    rep = {"ok": True, "fail": [], "max_kv_err": 0.0, "chunk_entries": 0, "chunk_entries_differing": 0,
+           "layer0_entries": 0, "layer0_entries_differing": 0}
     kp = case.k_pool.view(torch.int16)
     vp = case.v_pool.view(torch.int16)
     for i in case.sampled:
@@ -319,6 +320,13 @@ def compare_kv(case, atol=0.02):
                     tol_k = atol + 2.0 ** -6 * np.abs(oracle.bf16_from_bits(wk))
                     tol_v = atol + 2.0 ** -6 * np.abs(oracle.bf16_from_bits(wv))
                     rep["max_kv_err"] = max(rep["max_kv_err"], float(ek.max()), float(ev.max()))
+                    # entries whose bf16 rounding fell the other way than the oracle's (layer 0 sees identical
+                    # inputs on both sides, so its count measures the projection's own precision)
+                    dk, dv = gk[:, :, s, :] != wk, gv[:, :, :, s] != wv
+                    rep["chunk_entries"] += dk.size + dv.size
+                    rep["chunk_entries_differing"] += int(dk.sum()) + int(dv.sum())
+                    rep["layer0_entries"] += dk[0].size + dv[0].size
+                    rep["layer0_entries_differing"] += int(dk[0].sum()) + int(dv[0].sum())
                     if not (np.all(np.isfinite(ek)) and np.all(ek <= tol_k) and np.all(ev <= tol_v)):
                         rep["ok"] = False
                         rep["fail"].append(f"request {i} position {t}: appended K/V off (k {ek.max():.3e}, v {ev.max():.3e})")
