@@ -80,13 +80,15 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
   }
 }
 
-// The same for rows of at most 8192 values: the row stays in registers between the two passes (no re-read of
-// x), and all loads of a pass are issued before anything is stored, so they are in flight together.
+// The same for rows of at most 1024 IT values: the row stays in registers between the two passes (no re-read
+// of x), and all loads of a pass are issued before anything is stored, so they are in flight together; the
+// pending K slices are taken four at a time for the same reason (a slice per round trip is what a small batch,
+// whose projections split K eight ways, otherwise spends its time on).
+template <int IT>
 __global__ __launch_bounds__(256) void rmsnorm_row_in_registers_kernel(
     float* __restrict__ x, const float* __restrict__ parts, int n_parts, size_t part_stride,
     const bf16_t* __restrict__ gain, const int32_t* __restrict__ rows, bf16_t* __restrict__ y,
     bf16_t* __restrict__ y_lo, int d, float eps) {
-  constexpr int IT = 8;                                  // 8 x 256 threads x 4 values
   const int r = blockIdx.x;
   const size_t row_at = (size_t)(rows ? rows[r] : r) * d;
   float* src = x + row_at;
@@ -96,18 +98,24 @@ __global__ __launch_bounds__(256) void rmsnorm_row_in_registers_kernel(
     const int c = threadIdx.x * 4 + k * 1024;
     v[k] = c < d ? *reinterpret_cast<const float4*>(src + c) : make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  for (int s = 0; s < n_parts; ++s) {
-    const float* ps = parts + (size_t)s * part_stride + row_at;
-    float4 pv[IT];
+  for (int s = 0; s < n_parts; s += 4) {
+    float4 pv[4][IT];
 #pragma unroll
-    for (int k = 0; k < IT; ++k) {
-      const int c = threadIdx.x * 4 + k * 1024;
-      pv[k] = c < d ? *reinterpret_cast<const float4*>(ps + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int u = 0; u < 4; ++u) {
+      const bool on = s + u < n_parts;
+      const float* ps = parts + (size_t)(on ? s + u : s) * part_stride + row_at;
+#pragma unroll
+      for (int k = 0; k < IT; ++k) {
+        const int c = threadIdx.x * 4 + k * 1024;
+        pv[u][k] = on && c < d ? *reinterpret_cast<const float4*>(ps + c) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
     }
 #pragma unroll
-    for (int k = 0; k < IT; ++k) {
-      v[k].x += pv[k].x; v[k].y += pv[k].y; v[k].z += pv[k].z; v[k].w += pv[k].w;
-    }
+    for (int u = 0; u < 4; ++u)               // slices are added in their order, as before
+#pragma unroll
+      for (int k = 0; k < IT; ++k) {
+        v[k].x += pv[u][k].x; v[k].y += pv[u][k].y; v[k].z += pv[u][k].z; v[k].w += pv[u][k].w;
+      }
   }
   float ss = 0.f;
 #pragma unroll
@@ -144,8 +152,10 @@ hipError_t launch_rmsnorm(float* x, const float* parts, int n_parts, size_t part
                           const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo, int n_rows, int d, float eps,
                           hipStream_t s) {
   if (n_rows <= 0) return hipSuccess;
-  if (d <= 8192)
-    rmsnorm_row_in_registers_kernel<<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
+  if (d <= 4096)
+    rmsnorm_row_in_registers_kernel<4><<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
+  else if (d <= 8192)
+    rmsnorm_row_in_registers_kernel<8><<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
   else
     rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
   return hipGetLastError();
@@ -195,6 +205,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
   for (int p = blockIdx.y * 256 + threadIdx.x; p < n_pairs; p += 256 * gridDim.y) {
     const int head = p / half, i = p % half;
     float2 v = *reinterpret_cast<const float2*>(row + (size_t)head * hd + 2 * i);
+#pragma unroll 4
     for (int s = 1; s < n_parts; ++s) {         // the projection arrives as K-split slices: add them
       const float2 pv = *reinterpret_cast<const float2*>(row + (size_t)s * part_stride + (size_t)head * hd + 2 * i);
       v.x += pv.x;
