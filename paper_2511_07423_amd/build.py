@@ -16,6 +16,9 @@ SOURCES = ["api.hip", "elementwise.hip", "confidence.hip", "attention.hip", "imp
 ASM_CHECKED = {"gemm.hip": "gemm_tall"}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# The attention kernel's builtin MFMAs take their accumulators in VGPRs: in AGPRs (the compiler's default choice)
+# all 36 of them were read out at the top of every tile iteration and written back at its end.
+EXTRA_FLAGS = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def _quiet(stderr):
@@ -26,7 +29,7 @@ def _quiet(stderr):
 
 def _compile(src):
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = ["hipcc", *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     if src in ASM_CHECKED:
         cmd.append("-save-temps=obj")
     res = subprocess.run(cmd, capture_output=True, text=True, cwd=OBJ_DIR)

@@ -236,10 +236,11 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
         u_key_end = u[3];
         u_part = u[4];
         u_kh = u[5];
+        // The accumulators are not cleared here: with the reference at NEG_BIG the first visible score of a
+        // row gives alpha = 2^(-huge) = 0 and the rescale below multiplies the (finite) leftovers of the
+        // previous stream away.  Clearing them in this branch made them loop-carried values with two
+        // definitions, and the compiler then copied all 36 registers in and out in every iteration.
         m_run = NEG_BIG;
-        acc_l = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
       }
       continue;
     }
@@ -336,6 +337,8 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
       // row, the (hi, lo) pair makes it exact to fp32, and no cross-lane reduction is needed.
       acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pf, acc_l, 0, 0, 0);
       acc_l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pfl, acc_l, 0, 0, 0);
+      // O^T += V^T P^T.  The two arms repeat the MFMAs so that the blanked fragments of the rare arm are not
+      // merged with the plain ones in registers (that merge cost 24 copies per tile on the common arm).
       if (kb + 32 > key_end) {
         // Last tile of the stream: V slots past it may hold junk (0 * NaN), blank them.
         uint32_t vm[4];
@@ -347,17 +350,18 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
         }
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          vf[db].x &= vm[0];
-          vf[db].y &= vm[1];
-          vf[db].z &= vm[2];
-          vf[db].w &= vm[3];
+          const uint4 vb = make_uint4(vf[db].x & vm[0], vf[db].y & vm[1], vf[db].z & vm[2], vf[db].w & vm[3]);
+          const bf16x8 v8 = __builtin_bit_cast(bf16x8, vb);
+          acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, pf, acc[db], 0, 0, 0);
+          acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, pfl, acc[db], 0, 0, 0);
         }
-      }
+      } else {
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 v8 = __builtin_bit_cast(bf16x8, vf[db]);
-        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, pf, acc[db], 0, 0, 0);
-        acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, pfl, acc[db], 0, 0, 0);
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 v8 = __builtin_bit_cast(bf16x8, vf[db]);
+          acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, pf, acc[db], 0, 0, 0);
+          acc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v8, pfl, acc[db], 0, 0, 0);
+        }
       }
     }
 
