@@ -2,7 +2,7 @@
 bench.py at the repository root):
 
     python -m paper_2511_07423_amd.measure confidence   # synera_confidence on a 2048 x 128256 logits block
-    python -m paper_2511_07423_amd.measure gemm         # the four projection shapes of the 8B decoder at M = 532
+    python -m paper_2511_07423_amd.measure gemm [M ...] # the four projection shapes of the 8B decoder at M = 532, 1152, 2048
     python -m paper_2511_07423_amd.measure sched        # host time of the scheduler per iteration (no GPU needed)
     python -m paper_2511_07423_amd.measure ceilings     # what this GPU gives: device copy (HBM), register-resident MFMA loop
 
@@ -54,20 +54,23 @@ def gemm():
     import torch
     import paper_2511_07423_amd as synera
     import workloads as wl
-    M = 532
-    for name, N, K in (("qkv", 6144, 4096), ("o", 4096, 4096), ("gate_up (store epilogue)", 28672, 4096),
-                       ("down", 4096, 14336)):
-        x = torch.randn((M, K), generator=torch.Generator(device="cuda:0").manual_seed(7), device="cuda:0")
-        a = x.to(torch.bfloat16)
-        al = (x - a.float()).to(torch.bfloat16)
-        ws = [wl.draw_normal_bf16((N, K), 0.02, 100 + i, "cuda:0") for i in range(3)]     # rotated: no cache reuse
-        c = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
-        it = iter(range(10 ** 9))
-        ms = _time(lambda: synera.gemm_bf16(a, ws[next(it) % 3], a_lo=al, out=c), n=18)
-        fl = 2.0 * M * N * K
-        print(json.dumps({"kernel": "synera_gemm_bf16", "shape": name, "M": M, "N": N, "K": K, "avg_launch_ms": ms,
-                          "bound": "mfma", "achieved_TFLOPs": fl / ms / 1e9, "executed_TFLOPs": 2 * fl / ms / 1e9,
-                          "peak_TFLOPs": 2500.0, "frac": fl / ms / 1e9 / 2500.0}))
+    shapes = (("qkv", 6144, 4096), ("o", 4096, 4096), ("gate_up (store epilogue)", 28672, 4096), ("down", 4096, 14336))
+    ws = {}
+    for M in [int(v) for v in sys.argv[2:]] or [532, 1152, 2048]:
+        for name, N, K in shapes:
+            x = torch.randn((M, K), generator=torch.Generator(device="cuda:0").manual_seed(7), device="cuda:0")
+            a = x.to(torch.bfloat16)
+            al = (x - a.float()).to(torch.bfloat16)
+            if name not in ws:                                 # three copies, rotated: no cache reuse
+                ws[name] = [wl.draw_normal_bf16((N, K), 0.02, 100 + i, "cuda:0") for i in range(3)]
+            w3 = ws[name]
+            c = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
+            it = iter(range(10 ** 9))
+            ms = _time(lambda: synera.gemm_bf16(a, w3[next(it) % 3], a_lo=al, out=c), n=18)
+            fl = 2.0 * M * N * K
+            print(json.dumps({"kernel": "synera_gemm_bf16", "shape": name, "M": M, "N": N, "K": K, "avg_launch_ms": ms,
+                              "bound": "mfma", "achieved_TFLOPs": fl / ms / 1e9, "executed_TFLOPs": 2 * fl / ms / 1e9,
+                              "peak_TFLOPs": 2500.0, "frac": fl / ms / 1e9 / 2500.0}))
 
 
 def measured_ceilings(copy_bytes=1 << 30, mfma_iters=20000):
