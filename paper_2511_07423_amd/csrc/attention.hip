@@ -182,6 +182,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
   for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
   // descriptor of the stream being consumed (scalar registers)
   int u_tok0 = 0, u_nrows = 0, u_lim0 = 0, u_key_end = 0, u_part = -1, u_kh = 0;
+  int u_fresh = 0;                                    // this wavefront has not yet seen a tile of the stream
 
   // program entries of the coming iteration: the KP positions to consume and the KP positions to issue
   i32x4 ce[KP], ie[KP];
@@ -236,10 +237,10 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
         u_key_end = u[3];
         u_part = u[4];
         u_kh = u[5];
-        // The accumulators are not cleared here: with the reference at NEG_BIG the first visible score of a
-        // row gives alpha = 2^(-huge) = 0 and the rescale below multiplies the (finite) leftovers of the
-        // previous stream away.  Clearing them in this branch made them loop-carried values with two
-        // definitions, and the compiler then copied all 36 registers in and out in every iteration.
+        // The accumulators are cleared at the stream's first tile, not here: cleared in this branch they
+        // became loop-carried values with two definitions, and the compiler copied all 36 registers in and
+        // out in every iteration of the tile loop.
+        u_fresh = 1;
         m_run = NEG_BIG;
       }
       continue;
@@ -326,7 +327,14 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
       const bf16x8 pf = __builtin_bit_cast(bf16x8, pk);
       const bf16x8 pfl = __builtin_bit_cast(bf16x8, pl);
       // Rescale the accumulators only when some row's reference moved (the first tile, then hardly ever).
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+      if (u_fresh) {
+        // first tile of the stream for this wavefront: what the previous stream left goes, by assignment (a
+        // product with alpha = 0 would keep an inf or NaN of a request with bad data alive in the next one)
+        u_fresh = 0;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) acc[db] = f32x4{0.f, 0.f, 0.f, 0.f};
+        acc_l = f32x4{0.f, 0.f, 0.f, 0.f};
+      } else if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
           acc[db][0] *= alpha; acc[db][1] *= alpha; acc[db][2] *= alpha; acc[db][3] *= alpha;
@@ -368,7 +376,8 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
     if (!(cur[0][0] & ATTN_POS_LAST_BIT)) continue;     // block-uniform: set on the iteration's first position
 
     // ---- the stream's share in this block ends here: write its result
-    float l_run = acc_l[0];
+    const bool idle = u_fresh != 0;                     // this wavefront saw no tile of the stream: leftovers
+    float l_run = idle ? 0.f : acc_l[0];
     float m_fin = m_run * scale_log2;                   // running maximum in the exponent-2 domain
     if (KP == 2) {
       // Merge the two key phases through the two slots just consumed: nothing is copied into them before
@@ -380,7 +389,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) park[(db * 4 + r) * 64 + lane] = acc[db][r];
+          for (int r = 0; r < 4; ++r) park[(db * 4 + r) * 64 + lane] = idle ? 0.f : acc[db][r];
         park[(DB * 4) * 64 + lane] = m_fin;
         park[(DB * 4 + 1) * 64 + lane] = l_run;
       }

@@ -202,3 +202,53 @@ def test_model_wider_than_the_register_resident_rmsnorm():
     safe = want["margin"] >= gh.MARGIN
     assert np.array_equal(out["argmax"].cpu().numpy()[safe], want["argmax"][safe])
     ver.close()
+
+
+def test_a_request_with_nan_in_its_cache_leaves_the_others_untouched(monkeypatch):
+    """Requests are independent: NaN in one request's cached K/V makes that request's outputs NaN and
+    changes no bit of any other request's.  The attention kernel is cut down to 2 persistent blocks, so that
+    every block runs many streams one after another and the poisoned request's streams come first in them:
+    whatever a stream leaves in a block's registers must not reach the next one."""
+    import paper_2511_07423_amd as synera
+    monkeypatch.setenv("SYNERA_ATTN_BLOCKS", "2")
+    shape = _mini_shape()
+    head = wl.draw_head_weights(shape, 31, DEV)
+    layers = [wl.draw_layer_weights(shape, 31, l, DEV) for l in range(shape.n_layers)]
+    g = torch.Generator(device=DEV).manual_seed(32)
+    rng = np.random.default_rng(33)
+    ctx = np.array([90, 40, 300, 17, 64, 1, 700, 33], np.int32)
+    k = np.array([5, 16, 1, 8, 32, 3, 9, 12], np.int32)
+    B = len(ctx)
+    need = (ctx + k + 15) // 16
+    n_pages, max_pages = int(need.sum()), int(need.max())
+    bt = np.full((B, max_pages), -1, np.int32)
+    at = 0
+    for i in range(B):
+        bt[i, :need[i]] = np.arange(at, at + need[i])
+        at += int(need[i])
+    pool = (shape.n_layers, n_pages, shape.n_kv_heads)
+    k_pool = torch.randn(pool + (wl.PAGE_SIZE, shape.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    v_pool = torch.randn(pool + (shape.head_dim, wl.PAGE_SIZE), generator=g, device=DEV).to(torch.bfloat16)
+    toks = torch.from_numpy(rng.integers(0, shape.vocab, int(k.sum())).astype(np.int32)).to(DEV)
+    anchor = torch.from_numpy(rng.integers(0, shape.vocab, B).astype(np.int32)).to(DEV)
+    ver = synera.Verifier(shape, head, layers, max_batch=B, max_tokens=int(k.sum()), max_pages=max_pages)
+    zeros = np.zeros(B, np.int32)
+
+    def run(kp, vp):
+        out = ver.verify(ctx, zeros, k, toks, anchor, bt, n_pages, kp, vp, want_logits=True)
+        torch.cuda.synchronize()
+        return {n: v.cpu().numpy() for n, v in out.items() if v is not None}
+
+    clean = run(k_pool.clone(), v_pool.clone())
+    assert all(np.isfinite(v).all() for v in clean.values())
+    bad_k, bad_v = k_pool.clone(), v_pool.clone()
+    bad_k[:, int(bt[0, 0]), :, :8, :] = float("nan")        # positions 0..7 of request 0: inside its context
+    bad_v[:, int(bt[0, 1]), :, :, :4] = float("inf")        # positions 16..19
+    dirty = run(bad_k, bad_v)
+    ver.close()
+    cu = np.concatenate([[0], np.cumsum(k)])
+    assert not np.isfinite(dirty["logits"][:cu[1]]).all()    # the poisoned request shows it
+    for name in ("logits", "argmax", "top1_prob", "entropy"):
+        assert np.array_equal(clean[name][cu[1]:], dirty[name][cu[1]:]), name
+    for name in ("accept_len", "correction"):
+        assert np.array_equal(clean[name][1:], dirty[name][1:]), name
