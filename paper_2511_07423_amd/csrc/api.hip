@@ -410,9 +410,15 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
         iters[k] += Hkv * (k == 0 ? 2 + tiles : 1 + (tiles + 1) / 2);
       }
     }
-    // Time per iteration, measured on MI355X at head_dim 128 with every block busy: 1.85 us with four row
-    // blocks (one tile), 2.6 us with two row blocks x two key phases (two tiles).
-    const double t_iter[2] = {1.85, 2.6};
+    // Relative time per iteration of the two classes (four row blocks, one tile: 1; two row blocks x two key
+    // phases, two tiles: 1.85), which decides how many of the persistent blocks each class gets.  From a sweep
+    // of the ratio on the headline batch, where the classes hold about half of the tiles each: 1.8 - 2.0 gives
+    // the shortest launch (94 us against 98 us at 1.4, the ratio of the two classes timed alone).
+    double t_iter[2] = {1.85, 3.4};
+    if (const char* env = getenv("SYNERA_ATTN_T_ITER_RATIO")) {   // tuning knob: the ratio above
+      const double v = strtod(env, nullptr);
+      if (v >= 0.25 && v <= 8.0) t_iter[1] = t_iter[0] * v;
+    }
     const double time_all = iters[0] * t_iter[0] + iters[1] * t_iter[1];
     int nb[2] = {0, 0};
     for (int k = 0; k < 2; ++k)
