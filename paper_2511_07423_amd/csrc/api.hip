@@ -396,6 +396,15 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
     // up to 32 rows) are laid end to end and cut into shares of equal modelled time, one per block.
     const int G = c->desc.n_q_heads / c->desc.n_kv_heads, Hkv = c->desc.n_kv_heads;
     const int tg = c->rows_per_group_tokens;
+    // What a stream costs a block beyond its tiles and query positions (its last iteration merges the key
+    // phases or writes partials, and stores the rows), in iterations: part of the balance between blocks.
+    // One iteration, from a sweep on the headline batch (512 streams of 4 to 128 tiles on 512 blocks: 94 us
+    // per layer without the term, 89 - 90 us with 1, 91 us with 2; the uniform batches do not care).
+    double stream_cost = 1.0;
+    if (const char* env = getenv("SYNERA_ATTN_STREAM_COST")) {    // tuning knob
+      const double v = strtod(env, nullptr);
+      if (v >= 0.0 && v <= 16.0) stream_cost = v;
+    }
     struct Stream { int req, tok0, j0, ntok, keys; };
     std::vector<Stream> cls[2];                      // [0]: rbn 4, [1]: rbn 2
     double iters[2] = {0.0, 0.0};                    // iterations of each class (every stream once per KV head)
@@ -407,7 +416,7 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
         const int k = ntok * G > 32 ? 0 : 1;
         const int tiles = (st.keys + 31) / 32;
         cls[k].push_back(st);
-        iters[k] += Hkv * (k == 0 ? 2 + tiles : 1 + (tiles + 1) / 2);
+        iters[k] += Hkv * ((k == 0 ? 2 + tiles : 1 + (tiles + 1) / 2) + stream_cost);
       }
     }
     // Relative time per iteration of the two classes (four row blocks, one tile: 1; two row blocks x two key
@@ -444,14 +453,15 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
       // to the total, so the aim is renewed at each share rather than fixed up front).
       double rest = iters[k];
       int blocks_left = nb[k];
-      double target = rest / blocks_left + q_iters;
+      const double q_cost = q_iters + stream_cost;       // modelled cost of starting (and ending) a share
+      double target = rest / blocks_left + q_cost;
       double load = 0.0;
       size_t share_begin = n_pos;
       auto close_share = [&]() {
         if (n_pos > share_begin) {
           shares[n_shares++] = AttnShare{(int32_t)share_begin, (int32_t)(n_pos - share_begin), rbn, 0};
           --blocks_left;
-          if (blocks_left > 0) target = std::max(rest, 0.0) / blocks_left + q_iters;
+          if (blocks_left > 0) target = std::max(rest, 0.0) / blocks_left + q_cost;
         }
         share_begin = n_pos;
         load = 0.0;
@@ -464,16 +474,16 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
           while (t_done < tiles) {
             const int t_left = tiles - t_done;
             const double room = target - load;
-            const int need_all = q_iters + (t_left + KP - 1) / KP;
+            const double need_all = q_cost + (t_left + KP - 1) / KP;
             int take = t_left;
             if (blocks_left > 1 && need_all > room + 3.0) {    // does not fit: cut here, or start in the next block
-              const int fit = ((int)room - q_iters) * KP;
+              const int fit = (int)(room - q_cost) * KP;
               if (fit < 4 * KP) {
                 if (load > 0.0) {
                   close_share();
                   continue;
                 }
-                take = std::min(t_left, std::max(KP, ((int)target - q_iters) * KP));
+                take = std::min(t_left, std::max(KP, (int)(target - q_cost) * KP));
               } else {
                 take = std::min(t_left, fit);
               }
@@ -506,8 +516,8 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
             }
             if ((n_pos - first_kv) % KP) prog[n_pos++] = AttnPos{ATTN_POS_PAD, 0, 0, 0};
             prog[n_pos - KP].tag |= ATTN_POS_LAST_BIT;       // first position of the share's last iteration
-            load += q_iters + (take + KP - 1) / KP;
-            rest -= (t_done == 0 ? q_iters : 0) + (take + KP - 1) / KP;
+            load += q_cost + (take + KP - 1) / KP;
+            rest -= (t_done == 0 ? q_cost : 0.0) + (take + KP - 1) / KP;
             t_done = t_end;
             if (blocks_left > 1 && load >= target - 0.5) close_share();
           }
