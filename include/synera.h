@@ -351,6 +351,25 @@ int32_t synera_measure_mfma_bf16(float* d_out, int32_t blocks, int32_t iters, in
 int32_t synera_debug_set_gemm_tile(int32_t variant);
 
 /*
+ * Test hook, host only (no GPU call, no context): the work plan of the chunk attention of Section 3.2 for one
+ * batch, as synera_verify lays it out for `attn_blocks` (2 .. 8192) persistent blocks.  Inputs as for
+ * synera_verify (host).
+ * Outputs (host, int32): h_shares[attn_blocks][4] = (first position, positions, row blocks 4 | 2, 0) per block;
+ * h_prog[prog_cap][4] = the positions (tag, a, b, c): tag & 7 = 0 padding / 1 a 32-key tile (tag >> 4 = KV
+ * head, a / b = its two pages, c = first key) / 2 query rows of a stream (tag >> 4 = unit, a = first chunk
+ * token, b = rows, c = first of the 32 rows carried | KV head << 8), tag & 8 = the share of the stream ends with
+ * this iteration; h_units[unit_cap][8] = (first chunk token, rows, last key the first token sees, end of the
+ * share's keys, partial slot or -1, KV head, 0, 0); h_cuts[cut_cap][8] = (first partial slot, slots, first chunk
+ * token, rows, KV head, 0, 0, 0) per stream split over blocks; h_counts[4] = shares, positions, units, cuts.
+ * Errors: EINVAL, EUNSUP, ENOSPC (an output capacity is too small), ENOMEM.
+ */
+int32_t synera_debug_attention_plan(const synera_model_desc* desc, int32_t attn_blocks, int32_t B,
+                                    const int32_t* h_ctx_len, const int32_t* h_n_uncached, const int32_t* h_n_draft,
+                                    const int32_t* h_block_table, int32_t max_pages, int32_t* h_shares,
+                                    int32_t* h_prog, int64_t prog_cap, int32_t* h_units, int64_t unit_cap,
+                                    int32_t* h_cuts, int64_t cut_cap, int32_t* h_counts);
+
+/*
  * Test hook, host only (no GPU call): the tile (rows x columns) and the number of K slices the planner
  * gives a projection of M rows with (hi, lo) activations -- the form every projection of Section 3.4's
  * partial prefill takes.  epilogue as in synera_debug_gemm_epilogue; stored_slices != 0 plans the decoder

@@ -93,6 +93,9 @@ _lib.synera_measure_hbm_read.restype = C.c_int32
 _lib.synera_measure_hbm_read.argtypes = [_vp, _vp, C.c_int64, _vp]
 _lib.synera_measure_mfma_bf16.restype = C.c_int32
 _lib.synera_measure_mfma_bf16.argtypes = [_vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int64), _vp]
+_lib.synera_debug_attention_plan.restype = C.c_int32
+_lib.synera_debug_attention_plan.argtypes = [_vp, C.c_int32, C.c_int32, _i32p, _i32p, _i32p, _i32p, C.c_int32,
+                                             _i32p, _i32p, C.c_int64, _i32p, C.c_int64, _i32p, C.c_int64, _i32p]
 _lib.synera_debug_gemm_plan.restype = C.c_int32
 _lib.synera_debug_gemm_plan.argtypes = [C.c_int32] * 5 + [C.POINTER(C.c_int32)] * 3
 _lib.synera_debug_gemm_epilogue.restype = C.c_int32
@@ -270,6 +273,31 @@ def measure_mfma_bf16(out, blocks, iters, random_operands=True):
                                        C.byref(flops), _stream())
     _check(st, "synera_measure_mfma_bf16")
     return flops.value
+
+
+def debug_attention_plan(shape, attn_blocks, ctx_len, n_uncached, n_draft, block_table):
+    """Test hook (host only): the chunk attention's work plan for one batch -> dict of int32 arrays
+    shares [n][4], prog [n][4], units [n][8], cuts [n][8]."""
+    desc = _ModelDesc(shape.n_layers, shape.d_model, shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.d_ffn,
+                      shape.vocab, shape.rope_base, shape.rms_eps)
+    ctx, unc, nd = (np.ascontiguousarray(a, dtype=np.int32) for a in (ctx_len, n_uncached, n_draft))
+    bt = np.ascontiguousarray(block_table, dtype=np.int32)
+    B, max_pages = bt.shape
+    tiles = int(((ctx.astype(np.int64) + unc + nd + 31) // 32).sum())
+    per_request = -(-MAX_CHUNK // max(1, 64 // (shape.n_q_heads // shape.n_kv_heads)))   # row groups of <= 64 rows
+    groups = int(B * per_request)
+    prog_cap = (tiles * per_request + 4 * groups) * shape.n_kv_heads + 8 * attn_blocks + 64
+    unit_cap = groups * shape.n_kv_heads + attn_blocks + 8
+    shares = np.zeros((attn_blocks, 4), np.int32)
+    prog = np.zeros((prog_cap, 4), np.int32)
+    units = np.zeros((unit_cap, 8), np.int32)
+    cuts = np.zeros((2 * attn_blocks, 8), np.int32)
+    counts = np.zeros(4, np.int32)
+    p = lambda a: a.ctypes.data_as(_i32p)                                  # noqa: E731
+    st = _lib.synera_debug_attention_plan(C.byref(desc), attn_blocks, B, p(ctx), p(unc), p(nd), p(bt), max_pages,
+                                          p(shares), p(prog), prog_cap, p(units), unit_cap, p(cuts), len(cuts), p(counts))
+    _check(st, "synera_debug_attention_plan")
+    return {"shares": shares[:counts[0]], "prog": prog[:counts[1]], "units": units[:counts[2]], "cuts": cuts[:counts[3]]}
 
 
 def debug_gemm_plan(M, N, K, epilogue=0, stored_slices=True):

@@ -150,6 +150,27 @@ struct StageTimer {                      // brackets one stage launch when profi
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Capacities of the per-call metadata (c->desc, max_batch / max_tokens / max_pages / max_rows and attn_blocks
+// are set).  Worst case: every request at the full block table.  A stream (row group x KV head) has at most
+// max_pages / 2 + 1 key tiles; every share of a stream adds two query positions and at most one padding
+// position; cutting adds at most one share per block.
+static void size_plan(synera_ctx* c) {
+  const synera_model_desc& m = c->desc;
+  const int G = m.n_q_heads / m.n_kv_heads;
+  c->rows_per_group_tokens = std::max(1, 64 / G);
+  const int rg_max = (SYNERA_MAX_CHUNK + c->rows_per_group_tokens - 1) / c->rows_per_group_tokens;
+  const size_t streams = (size_t)c->max_batch * rg_max * m.n_kv_heads;
+  const size_t tiles = (size_t)c->max_pages / 2 + 2;
+  c->unit_cap = streams + (size_t)c->attn_blocks;
+  c->pos_cap = streams * tiles + c->unit_cap * 4 + 2 * (size_t)c->attn_blocks;
+  c->part_cap = 2 * (size_t)c->attn_blocks;
+  const size_t meta_ints = (size_t)c->max_batch * 5 + 2 + (size_t)c->max_tokens + (size_t)c->max_rows +
+                           (size_t)c->max_batch * c->max_pages + c->pos_cap * 4 + c->unit_cap * 8 +
+                           (size_t)c->attn_blocks * 4 + c->part_cap * 8 + 128 + ((size_t)c->max_batch + 1) +
+                           2 * (size_t)c->max_batch * ((size_t)c->max_pages / 16 + 2);
+  c->meta_cap = align_up(meta_ints * 4, 256);
+}
+
 extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc, const synera_weights* w,
                                  int32_t max_batch, int32_t max_tokens, int32_t max_pages) {
   if (!out) return SYNERA_EINVAL;
@@ -186,9 +207,6 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   c->max_pages = max_pages;
   c->max_rows = max_tokens + max_batch;
   c->device = dev;
-  const int G = m.n_q_heads / m.n_kv_heads;
-  c->rows_per_group_tokens = std::max(1, 64 / G);
-  const int rg_max = (SYNERA_MAX_CHUNK + c->rows_per_group_tokens - 1) / c->rows_per_group_tokens;
   // Attention runs as persistent blocks, two per compute unit (80 KB of LDS each at head_dim 128).
   {
     hipDeviceProp_t prop;
@@ -200,19 +218,10 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
     c->attn_blocks = 2 * std::max(1, prop.multiProcessorCount);
     if (const char* env = getenv("SYNERA_ATTN_BLOCKS")) {   // tuning knob
       const long v = strtol(env, nullptr, 10);
-      if (v >= 1 && v <= 8192) c->attn_blocks = (int32_t)v;
+      if (v >= 2 && v <= 8192) c->attn_blocks = (int32_t)v;   // two at least: one per class of streams
     }
   }
-  // Worst case: every request at the full block table.  A stream (row group x KV head) has at most
-  // max_pages / 2 + 1 key tiles; every share of a stream adds two query positions and at most one padding
-  // position; cutting adds at most one share per block.
-  {
-    const size_t streams = (size_t)max_batch * rg_max * m.n_kv_heads;
-    const size_t tiles = (size_t)max_pages / 2 + 2;
-    c->unit_cap = streams + (size_t)c->attn_blocks;
-    c->pos_cap = streams * tiles + c->unit_cap * 4 + 2 * (size_t)c->attn_blocks;
-    c->part_cap = 2 * (size_t)c->attn_blocks;
-  }
+  size_plan(c);
 
   const size_t T = (size_t)max_tokens, R = (size_t)c->max_rows;
   const size_t qkv_dim = (size_t)(qd + 2 * kd);
@@ -259,11 +268,6 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   c->last.valid = false;
   c->gparts = reinterpret_cast<float*>(c->arena + o_gp);
 
-  const size_t meta_ints = (size_t)max_batch * 5 + 2 + (size_t)max_tokens + (size_t)c->max_rows +
-                           (size_t)max_batch * max_pages + c->pos_cap * 4 + c->unit_cap * 8 + (size_t)c->attn_blocks * 4 +
-                           c->part_cap * 8 + 128 +
-                           ((size_t)max_batch + 1) + 2 * (size_t)max_batch * ((size_t)max_pages / 16 + 2);
-  c->meta_cap = align_up(meta_ints * 4, 256);
   for (int s = 0; s < N_STAGE; ++s) {
     c->h_meta[s] = nullptr;
     c->d_meta[s] = nullptr;
@@ -320,10 +324,10 @@ struct Plan {
 // n_second == nullptr means "append only": no LM rows, no attention items.
 static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, const int32_t* n_unc,
                           const int32_t* n_draft, const int32_t* block_table, int32_t max_pages, bool with_attention,
-                          hipStream_t stream, Plan& p) {
+                          hipStream_t stream, Plan& p, bool host_only = false) {
   c->last.valid = false;       // the metadata slots rotate: what synera_importance reads belongs to the newest verify only
   const int slot = (int)(c->calls % N_STAGE);
-  if (c->pending[slot]) {
+  if (!host_only && c->pending[slot]) {
     HIP_TRY(hipEventSynchronize(c->done[slot]));
     c->pending[slot] = false;
   }
@@ -540,7 +544,7 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
     at = o_prog + n_pos * 4;
   }
   if (at * 4 > c->meta_cap) return SYNERA_ENOSPC;
-  HIP_TRY(hipMemcpyAsync(d, h, at * 4, hipMemcpyHostToDevice, stream));
+  if (!host_only) HIP_TRY(hipMemcpyAsync(d, h, at * 4, hipMemcpyHostToDevice, stream));
   p.meta.ctx_len = d + o_ctx;
   p.meta.cu_tok = d + o_cu;
   p.meta.cu_draft = d + o_cud;
@@ -927,6 +931,67 @@ extern "C" int32_t synera_debug_read_scratch(synera_ctx* c, int32_t which, void*
 extern "C" int32_t synera_debug_set_gemm_tile(int32_t variant) {
   gemm_force_variant(variant);
   return SYNERA_OK;
+}
+
+extern "C" int32_t synera_debug_attention_plan(const synera_model_desc* desc, int32_t attn_blocks, int32_t B,
+                                               const int32_t* h_ctx_len, const int32_t* h_n_uncached,
+                                               const int32_t* h_n_draft, const int32_t* h_block_table,
+                                               int32_t max_pages, int32_t* h_shares, int32_t* h_prog, int64_t prog_cap,
+                                               int32_t* h_units, int64_t unit_cap, int32_t* h_cuts, int64_t cut_cap,
+                                               int32_t* h_counts) {
+  if (!desc || !h_ctx_len || !h_n_uncached || !h_n_draft || !h_block_table || !h_shares || !h_prog || !h_units ||
+      !h_cuts || !h_counts || attn_blocks < 2 || attn_blocks > 8192 || B < 1 || max_pages < 1)
+    return SYNERA_EINVAL;
+  const synera_model_desc& m = *desc;
+  if (m.n_q_heads < 1 || m.n_kv_heads < 1 || m.n_q_heads % m.n_kv_heads != 0 || m.n_q_heads / m.n_kv_heads > 16)
+    return SYNERA_EUNSUP;
+  int64_t T = 0;
+  for (int i = 0; i < B; ++i) {
+    if (h_ctx_len[i] < 0 || h_n_uncached[i] < 0 || h_n_draft[i] < 1 || h_n_uncached[i] + h_n_draft[i] > SYNERA_MAX_CHUNK ||
+        (int64_t)h_ctx_len[i] + h_n_uncached[i] + h_n_draft[i] > (int64_t)max_pages * SYNERA_PAGE_SIZE)
+      return SYNERA_EINVAL;
+    T += h_n_uncached[i] + h_n_draft[i];
+  }
+  synera_ctx* c = new (std::nothrow) synera_ctx();   // host-only: no arena, no events, one malloc'ed staging slot
+  if (!c) return SYNERA_ENOMEM;
+  c->desc = m;
+  c->max_batch = B;
+  c->max_tokens = (int32_t)T;
+  c->max_pages = max_pages;
+  c->max_rows = (int32_t)T + B;
+  c->attn_blocks = attn_blocks;
+  c->arena = nullptr;
+  c->calls = 0;
+  for (int s = 0; s < N_STAGE; ++s) {
+    c->h_meta[s] = c->d_meta[s] = nullptr;
+    c->done[s] = nullptr;
+    c->pending[s] = false;
+  }
+  size_plan(c);
+  std::vector<int32_t> blob(c->meta_cap / 4);
+  c->h_meta[0] = c->d_meta[0] = blob.data();        // "device" addresses of the plan point into the same blob
+  Plan p;
+  int32_t st = build_plan(c, B, h_ctx_len, h_n_uncached, h_n_draft, h_block_table, max_pages, true, nullptr, p, true);
+  if (st == SYNERA_OK) {
+    int64_t n_pos = 0, n_units = 0;
+    for (int i = 0; i < p.n_shares; ++i) n_pos = std::max<int64_t>(n_pos, p.d_shares[i].pos_begin + p.d_shares[i].n_pos);
+    for (int64_t i = 0; i < n_pos; ++i)
+      if ((p.d_prog[i].tag & ATTN_POS_KIND_MASK) == ATTN_POS_Q) n_units = std::max<int64_t>(n_units, (p.d_prog[i].tag >> 4) + 1);
+    if (n_pos > prog_cap || n_units > unit_cap || p.n_cuts > cut_cap) {
+      st = SYNERA_ENOSPC;
+    } else {
+      std::memcpy(h_shares, p.d_shares, (size_t)p.n_shares * sizeof(AttnShare));
+      std::memcpy(h_prog, p.d_prog, (size_t)n_pos * sizeof(AttnPos));
+      std::memcpy(h_units, p.d_units, (size_t)n_units * sizeof(AttnUnit));
+      std::memcpy(h_cuts, p.d_cuts, (size_t)p.n_cuts * sizeof(AttnCut));
+      h_counts[0] = p.n_shares;
+      h_counts[1] = (int32_t)n_pos;
+      h_counts[2] = (int32_t)n_units;
+      h_counts[3] = p.n_cuts;
+    }
+  }
+  delete c;
+  return st;
 }
 
 extern "C" int32_t synera_debug_gemm_plan(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices,
