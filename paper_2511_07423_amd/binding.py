@@ -73,8 +73,12 @@ _lib.synera_profile_begin.restype = C.c_int32
 _lib.synera_profile_begin.argtypes = [_vp, C.c_int32]
 _lib.synera_profile_end.restype = C.c_int32
 _lib.synera_profile_end.argtypes = [_vp, C.POINTER(C.c_int32), C.POINTER(C.c_float)]
-_lib.synera_gemm_bf16.restype = C.c_int32
-_lib.synera_gemm_bf16.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
+_lib.synera_gemm_pair.restype = C.c_int32
+_lib.synera_gemm_pair.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
+_lib.synera_debug_set_lo_off.restype = C.c_int32
+_lib.synera_debug_set_lo_off.argtypes = [_vp, C.c_int32]
+_lib.synera_debug_set_attention_plan.restype = C.c_int32
+_lib.synera_debug_set_attention_plan.argtypes = [_vp, C.c_int32, C.c_float, C.c_float, C.c_float]
 _lib.synera_debug_read_scratch.restype = C.c_int32
 _lib.synera_debug_read_scratch.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp]
 _lib.synera_debug_set_gemm_tile.restype = C.c_int32
@@ -85,8 +89,8 @@ _lib.synera_topp_count.restype = C.c_int32
 _lib.synera_topp_count.argtypes = [_vp, C.c_int64, C.c_int32, C.c_float, _vp, _vp, _vp]
 _lib.synera_importance.restype = C.c_int32
 _lib.synera_importance.argtypes = [_vp, C.c_int32, _vp, C.c_int64, _vp, C.c_float, C.c_float, _vp, _vp, _vp]
-_lib.synera_debug_gemm_deferred.restype = C.c_int32
-_lib.synera_debug_gemm_deferred.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), _vp]
+_lib.synera_debug_gemm_slices.restype = C.c_int32
+_lib.synera_debug_gemm_slices.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), _vp]
 _lib.synera_measure_hbm_copy.restype = C.c_int32
 _lib.synera_measure_hbm_copy.argtypes = [_vp, _vp, C.c_int64, _vp]
 _lib.synera_measure_hbm_read.restype = C.c_int32
@@ -198,22 +202,34 @@ def chunk_dispatch(top1_prob, cu_rows, c_th, k_slope=10.0):
     return mean, pc
 
 
-def gemm_bf16(a, w, a_lo=None, out=None):
-    """C = (A + A_lo) W^T on the matrix cores; a (and a_lo) bf16 [M,K], w bf16 [N,K] -> f32 [M,N]."""
+LO_SITES = {"qkv_in": 1, "gate_up_in": 2, "down_in": 4, "o_in": 8, "lm_head_in": 16, "q": 32, "p": 64}
+
+
+def split_pair(x, scale=1.0):
+    """The fp16 (hi, lo) pair of scale * x (float32 tensor): hi = fp16(v), lo = fp16(v - hi).  Test helper
+    (plain torch ops on whatever device x is on); inside a verify the kernels produce the pairs."""
+    v = x.float() * scale
+    hi = v.to(torch.float16)
+    return hi, (v - hi.float()).to(torch.float16)
+
+
+def gemm_pair(a, a_lo, w, out=None):
+    """C = (A + A_lo) W^T on the matrix cores; a, a_lo fp16 [M,K], w bf16 [N,K] -> f32 [M,N]."""
     M, K = a.shape
     N = w.shape[0]
     c = torch.empty((M, N), dtype=torch.float32, device=a.device) if out is None else out
-    st = _lib.synera_gemm_bf16(_dev(a, torch.bfloat16), _dev(a_lo, torch.bfloat16), _dev(w, torch.bfloat16),
+    st = _lib.synera_gemm_pair(_dev(a, torch.float16), _dev(a_lo, torch.float16), _dev(w, torch.bfloat16),
                                c.data_ptr(), M, N, K, _stream())
-    _check(st, "synera_gemm_bf16")
+    _check(st, "synera_gemm_pair")
     return c
 
 
 def debug_gemm_epilogue(a, a_lo, w0, w1, c, c_lo, epilogue):
-    """Test hook: one projection GEMM with epilogue 0 (store), 1 (add into c) or 2 (SwiGLU into the bf16 pair c, c_lo)."""
+    """Test hook: one projection GEMM with epilogue 0 (store), 1 (add into c) or 2 (SwiGLU into the fp16 pair c, c_lo,
+    which holds 8 x the value)."""
     M, K = a.shape
     N = w0.shape[0] * (2 if epilogue == 2 else 1)
-    st = _lib.synera_debug_gemm_epilogue(_dev(a, torch.bfloat16), _dev(a_lo, torch.bfloat16), _dev(w0, torch.bfloat16),
+    st = _lib.synera_debug_gemm_epilogue(_dev(a, torch.float16), _dev(a_lo, torch.float16), _dev(w0, torch.bfloat16),
                                          _dev(w1, torch.bfloat16), c.data_ptr(), c_lo.data_ptr() if c_lo is not None else None,
                                          M, N, K, epilogue, _stream())
     _check(st, "synera_debug_gemm_epilogue")
@@ -229,15 +245,15 @@ def topp_count(topk_prob, top_p):
     return n, mass
 
 
-def debug_gemm_deferred(a, a_lo, w):
+def debug_gemm_slices(a, a_lo, w):
     """Test hook: the store-form GEMM with K slices stored side by side; returns the f32 slices [n][M][N]."""
     M, K = a.shape
     N = w.shape[0]
     parts = torch.empty((8, M, N), dtype=torch.float32, device=a.device)
     n = C.c_int32(0)
-    st = _lib.synera_debug_gemm_deferred(_dev(a, torch.bfloat16), _dev(a_lo, torch.bfloat16), _dev(w, torch.bfloat16),
-                                         parts.data_ptr(), M, N, K, C.byref(n), _stream())
-    _check(st, "synera_debug_gemm_deferred")
+    st = _lib.synera_debug_gemm_slices(_dev(a, torch.float16), _dev(a_lo, torch.float16), _dev(w, torch.bfloat16),
+                                       parts.data_ptr(), M, N, K, C.byref(n), _stream())
+    _check(st, "synera_debug_gemm_slices")
     return parts[:n.value]
 
 
@@ -407,6 +423,15 @@ class Verifier:
                                            _dev(u_sample, torch.float32), _dev(acc), _dev(tok), _stream())
         _check(st, "synera_stochastic_accept")
         return acc, tok
+
+    def debug_set_lo_off(self, sites):
+        """Ablation hook: `sites` = names from LO_SITES (or the bit mask) whose low activation part is dropped."""
+        mask = sites if isinstance(sites, int) else sum(LO_SITES[n] for n in sites)
+        _check(_lib.synera_debug_set_lo_off(self._ctx, mask), "synera_debug_set_lo_off")
+
+    def debug_set_attention_plan(self, attn_blocks=0, stream_cost=1.0, cut_slack=1.5, t_iter_ratio=3.4 / 1.85):
+        _check(_lib.synera_debug_set_attention_plan(self._ctx, attn_blocks, stream_cost, cut_slack, t_iter_ratio),
+               "synera_debug_set_attention_plan")
 
     def debug_read_scratch(self, which, out):
         """Test hook: copy an intermediate buffer of the last layer of the last verify into `out`."""

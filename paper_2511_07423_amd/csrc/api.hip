@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "../../include/synera.h"
+#include "../../include/synera_debug.h"
 #include "common.h"
 
 #define SY_VERSION 100
@@ -79,23 +80,27 @@ struct synera_ctx {
   const void* embed;
   const void* final_norm;
   const void* lm_head;
-  int32_t max_batch, max_tokens, max_pages, max_rows, rows_per_group_tokens, attn_blocks;
+  int32_t max_batch, max_tokens, max_pages, max_rows, rows_per_group_tokens;
+  int32_t attn_blocks, attn_blocks_cap;   // persistent attention blocks in use / the most the scratch is sized for
   size_t pos_cap, unit_cap, part_cap;   // capacities of the attention program, its stream shares, the partial slots
   int device;
+  // attention share planner (set once in synera_create)
+  double attn_stream_cost, attn_cut_slack, attn_t_iter[2];
+  int32_t lo_off;              // test hook: SYNERA_LO_* sites whose low activation part is written as zeros
   // device scratch (one allocation)
   char* arena;
   float* x;
-  bf16_t* y;        // activations travel as bf16 (hi, lo) pairs: *_lo is the low part
-  bf16_t* y_lo;
+  uint16_t* y;      // GEMM inputs travel as scaled fp16 (hi, lo) pairs: *_lo is the low part
+  uint16_t* y_lo;
   float* qkv;
-  bf16_t* q;
+  bf16_t* q;        // rotated queries: a bf16 pair (they meet the bf16 cache in the attention kernel)
   bf16_t* q_lo;
-  bf16_t* o;
-  bf16_t* o_lo;
-  bf16_t* act;
-  bf16_t* act_lo;
-  bf16_t* ysel;
-  bf16_t* ysel_lo;
+  uint16_t* o;
+  uint16_t* o_lo;
+  uint16_t* act;
+  uint16_t* act_lo;
+  uint16_t* ysel;
+  uint16_t* ysel_lo;
   float* logits;
   int32_t* lm_ids;
   float* lm_p;
@@ -108,12 +113,12 @@ struct synera_ctx {
   struct {
     const int32_t *ctx_len, *cu_tok, *block_table, *cu_keys, *items, *n_unc, *cu_draft;
     BatchMeta meta;
-    int32_t B, T, R, n_items, max_pages, total_keys, n_pages_in_pool;
+    int32_t B, T, R, n_items, max_pages, total_keys, n_pages_in_pool, slot;
     const void* k_pool;
     bool valid;
     bool all_rows_kept;          // every request had an uncached token: c->logits / lm_ids / lm_p hold all LM-head rows
   } last;
-  float* gparts;               // K-split slices of one projection: [SY_MAX_DEFERRED_SPLIT][max_tokens][max(d, q+2kv)]
+  float* gparts;               // K-split slices of one projection: [SY_MAX_K_SLICES][max_tokens][max(d, q+2kv)]
   size_t gpart_elems;          // elements of one slice slot
   // metadata staging ring
   size_t meta_cap;             // bytes per slot
@@ -150,7 +155,7 @@ struct StageTimer {                      // brackets one stage launch when profi
 
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-// Capacities of the per-call metadata (c->desc, max_batch / max_tokens / max_pages / max_rows and attn_blocks
+// Capacities of the per-call metadata (c->desc, max_batch / max_tokens / max_pages / max_rows and attn_blocks_cap
 // are set).  Worst case: every request at the full block table.  A stream (row group x KV head) has at most
 // max_pages / 2 + 1 key tiles; every share of a stream adds two query positions and at most one padding
 // position; cutting adds at most one share per block.
@@ -161,14 +166,32 @@ static void size_plan(synera_ctx* c) {
   const int rg_max = (SYNERA_MAX_CHUNK + c->rows_per_group_tokens - 1) / c->rows_per_group_tokens;
   const size_t streams = (size_t)c->max_batch * rg_max * m.n_kv_heads;
   const size_t tiles = (size_t)c->max_pages / 2 + 2;
-  c->unit_cap = streams + (size_t)c->attn_blocks;
-  c->pos_cap = streams * tiles + c->unit_cap * 4 + 2 * (size_t)c->attn_blocks;
-  c->part_cap = 2 * (size_t)c->attn_blocks;
+  c->unit_cap = streams + (size_t)c->attn_blocks_cap;
+  c->pos_cap = streams * tiles + c->unit_cap * 4 + 2 * (size_t)c->attn_blocks_cap;
+  c->part_cap = 2 * (size_t)c->attn_blocks_cap;
   const size_t meta_ints = (size_t)c->max_batch * 5 + 2 + (size_t)c->max_tokens + (size_t)c->max_rows +
                            (size_t)c->max_batch * c->max_pages + c->pos_cap * 4 + c->unit_cap * 8 +
-                           (size_t)c->attn_blocks * 4 + c->part_cap * 8 + 128 + ((size_t)c->max_batch + 1) +
+                           (size_t)c->attn_blocks_cap * 4 + c->part_cap * 8 + 128 + ((size_t)c->max_batch + 1) +
                            2 * (size_t)c->max_batch * ((size_t)c->max_pages / 16 + 2);
   c->meta_cap = align_up(meta_ints * 4, 256);
+}
+
+// Constants of the attention share planner (build_plan).
+static void attention_plan_defaults(synera_ctx* c) {
+  // What a stream costs a block beyond its tiles and query positions (its last iteration merges the key phases
+  // or writes partials, and stores the rows), in iterations: part of the balance between blocks.  One iteration,
+  // from a sweep on the 8B ragged batch of 64 (512 streams of 4 to 128 tiles on 512 blocks: 94 us per layer
+  // without the term, 89 - 90 us with 1, 91 us with 2; the uniform batches do not care).
+  c->attn_stream_cost = 1.0;
+  // A stream that overshoots its block's share by less than this is not cut (iterations; swept: 0 .. 1.5 best,
+  // 3 +1.5 %, 8 +9 %).
+  c->attn_cut_slack = 1.5;
+  // Relative time per iteration of the two classes (four row blocks, one tile: 1; two row blocks x two key
+  // phases, two tiles: 1.85), which decides how many of the persistent blocks each class gets.  From a sweep of
+  // the ratio on that batch, where the classes hold about half of the tiles each: 1.8 - 2.0 gives the shortest
+  // launch (94 us against 98 us at 1.4, the ratio of the two classes timed alone).
+  c->attn_t_iter[0] = 1.85;
+  c->attn_t_iter[1] = 3.4;
 }
 
 extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc, const synera_weights* w,
@@ -216,11 +239,10 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
       return SYNERA_EHIP;
     }
     c->attn_blocks = 2 * std::max(1, prop.multiProcessorCount);
-    if (const char* env = getenv("SYNERA_ATTN_BLOCKS")) {   // tuning knob
-      const long v = strtol(env, nullptr, 10);
-      if (v >= 2 && v <= 8192) c->attn_blocks = (int32_t)v;   // two at least: one per class of streams
-    }
+    c->attn_blocks_cap = 2 * c->attn_blocks;
   }
+  attention_plan_defaults(c);
+  c->lo_off = 0;
   size_plan(c);
 
   const size_t T = (size_t)max_tokens, R = (size_t)c->max_rows;
@@ -239,24 +261,24 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   const size_t o_pml = take(c->part_cap * 64 * 2 * 4);
   const size_t o_rml = take(T * (size_t)m.n_q_heads * 8);
   c->gpart_elems = T * std::max<size_t>(qkv_dim, (size_t)m.d_model);
-  const size_t o_gp = take(SY_MAX_DEFERRED_SPLIT * c->gpart_elems * 4);
+  const size_t o_gp = take(SY_MAX_K_SLICES * c->gpart_elems * 4);
   if (hipMalloc(reinterpret_cast<void**>(&c->arena), off) != hipSuccess) {
     (void)hipGetLastError();
     delete c;
     return SYNERA_ENOMEM;
   }
   c->x = reinterpret_cast<float*>(c->arena + o_x);
-  c->y = reinterpret_cast<bf16_t*>(c->arena + o_y);
-  c->y_lo = reinterpret_cast<bf16_t*>(c->arena + o_yl);
+  c->y = reinterpret_cast<uint16_t*>(c->arena + o_y);
+  c->y_lo = reinterpret_cast<uint16_t*>(c->arena + o_yl);
   c->q_lo = reinterpret_cast<bf16_t*>(c->arena + o_ql);
-  c->o_lo = reinterpret_cast<bf16_t*>(c->arena + o_ol);
-  c->act_lo = reinterpret_cast<bf16_t*>(c->arena + o_actl);
-  c->ysel_lo = reinterpret_cast<bf16_t*>(c->arena + o_ysell);
+  c->o_lo = reinterpret_cast<uint16_t*>(c->arena + o_ol);
+  c->act_lo = reinterpret_cast<uint16_t*>(c->arena + o_actl);
+  c->ysel_lo = reinterpret_cast<uint16_t*>(c->arena + o_ysell);
   c->qkv = reinterpret_cast<float*>(c->arena + o_qkv);
   c->q = reinterpret_cast<bf16_t*>(c->arena + o_q);
-  c->o = reinterpret_cast<bf16_t*>(c->arena + o_o);
-  c->act = reinterpret_cast<bf16_t*>(c->arena + o_act);
-  c->ysel = reinterpret_cast<bf16_t*>(c->arena + o_ysel);
+  c->o = reinterpret_cast<uint16_t*>(c->arena + o_o);
+  c->act = reinterpret_cast<uint16_t*>(c->arena + o_act);
+  c->ysel = reinterpret_cast<uint16_t*>(c->arena + o_ysel);
   c->logits = reinterpret_cast<float*>(c->arena + o_logits);
   c->lm_ids = reinterpret_cast<int32_t*>(c->arena + o_ids);
   c->lm_p = reinterpret_cast<float*>(c->arena + o_p);
@@ -324,7 +346,7 @@ struct Plan {
 // n_second == nullptr means "append only": no LM rows, no attention items.
 static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, const int32_t* n_unc,
                           const int32_t* n_draft, const int32_t* block_table, int32_t max_pages, bool with_attention,
-                          hipStream_t stream, Plan& p, bool host_only = false) {
+                          hipStream_t stream, Plan& p, bool host_only = false, bool* uploaded = nullptr) {
   c->last.valid = false;       // the metadata slots rotate: what synera_importance reads belongs to the newest verify only
   const int slot = (int)(c->calls % N_STAGE);
   if (!host_only && c->pending[slot]) {
@@ -400,21 +422,7 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
     // up to 32 rows) are laid end to end and cut into shares of equal modelled time, one per block.
     const int G = c->desc.n_q_heads / c->desc.n_kv_heads, Hkv = c->desc.n_kv_heads;
     const int tg = c->rows_per_group_tokens;
-    // What a stream costs a block beyond its tiles and query positions (its last iteration merges the key
-    // phases or writes partials, and stores the rows), in iterations: part of the balance between blocks.
-    // One iteration, from a sweep on the headline batch (512 streams of 4 to 128 tiles on 512 blocks: 94 us
-    // per layer without the term, 89 - 90 us with 1, 91 us with 2; the uniform batches do not care).
-    double stream_cost = 1.0;
-    double cut_slack = 1.5;                           // a stream that overshoots its block's share by less is not
-                                                      // cut (iterations; swept: 0 .. 1.5 best, 3 +1.5 %, 8 +9 %)
-    if (const char* env = getenv("SYNERA_ATTN_CUT_SLACK")) {      // tuning knob
-      const double v = strtod(env, nullptr);
-      if (v >= 0.0 && v <= 64.0) cut_slack = v;
-    }
-    if (const char* env = getenv("SYNERA_ATTN_STREAM_COST")) {    // tuning knob
-      const double v = strtod(env, nullptr);
-      if (v >= 0.0 && v <= 16.0) stream_cost = v;
-    }
+    const double stream_cost = c->attn_stream_cost, cut_slack = c->attn_cut_slack;
     struct Stream { int req, tok0, j0, ntok, keys; };
     std::vector<Stream> cls[2];                      // [0]: rbn 4, [1]: rbn 2
     double iters[2] = {0.0, 0.0};                    // iterations of each class (every stream once per KV head)
@@ -429,15 +437,7 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
         iters[k] += Hkv * ((k == 0 ? 2 + tiles : 1 + (tiles + 1) / 2) + stream_cost);
       }
     }
-    // Relative time per iteration of the two classes (four row blocks, one tile: 1; two row blocks x two key
-    // phases, two tiles: 1.85), which decides how many of the persistent blocks each class gets.  From a sweep
-    // of the ratio on the headline batch, where the classes hold about half of the tiles each: 1.8 - 2.0 gives
-    // the shortest launch (94 us against 98 us at 1.4, the ratio of the two classes timed alone).
-    double t_iter[2] = {1.85, 3.4};
-    if (const char* env = getenv("SYNERA_ATTN_T_ITER_RATIO")) {   // tuning knob: the ratio above
-      const double v = strtod(env, nullptr);
-      if (v >= 0.25 && v <= 8.0) t_iter[1] = t_iter[0] * v;
-    }
+    const double t_iter[2] = {c->attn_t_iter[0], c->attn_t_iter[1]};
     const double time_all = iters[0] * t_iter[0] + iters[1] * t_iter[1];
     int nb[2] = {0, 0};
     for (int k = 0; k < 2; ++k)
@@ -449,7 +449,7 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
 
     at = (at + 7) & ~(size_t)7;                      // 32-byte alignment for the structs
     // the program goes last: only its used part is uploaded
-    const size_t o_units = region(c->unit_cap * 8), o_shares = region((size_t)c->attn_blocks * 4);
+    const size_t o_units = region(c->unit_cap * 8), o_shares = region((size_t)c->attn_blocks_cap * 4);
     const size_t o_cuts = region(c->part_cap * 8), o_prog = region(c->pos_cap * 4);
     AttnPos* prog = reinterpret_cast<AttnPos*>(h + o_prog);
     AttnUnit* units = reinterpret_cast<AttnUnit*>(h + o_units);
@@ -544,7 +544,11 @@ static int32_t build_plan(synera_ctx* c, int32_t B, const int32_t* ctx_len, cons
     at = o_prog + n_pos * 4;
   }
   if (at * 4 > c->meta_cap) return SYNERA_ENOSPC;
-  if (!host_only) HIP_TRY(hipMemcpyAsync(d, h, at * 4, hipMemcpyHostToDevice, stream));
+  p.slot = slot;
+  if (!host_only) {
+    HIP_TRY(hipMemcpyAsync(d, h, at * 4, hipMemcpyHostToDevice, stream));
+    if (uploaded) *uploaded = true;
+  }
   p.meta.ctx_len = d + o_ctx;
   p.meta.cu_tok = d + o_cu;
   p.meta.cu_draft = d + o_cud;
@@ -568,11 +572,11 @@ static int32_t finish_call(synera_ctx* c, const Plan& p, hipStream_t stream) {
   return SYNERA_OK;
 }
 
-// parts / n_parts: if given and the contraction is K-split on the tall tiles, the slices are stored to
-// `parts` ([n][M][N], *n_parts = n) for the consumer kernel to add, and cbuf is left alone; otherwise
-// *n_parts = 0 and cbuf holds the result (K-split slices added with atomics).
-static int32_t run_gemm(const bf16_t* a, const bf16_t* a_lo, const void* w0, int r0, const void* w1, int r1,
-                        const void* w2, int r2, void* cbuf, void* cbuf_lo, int M, int N, int K, int epi,
+// One projection.  a / a_lo: the fp16 pair of a_scale x activation.  parts / n_parts: if given, the planner may
+// split K; the slices are then stored to `parts` ([n][M][N], *n_parts = n) for the consumer kernel to add, and
+// cbuf is left alone; otherwise *n_parts = 0 and cbuf holds the result.
+static int32_t run_gemm(const uint16_t* a, const uint16_t* a_lo, float a_scale, const void* w0, int r0, const void* w1,
+                        int r1, const void* w2, int r2, void* cbuf, void* cbuf_lo, int M, int N, int K, int epi,
                         hipStream_t s, float* parts = nullptr, int* n_parts = nullptr) {
   GemmArgs g;
   g.a = a;
@@ -590,43 +594,31 @@ static int32_t run_gemm(const bf16_t* a, const bf16_t* a_lo, const void* w0, int
   g.K = K;
   g.epilogue = epi;
   g.split_k = 1;
-  g.deferred = 0;
-  g.c_parts = parts;
-  if (n_parts) *n_parts = 0;
-  if (parts && n_parts && epi != GEMM_SWIGLU_BF16 && a_lo && gemm_uses_tall_tiles(g)) g.deferred = 1;
+  g.c_parts = (parts && n_parts && epi != GEMM_SWIGLU) ? parts : nullptr;
+  g.out_scale = 1.0f / ((float)(1 << SY_W_SHIFT) * a_scale);
+  g.c_scale = SY_ACT_SCALE;
   g.split_k = gemm_pick_split(g);
-  if (g.deferred && g.split_k > 1) {
-    *n_parts = g.split_k;
-  } else {
-    g.deferred = 0;
-    if (epi == GEMM_STORE_F32 && g.split_k > 1) HIP_TRY(launch_fill_zero(static_cast<float*>(cbuf), (size_t)M * N, s));
-  }
+  if (n_parts) *n_parts = g.split_k > 1 ? g.split_k : 0;
   HIP_TRY(launch_gemm(g, s));
   return SYNERA_OK;
 }
 
 // ------------------------------------------------------------------------------------ verify
-extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_len, const int32_t* h_n_uncached,
-                                 const int32_t* h_n_draft, const int32_t* d_tokens, const int32_t* d_anchor,
-                                 const int32_t* h_block_table, int32_t max_pages, int32_t n_pages_in_pool,
-                                 void* d_k_pool, void* d_v_pool, float* d_logits, int32_t* d_argmax,
-                                 float* d_top1_prob, float* d_entropy, int32_t* d_accept_len,
-                                 int32_t* d_correction, void* stream_) {
-  if (!c || !h_n_uncached || !d_tokens || !d_anchor || !d_k_pool || !d_v_pool || !d_argmax || !d_accept_len ||
-      !d_correction)
-    return SYNERA_EINVAL;
-  if (max_pages > c->max_pages) return SYNERA_ENOSPC;
-  int32_t st = synera_validate_batch(B, h_ctx_len, h_n_draft, h_n_uncached, h_block_table, max_pages,
-                                     n_pages_in_pool, c->max_batch, c->max_tokens, SYNERA_MAX_CHUNK);
-  if (st != SYNERA_OK) return st;
-  hipStream_t s = static_cast<hipStream_t>(stream_);
-  const synera_model_desc& m = c->desc;
-  Plan p;
-  st = build_plan(c, B, h_ctx_len, h_n_uncached, h_n_draft, h_block_table, max_pages, true, s, p);
-  if (st != SYNERA_OK) return st;
+// Sites whose activations travel as (hi, lo) pairs; a bit set in synera_ctx::lo_off makes the producer write the
+// low part as zeros (synera_debug_set_lo_off: the ablation that shows which sites need the second term).
+enum { LO_QKV_IN = SYNERA_LO_QKV_IN, LO_GATE_UP_IN = SYNERA_LO_GATE_UP_IN, LO_DOWN_IN = SYNERA_LO_DOWN_IN,
+       LO_O_IN = SYNERA_LO_O_IN, LO_LM_HEAD_IN = SYNERA_LO_LM_HEAD_IN, LO_Q = SYNERA_LO_Q, LO_P = SYNERA_LO_P };
 
+// Every launch of one verify, after the plan's metadata upload has been queued.
+static int32_t verify_launches(synera_ctx* c, const Plan& p, int32_t B, const int32_t* d_tokens, const int32_t* d_anchor,
+                               int32_t n_pages_in_pool, void* d_k_pool, void* d_v_pool, float* d_logits,
+                               int32_t* d_argmax, float* d_top1_prob, float* d_entropy, int32_t* d_accept_len,
+                               int32_t* d_correction, hipStream_t s) {
+  const synera_model_desc& m = c->desc;
+  int32_t st;
   const int T = p.T, d = m.d_model, Hq = m.n_q_heads, Hkv = m.n_kv_heads, hd = m.head_dim;
   const int qd = Hq * hd, kd = Hkv * hd;
+  const int lo_off = c->lo_off;
   const size_t layer_elems = (size_t)n_pages_in_pool * Hkv * SY_PAGE * hd;
   HIP_TRY(launch_embed(static_cast<const bf16_t*>(c->embed), d_tokens, c->x, T, d, m.vocab, s));
   HIP_TRY(launch_rope_table(p.meta, c->cs, T, hd, m.rope_base, s));
@@ -644,6 +636,7 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   al.part_o = c->part_o;
   al.part_ml = c->part_ml;
   al.o = c->o;
+  al.lo_off = ((lo_off & LO_P) ? 1 : 0) | ((lo_off & LO_O_IN) ? 2 : 0);
   al.T = T;
   al.Hq = Hq;
   al.Hkv = Hkv;
@@ -660,20 +653,20 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
     {
       StageTimer t(c, SYNERA_STAGE_NORM, s);
       HIP_TRY(launch_rmsnorm(c->x, c->gparts, pend, x_stride, static_cast<const bf16_t*>(w.attn_norm), nullptr, c->y,
-                             c->y_lo, T, d, m.rms_eps, s));
+                             c->y_lo, T, d, m.rms_eps, (lo_off & LO_QKV_IN) != 0, s));
       pend = 0;
     }
     int qkv_parts = 0;
     {
       StageTimer t(c, SYNERA_STAGE_QKV, s);
-      if ((st = run_gemm(c->y, c->y_lo, w.wq, qd, w.wk, kd, w.wv, kd, c->qkv, nullptr, T, qd + 2 * kd, d,
+      if ((st = run_gemm(c->y, c->y_lo, SY_Y_SCALE, w.wq, qd, w.wk, kd, w.wv, kd, c->qkv, nullptr, T, qd + 2 * kd, d,
                          GEMM_STORE_F32, s, c->gparts, &qkv_parts)))
         return st;
     }
     {
       StageTimer t(c, SYNERA_STAGE_ROPE_APPEND, s);
       HIP_TRY(launch_rope_append(qkv_parts ? c->gparts : c->qkv, qkv_parts, qkv_stride, c->cs, p.meta, c->q, c->q_lo,
-                                 k_layer, v_layer, T, Hq, Hkv, hd, s));
+                                 k_layer, v_layer, T, Hq, Hkv, hd, (lo_off & LO_Q) != 0, s));
     }
     al.k_layer = k_layer;
     al.v_layer = v_layer;
@@ -684,26 +677,27 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
     }
     {
       StageTimer t(c, SYNERA_STAGE_O, s);
-      if ((st = run_gemm(c->o, c->o_lo, w.wo, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, qd, GEMM_ADD_F32, s,
-                         c->gparts, &pend)))
+      if ((st = run_gemm(c->o, c->o_lo, SY_O_SCALE, w.wo, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, qd,
+                         GEMM_ADD_F32, s, c->gparts, &pend)))
         return st;
     }
     {
       StageTimer t(c, SYNERA_STAGE_NORM, s);
       HIP_TRY(launch_rmsnorm(c->x, c->gparts, pend, x_stride, static_cast<const bf16_t*>(w.mlp_norm), nullptr, c->y,
-                             c->y_lo, T, d, m.rms_eps, s));
+                             c->y_lo, T, d, m.rms_eps, (lo_off & LO_GATE_UP_IN) != 0, s));
       pend = 0;
     }
     {
       StageTimer t(c, SYNERA_STAGE_GATE_UP, s);
-      if ((st = run_gemm(c->y, c->y_lo, w.w_gate, 0, w.w_up, 0, nullptr, 0, c->act, c->act_lo, T, 2 * m.d_ffn, d,
-                         GEMM_SWIGLU_BF16, s)))
+      if ((st = run_gemm(c->y, c->y_lo, SY_Y_SCALE, w.w_gate, 0, w.w_up, 0, nullptr, 0, c->act,
+                         c->act_lo, T, 2 * m.d_ffn, d, GEMM_SWIGLU, s)))
         return st;
     }
+    if (lo_off & LO_DOWN_IN) HIP_TRY(launch_fill_zero(reinterpret_cast<float*>(c->act_lo), (size_t)T * m.d_ffn / 2, s));
     {
       StageTimer t(c, SYNERA_STAGE_DOWN, s);
-      if ((st = run_gemm(c->act, c->act_lo, w.w_down, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, m.d_ffn,
-                         GEMM_ADD_F32, s, c->gparts, &pend)))
+      if ((st = run_gemm(c->act, c->act_lo, SY_ACT_SCALE, w.w_down, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d,
+                         m.d_ffn, GEMM_ADD_F32, s, c->gparts, &pend)))
         return st;
     }
   }
@@ -712,12 +706,12 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   const bool extra = p.R_all > p.R;
   // (the last down projection's slices are added here, for the selected rows only)
   HIP_TRY(launch_rmsnorm(c->x, c->gparts, pend, x_stride, static_cast<const bf16_t*>(c->final_norm), p.meta.sel_rows,
-                         c->ysel, c->ysel_lo, p.R_all, d, m.rms_eps, s));
+                         c->ysel, c->ysel_lo, p.R_all, d, m.rms_eps, (lo_off & LO_LM_HEAD_IN) != 0, s));
   float* logits = (d_logits && !extra) ? d_logits : c->logits;
   {
     StageTimer t(c, SYNERA_STAGE_LM_HEAD, s);
-    if ((st = run_gemm(c->ysel, c->ysel_lo, c->lm_head, m.vocab, nullptr, 0, nullptr, 0, logits, nullptr, p.R_all,
-                       m.vocab, d, GEMM_STORE_F32, s)))
+    if ((st = run_gemm(c->ysel, c->ysel_lo, SY_Y_SCALE, c->lm_head, m.vocab, nullptr, 0, nullptr, 0, logits, nullptr,
+                       p.R_all, m.vocab, d, GEMM_STORE_F32, s)))
       return st;
   }
   float* p_out = (d_top1_prob && !extra) ? d_top1_prob : c->lm_p;
@@ -733,6 +727,36 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
     if (d_entropy) HIP_TRY(hipMemcpyAsync(d_entropy, c->lm_h, (size_t)p.R * 4, hipMemcpyDeviceToDevice, s));
   }
   HIP_TRY(launch_accept(d_tokens, d_anchor, c->lm_ids, p.meta, B, p.R, d_argmax, d_accept_len, d_correction, s));
+  return SYNERA_OK;
+}
+
+extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_len, const int32_t* h_n_uncached,
+                                 const int32_t* h_n_draft, const int32_t* d_tokens, const int32_t* d_anchor,
+                                 const int32_t* h_block_table, int32_t max_pages, int32_t n_pages_in_pool,
+                                 void* d_k_pool, void* d_v_pool, float* d_logits, int32_t* d_argmax,
+                                 float* d_top1_prob, float* d_entropy, int32_t* d_accept_len,
+                                 int32_t* d_correction, void* stream_) {
+  if (!c || !h_n_uncached || !d_tokens || !d_anchor || !d_k_pool || !d_v_pool || !d_argmax || !d_accept_len ||
+      !d_correction)
+    return SYNERA_EINVAL;
+  if (max_pages > c->max_pages) return SYNERA_ENOSPC;
+  int32_t st = synera_validate_batch(B, h_ctx_len, h_n_draft, h_n_uncached, h_block_table, max_pages,
+                                     n_pages_in_pool, c->max_batch, c->max_tokens, SYNERA_MAX_CHUNK);
+  if (st != SYNERA_OK) return st;
+  hipStream_t s = static_cast<hipStream_t>(stream_);
+  Plan p;
+  bool uploaded = false;
+  st = build_plan(c, B, h_ctx_len, h_n_uncached, h_n_draft, h_block_table, max_pages, true, s, p, false, &uploaded);
+  if (st == SYNERA_OK)
+    st = verify_launches(c, p, B, d_tokens, d_anchor, n_pages_in_pool, d_k_pool, d_v_pool, d_logits, d_argmax,
+                         d_top1_prob, d_entropy, d_accept_len, d_correction, s);
+  if (uploaded) {
+    // Whatever was queued reads the metadata slot: mark it busy and move on to the next one even when a launch
+    // failed half way, so that the next call cannot overwrite a slot the stream has not finished with.
+    const int32_t fin = finish_call(c, p, s);
+    if (st == SYNERA_OK) st = fin;
+  }
+  if (st != SYNERA_OK) return st;
   c->last.ctx_len = p.meta.ctx_len;
   c->last.cu_tok = p.meta.cu_tok;
   c->last.block_table = p.meta.block_table;
@@ -741,7 +765,7 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   c->last.cu_keys = p.d_cu_keys;
   c->last.items = p.d_imp_items;
   c->last.B = B;
-  c->last.T = T;
+  c->last.T = p.T;
   c->last.n_pages_in_pool = n_pages_in_pool;
   c->last.k_pool = d_k_pool;
   c->last.R = p.R;
@@ -750,8 +774,9 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   c->last.n_items = p.n_imp_items;
   c->last.max_pages = max_pages;
   c->last.total_keys = p.total_keys;
+  c->last.slot = p.slot;
   c->last.valid = true;
-  return finish_call(c, p, s);
+  return SYNERA_OK;
 }
 
 // ------------------------------------------------------------------------------------ stochastic verification
@@ -806,6 +831,9 @@ extern "C" int32_t synera_importance(synera_ctx* c, int32_t n_pages_in_pool, con
   HIP_TRY(launch_importance(a, s));
   HIP_TRY(launch_importance_dispatch(d_importance, c->last.cu_keys, c->last.ctx_len, c->last.n_unc, c->last.cu_draft,
                                      c->last.B, i_th, theta, d_mean_importance, d_p_imp, s));
+  // these kernels read that verify's metadata slot: it stays busy until they are through
+  HIP_TRY(hipEventRecord(c->done[c->last.slot], s));
+  c->pending[c->last.slot] = true;
   return SYNERA_OK;
 }
 
@@ -900,10 +928,12 @@ extern "C" int32_t synera_kv_append(synera_ctx* c, int32_t layer, int32_t B, con
   if (st != SYNERA_OK) return st;
   const int Hkv = c->desc.n_kv_heads, hd = c->desc.head_dim;
   const size_t layer_elems = (size_t)n_pages_in_pool * Hkv * SY_PAGE * hd;
-  HIP_TRY(launch_kv_append(static_cast<const bf16_t*>(d_k), static_cast<const bf16_t*>(d_v), p.meta, B,
-                           static_cast<bf16_t*>(d_k_pool) + (size_t)layer * layer_elems,
-                           static_cast<bf16_t*>(d_v_pool) + (size_t)layer * layer_elems, p.T, Hkv, hd, s));
-  return finish_call(c, p, s);
+  const hipError_t e = launch_kv_append(static_cast<const bf16_t*>(d_k), static_cast<const bf16_t*>(d_v), p.meta, B,
+                                        static_cast<bf16_t*>(d_k_pool) + (size_t)layer * layer_elems,
+                                        static_cast<bf16_t*>(d_v_pool) + (size_t)layer * layer_elems, p.T, Hkv, hd, s);
+  if (e != hipSuccess) (void)hipGetLastError();
+  const int32_t fin = finish_call(c, p, s);      // the upload is queued either way: the slot is busy
+  return e != hipSuccess ? SYNERA_EHIP : fin;
 }
 
 // ------------------------------------------------------------------------------------ plain GEMM
@@ -959,7 +989,8 @@ extern "C" int32_t synera_debug_attention_plan(const synera_model_desc* desc, in
   c->max_tokens = (int32_t)T;
   c->max_pages = max_pages;
   c->max_rows = (int32_t)T + B;
-  c->attn_blocks = attn_blocks;
+  c->attn_blocks = c->attn_blocks_cap = attn_blocks;
+  attention_plan_defaults(c);
   c->arena = nullptr;
   c->calls = 0;
   for (int s = 0; s < N_STAGE; ++s) {
@@ -998,17 +1029,16 @@ extern "C" int32_t synera_debug_gemm_plan(int32_t M, int32_t N, int32_t K, int32
                                           int32_t* h_tile_rows, int32_t* h_tile_cols, int32_t* h_k_slices) {
   if (!h_tile_rows || !h_tile_cols || !h_k_slices || M < 1 || N < 1 || K < 1 || epilogue < 0 || epilogue > 2)
     return SYNERA_EINVAL;
-  if (N % (epilogue == GEMM_SWIGLU_BF16 ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
+  if (N % (epilogue == GEMM_SWIGLU ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
   GemmArgs g{};
-  g.a_lo = reinterpret_cast<const bf16_t*>(uintptr_t(64));   // the planner only asks whether there is a low part
-  g.w_rows[0] = epilogue == GEMM_SWIGLU_BF16 ? N / 2 : N;
-  g.w_rows[1] = epilogue == GEMM_SWIGLU_BF16 ? N / 2 : 0;
+  g.w_rows[0] = epilogue == GEMM_SWIGLU ? N / 2 : N;
+  g.w_rows[1] = epilogue == GEMM_SWIGLU ? N / 2 : 0;
   g.M = M;
   g.N = N;
   g.K = K;
   g.epilogue = epilogue;
   g.split_k = 1;
-  g.deferred = stored_slices && epilogue != GEMM_SWIGLU_BF16 && gemm_uses_tall_tiles(g) ? 1 : 0;   // as run_gemm decides
+  g.c_parts = stored_slices && epilogue != GEMM_SWIGLU ? reinterpret_cast<float*>(uintptr_t(64)) : nullptr;   // only asked whether there
   int bm = 0, bn = 0, split = 1;
   gemm_plan(g, &bm, &bn, &split);
   *h_tile_rows = bm;
@@ -1021,31 +1051,51 @@ extern "C" int32_t synera_debug_gemm_epilogue(const void* d_a, const void* d_a_l
                                               void* d_c, void* d_c_lo, int32_t M, int32_t N, int32_t K,
                                               int32_t epilogue, void* stream) {
   if (!d_a || !d_a_lo || !d_w0 || !d_c || M < 1 || N < 1 || K < 1 || epilogue < 0 || epilogue > 2) return SYNERA_EINVAL;
-  if (epilogue == GEMM_SWIGLU_BF16 && (!d_w1 || !d_c_lo)) return SYNERA_EINVAL;
-  if (N % (epilogue == GEMM_SWIGLU_BF16 ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
-  const bool glu = epilogue == GEMM_SWIGLU_BF16;
-  return run_gemm(static_cast<const bf16_t*>(d_a), static_cast<const bf16_t*>(d_a_lo), d_w0, glu ? N / 2 : N,
+  if (epilogue == GEMM_SWIGLU && (!d_w1 || !d_c_lo)) return SYNERA_EINVAL;
+  if (N % (epilogue == GEMM_SWIGLU ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
+  const bool glu = epilogue == GEMM_SWIGLU;
+  return run_gemm(static_cast<const uint16_t*>(d_a), static_cast<const uint16_t*>(d_a_lo), 1.0f, d_w0, glu ? N / 2 : N,
                   glu ? d_w1 : nullptr, glu ? N / 2 : 0, nullptr, 0, d_c, d_c_lo, M, N, K, epilogue,
                   static_cast<hipStream_t>(stream));
 }
 
-static_assert(SYNERA_MAX_GEMM_SLICES == SY_MAX_DEFERRED_SPLIT, "header and planner disagree on the slice limit");
-extern "C" int32_t synera_debug_gemm_deferred(const void* d_a, const void* d_a_lo, const void* d_w, float* d_parts,
-                                              int32_t M, int32_t N, int32_t K, int32_t* h_n_parts, void* stream) {
+static_assert(SYNERA_MAX_GEMM_SLICES == SY_MAX_K_SLICES, "header and planner disagree on the slice limit");
+extern "C" int32_t synera_debug_gemm_slices(const void* d_a, const void* d_a_lo, const void* d_w, float* d_parts,
+                                            int32_t M, int32_t N, int32_t K, int32_t* h_n_parts, void* stream) {
   if (!d_a || !d_a_lo || !d_w || !d_parts || !h_n_parts || M < 1 || N < 1 || K < 1) return SYNERA_EINVAL;
   if (N % 128 != 0 || K % 64 != 0) return SYNERA_EUNSUP;
   int n_parts = 0;
-  const int32_t st = run_gemm(static_cast<const bf16_t*>(d_a), static_cast<const bf16_t*>(d_a_lo), d_w, N, nullptr, 0,
-                              nullptr, 0, d_parts, nullptr, M, N, K, GEMM_STORE_F32, static_cast<hipStream_t>(stream),
-                              d_parts, &n_parts);
+  const int32_t st = run_gemm(static_cast<const uint16_t*>(d_a), static_cast<const uint16_t*>(d_a_lo), 1.0f, d_w, N,
+                              nullptr, 0, nullptr, 0, d_parts, nullptr, M, N, K, GEMM_STORE_F32,
+                              static_cast<hipStream_t>(stream), d_parts, &n_parts);
   *h_n_parts = n_parts > 0 ? n_parts : 1;
   return st;
 }
 
-extern "C" int32_t synera_gemm_bf16(const void* d_a, const void* d_a_lo, const void* d_w, float* d_c, int32_t M,
+extern "C" int32_t synera_gemm_pair(const void* d_a, const void* d_a_lo, const void* d_w, float* d_c, int32_t M,
                                     int32_t N, int32_t K, void* stream) {
-  if (!d_a || !d_w || !d_c || M < 1 || N < 1 || K < 1) return SYNERA_EINVAL;
+  if (!d_a || !d_a_lo || !d_w || !d_c || M < 1 || N < 1 || K < 1) return SYNERA_EINVAL;
   if (N % 128 != 0 || K % 64 != 0) return SYNERA_EUNSUP;
-  return run_gemm(static_cast<const bf16_t*>(d_a), static_cast<const bf16_t*>(d_a_lo), d_w, N, nullptr, 0, nullptr, 0, d_c, nullptr, M, N, K,
-                  GEMM_STORE_F32, static_cast<hipStream_t>(stream));
+  return run_gemm(static_cast<const uint16_t*>(d_a), static_cast<const uint16_t*>(d_a_lo), 1.0f, d_w, N, nullptr, 0,
+                  nullptr, 0, d_c, nullptr, M, N, K, GEMM_STORE_F32, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t synera_debug_set_lo_off(synera_ctx* c, int32_t sites) {
+  if (!c || sites < 0 || sites > 127) return SYNERA_EINVAL;
+  c->lo_off = sites;
+  return SYNERA_OK;
+}
+
+extern "C" int32_t synera_debug_set_attention_plan(synera_ctx* c, int32_t attn_blocks, float stream_cost,
+                                                   float cut_slack, float t_iter_ratio) {
+  if (!c) return SYNERA_EINVAL;
+  if (attn_blocks != 0 && (attn_blocks < 2 || attn_blocks > c->attn_blocks_cap)) return SYNERA_EINVAL;
+  if (!(stream_cost >= 0.0f && stream_cost <= 16.0f) || !(cut_slack >= 0.0f && cut_slack <= 64.0f) ||
+      !(t_iter_ratio >= 0.25f && t_iter_ratio <= 8.0f))
+    return SYNERA_EINVAL;
+  if (attn_blocks) c->attn_blocks = attn_blocks;
+  c->attn_stream_cost = stream_cost;
+  c->attn_cut_slack = cut_slack;
+  c->attn_t_iter[1] = c->attn_t_iter[0] * t_iter_ratio;
+  return SYNERA_OK;
 }

@@ -28,8 +28,9 @@
 //     V pages are stored dim-major ([dim][slot]), which makes the A operand of that product plain
 //     8-byte LDS reads.  Row sums ride on the matrix core (an all-ones A operand).
 //   * q and the probabilities enter the matrix cores as bf16 (hi, lo) pairs (two MFMAs per
-//     product, K/V fragments reused), and o leaves as a pair: single bf16 terms here cost the
-//     logits of a deep decoder an order of magnitude in accuracy.
+//     product, K/V fragments reused; the cache is bf16, so these products stay bf16), and o leaves as
+//     the fp16 pair the output projection consumes: single bf16 terms here cost the logits of a deep
+//     decoder an order of magnitude in accuracy.
 //   * The compiler cannot see the asynchronous copies (inline assembly), and any vector-memory load it
 //     emits itself inside the loop would be guarded by a wait that drains them.  The loop's own small
 //     reads -- program entries, stream descriptors -- therefore go through the constant address space
@@ -53,15 +54,13 @@ __device__ __forceinline__ float row_max4(float v) {
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
-// Four consecutive outputs as a bf16 (hi, lo) pair: 8 bytes to each array.
-__device__ __forceinline__ void store_pair(bf16_t* hi, bf16_t* lo, float a, float b, float c, float d) {
+// Four consecutive outputs as the fp16 (hi, lo) pair of SY_O_SCALE x value: 8 bytes to each array.
+__device__ __forceinline__ void store_pair(uint16_t* hi, uint16_t* lo, float a, float b, float c, float d, bool lo_off) {
   uint2 h, l;
-  h.x = pack_bf2(a, b);
-  h.y = pack_bf2(c, d);
-  l.x = pack_bf2(a - bf2f(h.x & 0xFFFF), b - bf2f(h.x >> 16));
-  l.y = pack_bf2(c - bf2f(h.y & 0xFFFF), d - bf2f(h.y >> 16));
+  split_f16x2(a * SY_O_SCALE, b * SY_O_SCALE, h.x, l.x);
+  split_f16x2(c * SY_O_SCALE, d * SY_O_SCALE, h.y, l.y);
   *reinterpret_cast<uint2*>(hi) = h;
-  *reinterpret_cast<uint2*>(lo) = l;
+  *reinterpret_cast<uint2*>(lo) = lo_off ? make_uint2(0u, 0u) : l;
 }
 
 // Asynchronous 16-byte-per-lane copy global -> LDS; lane i lands at lds_addr + 16 i (m0 carries the
@@ -324,6 +323,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
       pl.y = pack_bf2(p[2] - bf2f(pk.y & 0xFFFF), p[3] - bf2f(pk.y >> 16));
       pl.z = pack_bf2(p[4] - bf2f(pk.z & 0xFFFF), p[5] - bf2f(pk.z >> 16));
       pl.w = pack_bf2(p[6] - bf2f(pk.w & 0xFFFF), p[7] - bf2f(pk.w >> 16));
+      if (a.lo_off & 1) pl = make_uint4(0u, 0u, 0u, 0u);   // ablation of the probabilities' low part (block-uniform)
       const bf16x8 pf = __builtin_bit_cast(bf16x8, pk);
       const bf16x8 pfl = __builtin_bit_cast(bf16x8, pl);
       // Rescale the accumulators only when some row's reference moved (the first tile, then hardly ever).
@@ -414,7 +414,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
 #pragma unroll
         for (int db = 0; db < DB; ++db)
           store_pair(a.o + at + db * 16, a.o_lo + at + db * 16, acc[db][0] * inv, acc[db][1] * inv,
-                     acc[db][2] * inv, acc[db][3] * inv);
+                     acc[db][2] * inv, acc[db][3] * inv, (a.lo_off & 2) != 0);
         if (a.row_ml && g == 0)
           a.row_ml[(size_t)(u_tok0 + row / G) * Hq + u_kh * G + row % G] = make_float2(m_fin, l_run);
       } else {
@@ -457,7 +457,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnLaunch a) {
     }
     const float inv = 1.0f / l;
     const size_t at = ((size_t)(c.tok0 + row / G) * Hq + c.kh * G + row % G) * HD + d4;
-    store_pair(a.o + at, a.o_lo + at, sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
+    store_pair(a.o + at, a.o_lo + at, sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv, (a.lo_off & 2) != 0);
     if (a.row_ml && d4 == 0) a.row_ml[(size_t)(c.tok0 + row / G) * Hq + c.kh * G + row % G] = make_float2(M, l);
   }
 }

@@ -3,7 +3,7 @@
 // measurement tools launch them in the same process as the kernels they compare with, because the
 // sustained matrix-core rate depends on the operands (the clock drops under the switching activity of
 // random mantissas) and differs from box to box.
-#include "../../include/synera.h"
+#include "../../include/synera_debug.h"
 #include "common.h"
 
 // Both streams split the `n16` 16-byte pieces into one contiguous segment of `seg` pieces per block; lane t

@@ -12,8 +12,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 #define SY_PAGE 16
 
-// Activations travel between kernels as a bf16 pair (hi, lo): hi = bf16(v), lo = bf16(v - hi), which keeps
-// about 16 mantissa bits while every matrix-core operand stays bf16.
 // fp32 -> bf16, round-to-nearest-even, two at a time with gfx950's v_cvt_pk_bf16_f32.
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) float f32x2_t;
@@ -23,6 +21,25 @@ __device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
 }
 __device__ __forceinline__ uint32_t f2bf(float f) { return pack_bf2(f, 0.f) & 0xFFFFu; }
 __device__ __forceinline__ float bf2f(uint32_t b) { return __uint_as_float(b << 16); }
+
+// The inputs of the projection GEMMs travel between kernels as an fp16 pair (hi, lo): hi = fp16(s v),
+// lo = fp16(s v - hi), 22 mantissa bits of the fp32 value v.  s is a power of two fixed per producer (below) that
+// lifts typical activations to 2^3 .. 2^6, so that the lo part of all but tiny elements stays in fp16's normal
+// range whether or not the matrix cores flush subnormal inputs; the consuming GEMM divides it out again.
+// Scaled values beyond +-65504 (activations of magnitude 1000 / 8000) overflow to infinity and surface as
+// non-finite logits: nothing is clamped, so a NaN in the input stays a NaN too.
+#define SY_Y_SCALE 64.0f      // RMSNorm output (|y| <= sqrt(d) |gain|)
+#define SY_O_SCALE 64.0f      // attention output (a convex combination of V rows)
+#define SY_ACT_SCALE 8.0f     // SiLU(gate) * up
+#define SY_W_SHIFT 8          // exponent added to the bf16 weights on their way to fp16 (weights below 256)
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+__device__ __forceinline__ void split_f16x2(float a, float b, uint32_t& hi, uint32_t& lo) {   // a, b: scaled values
+  const f32x2_t v = {a, b};
+  const f16x2_t h = __builtin_convertvector(v, f16x2_t);
+  const f32x2_t r = v - __builtin_convertvector(h, f32x2_t);
+  hi = __builtin_bit_cast(uint32_t, h);
+  lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, f16x2_t));
+}
 
 // ---------------------------------------------------------------- elementwise.hip
 struct BatchMeta {        // device pointers into one uploaded metadata blob (all int32)
@@ -41,14 +58,15 @@ hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, in
                         hipStream_t s);
 // parts / n_parts: pending K-split slices [n_parts][T][d] of the projection that feeds the residual; the
 // kernel adds them to x first (and writes x back), so the GEMM needs no atomics.  n_parts = 0: none.
+// y_hi / y_lo: the normalised rows as an fp16 pair scaled by SY_Y_SCALE (lo_off: the low part is written as zeros).
 hipError_t launch_rmsnorm(float* x, const float* parts, int n_parts, size_t part_stride, const bf16_t* gain,
-                          const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo, int n_rows, int d, float eps,
-                          hipStream_t s);
+                          const int32_t* rows, uint16_t* y_hi, uint16_t* y_lo, int n_rows, int d, float eps,
+                          bool lo_off, hipStream_t s);
 hipError_t launch_rope_table(const BatchMeta& m, float2* cs, int T, int head_dim, float base, hipStream_t s);
 // n_parts > 0: qkv points at K-split slices [n_parts][T][(Hq+2Hkv) hd] whose sum is the projection.
 hipError_t launch_rope_append(const float* qkv, int n_parts, size_t part_stride, const float2* cs, const BatchMeta& m,
                               bf16_t* q_hi, bf16_t* q_lo, bf16_t* k_layer, bf16_t* v_layer, int T, int Hq, int Hkv,
-                              int hd, hipStream_t s);
+                              int hd, bool lo_off, hipStream_t s);
 hipError_t launch_kv_append(const bf16_t* k, const bf16_t* v, const BatchMeta& m, int B, bf16_t* k_layer,
                             bf16_t* v_layer, int T, int Hkv, int hd, hipStream_t s);
 hipError_t launch_accept(const int32_t* tokens, const int32_t* anchor, const int32_t* lm_argmax, const BatchMeta& m,
@@ -113,8 +131,9 @@ struct AttnLaunch {
   int32_t n_shares, n_cuts;
   float* part_o;             // [slots][64][hd]
   float* part_ml;            // [slots][64][2]
-  bf16_t* o;                 // [T][Hq][hd], high part of the output pair
-  bf16_t* o_lo;              // low part
+  uint16_t* o;               // [T][Hq][hd], high part of the output's fp16 pair (scaled by SY_O_SCALE)
+  uint16_t* o_lo;            // low part
+  int32_t lo_off;            // ablation: bit 0 drops the low part of the probabilities, bit 1 writes o_lo as zeros
   float2* row_ml;            // optional [T][Hq]: per query row the softmax reference m (exponent-2 domain) and
                              // the sum l of 2^(s - m) over its keys, i.e. p(key) = 2^(s scale log2e - m) / l
   int32_t T, Hq, Hkv, hd;
@@ -144,25 +163,28 @@ hipError_t launch_importance_dispatch(const float* importance, const int32_t* cu
                                       float* mean_imp, float* p_imp, hipStream_t s);
 
 // ---------------------------------------------------------------- gemm.hip
-enum GemmEpilogue { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU_BF16 = 2 };
+enum GemmEpilogue { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU = 2 };
 struct GemmArgs {
-  const bf16_t* a;       // [M][K], high part of the activation pair
-  const bf16_t* a_lo;    // [M][K], low part (nullptr: single-term activations)
-  const bf16_t* w[3];    // up to three row segments of the weight (each [rows][K])
+  const uint16_t* a;     // [M][K], high part of the activation's fp16 pair
+  const uint16_t* a_lo;  // [M][K], low part
+  const bf16_t* w[3];    // up to three row segments of the bf16 weight (each [rows][K])
   int32_t w_rows[3];     // rows per segment (multiples of the N tile); unused = 0
-  void* c;               // f32 [M][N] (STORE/ADD) or bf16 [M][N/2] (SWIGLU: w[0] = gate, w[1] = up)
-  void* c_lo;            // SWIGLU only: low part of the bf16 output pair
+  void* c;               // f32 [M][N] (STORE/ADD) or the high part of an fp16 pair [M][N/2] (SWIGLU: w[0] = gate, w[1] = up)
+  void* c_lo;            // SWIGLU only: low part of the output pair
   int32_t M, N, K;       // N = total output columns of the contraction (gate + up for SWIGLU)
   int32_t epilogue;
-  int32_t split_k;       // >= 1; > 1 only with STORE or ADD
-  int32_t deferred;      // K-split results: 0 = added into c with fp32 atomics (STORE: c pre-zeroed);
-                         // 1 = slice z stored plainly to c_parts + z*M*N, c untouched: the consumer kernel
-                         // (RMSNorm, RoPE) adds the slices (tall tiles only; the launcher falls back to 0)
-  float* c_parts;        // deferred only: [split_k][M][N] fp32
+  int32_t split_k;       // >= 1; > 1 only with STORE or ADD and c_parts: slice z is stored plainly to
+                         // c_parts + z*M*N and c is left alone; the consumer kernel (RMSNorm, RoPE) adds the slices
+  float* c_parts;        // [split_k][M][N] fp32, or nullptr (then the planner never splits K)
+  float out_scale;       // accumulators x this = the product: 2^-SY_W_SHIFT / (the activation pair's scale)
+  float c_scale;         // SWIGLU only: scale of the output pair (SY_ACT_SCALE)
 };
-#define SY_MAX_DEFERRED_SPLIT 8
+#define SY_MAX_K_SLICES 8
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
-int gemm_pick_split(const GemmArgs& g);
-void gemm_plan(const GemmArgs& g, int* bm, int* bn, int* split);   // tile and K slices launch_gemm would use (host only)
-bool gemm_uses_tall_tiles(const GemmArgs& g);   // the tile family that can defer the K-split merge
-void gemm_force_variant(int v);   // tuning hook: -1 automatic, else a tile configuration index
+int gemm_pick_split(const GemmArgs& g);                             // K slices launch_gemm should be given (1 without c_parts)
+void gemm_plan(const GemmArgs& g, int* bm, int* bn, int* split);    // tile and K slices launch_gemm would use (host only)
+void gemm_force_variant(int v);   // tuning hook: -1 automatic, else tile rows / 16 + (128-column tile ? 100 : 0)
+// the instantiations live in three translation units (compile time)
+hipError_t launch_proj_nf4_low(int mt, const GemmArgs& g, hipStream_t s);    // 256 columns, 16 .. 144 rows
+hipError_t launch_proj_nf4_high(int mt, const GemmArgs& g, hipStream_t s);   // 256 columns, 160 .. 272 rows
+hipError_t launch_proj_nf2(int mt, const GemmArgs& g, hipStream_t s);        // 128 columns, 16 .. 192 rows

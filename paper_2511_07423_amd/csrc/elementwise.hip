@@ -33,16 +33,16 @@ hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, in
 }
 
 // ------------------------------------------------------------------ RMSNorm
-// y = x * rsqrt(mean(x^2) + eps) * g, fp32 in, bf16 (hi, lo) pair out.  One block per
-// output row; `rows` (optional) selects which input row feeds output row r.
+// y = x * rsqrt(mean(x^2) + eps) * g, fp32 in, fp16 (hi, lo) pair of SY_Y_SCALE y out (lo_off: lo = 0).  One block
+// per output row; `rows` (optional) selects which input row feeds output row r.
 // With n_parts > 0 the row first takes the pending K-split slices of the projection before it,
 // x += sum_s parts[s], and the sum is written back to x (each thread re-reads only what it wrote).
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, const float* __restrict__ parts,
                                                       int n_parts, size_t part_stride,
                                                       const bf16_t* __restrict__ gain,
                                                       const int32_t* __restrict__ rows,
-                                                      bf16_t* __restrict__ y, bf16_t* __restrict__ y_lo, int d,
-                                                      float eps) {
+                                                      uint16_t* __restrict__ y, uint16_t* __restrict__ y_lo, int d,
+                                                      float eps, bool lo_off) {
   const int r = blockIdx.x;
   const size_t row_at = (size_t)(rows ? rows[r] : r) * d;
   float* src = x + row_at;
@@ -62,21 +62,19 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
   __shared__ float red[4];
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
-  const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
-  bf16_t* dst = y + (size_t)r * d;
-  bf16_t* dst_lo = y_lo + (size_t)r * d;
+  const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps) * SY_Y_SCALE;
+  uint16_t* dst = y + (size_t)r * d;
+  uint16_t* dst_lo = y_lo + (size_t)r * d;
   for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
     float4 v = *reinterpret_cast<const float4*>(src + c);
     uint2 g = *reinterpret_cast<const uint2*>(gain + c);
     const float o0 = v.x * inv * bf2f(g.x & 0xFFFF), o1 = v.y * inv * bf2f(g.x >> 16);
     const float o2 = v.z * inv * bf2f(g.y & 0xFFFF), o3 = v.w * inv * bf2f(g.y >> 16);
     uint2 hi, lo;
-    hi.x = pack_bf2(o0, o1);
-    hi.y = pack_bf2(o2, o3);
-    lo.x = pack_bf2(o0 - bf2f(hi.x & 0xFFFF), o1 - bf2f(hi.x >> 16));
-    lo.y = pack_bf2(o2 - bf2f(hi.y & 0xFFFF), o3 - bf2f(hi.y >> 16));
+    split_f16x2(o0, o1, hi.x, lo.x);
+    split_f16x2(o2, o3, hi.y, lo.y);
     *reinterpret_cast<uint2*>(dst + c) = hi;
-    *reinterpret_cast<uint2*>(dst_lo + c) = lo;
+    *reinterpret_cast<uint2*>(dst_lo + c) = lo_off ? make_uint2(0u, 0u) : lo;
   }
 }
 
@@ -87,8 +85,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
 template <int IT>
 __global__ __launch_bounds__(256) void rmsnorm_row_in_registers_kernel(
     float* __restrict__ x, const float* __restrict__ parts, int n_parts, size_t part_stride,
-    const bf16_t* __restrict__ gain, const int32_t* __restrict__ rows, bf16_t* __restrict__ y,
-    bf16_t* __restrict__ y_lo, int d, float eps) {
+    const bf16_t* __restrict__ gain, const int32_t* __restrict__ rows, uint16_t* __restrict__ y,
+    uint16_t* __restrict__ y_lo, int d, float eps, bool lo_off) {
   const int r = blockIdx.x;
   const size_t row_at = (size_t)(rows ? rows[r] : r) * d;
   float* src = x + row_at;
@@ -128,9 +126,9 @@ __global__ __launch_bounds__(256) void rmsnorm_row_in_registers_kernel(
   __shared__ float red[4];
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
-  const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps);
-  bf16_t* dst = y + (size_t)r * d;
-  bf16_t* dst_lo = y_lo + (size_t)r * d;
+  const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps) * SY_Y_SCALE;
+  uint16_t* dst = y + (size_t)r * d;
+  uint16_t* dst_lo = y_lo + (size_t)r * d;
 #pragma unroll
   for (int k = 0; k < IT; ++k) {
     const int c = threadIdx.x * 4 + k * 1024;
@@ -139,25 +137,23 @@ __global__ __launch_bounds__(256) void rmsnorm_row_in_registers_kernel(
     const float o0 = v[k].x * inv * bf2f(g.x & 0xFFFF), o1 = v[k].y * inv * bf2f(g.x >> 16);
     const float o2 = v[k].z * inv * bf2f(g.y & 0xFFFF), o3 = v[k].w * inv * bf2f(g.y >> 16);
     uint2 hi, lo;
-    hi.x = pack_bf2(o0, o1);
-    hi.y = pack_bf2(o2, o3);
-    lo.x = pack_bf2(o0 - bf2f(hi.x & 0xFFFF), o1 - bf2f(hi.x >> 16));
-    lo.y = pack_bf2(o2 - bf2f(hi.y & 0xFFFF), o3 - bf2f(hi.y >> 16));
+    split_f16x2(o0, o1, hi.x, lo.x);
+    split_f16x2(o2, o3, hi.y, lo.y);
     *reinterpret_cast<uint2*>(dst + c) = hi;
-    *reinterpret_cast<uint2*>(dst_lo + c) = lo;
+    *reinterpret_cast<uint2*>(dst_lo + c) = lo_off ? make_uint2(0u, 0u) : lo;
   }
 }
 
 hipError_t launch_rmsnorm(float* x, const float* parts, int n_parts, size_t part_stride, const bf16_t* gain,
-                          const int32_t* rows, bf16_t* y_hi, bf16_t* y_lo, int n_rows, int d, float eps,
-                          hipStream_t s) {
+                          const int32_t* rows, uint16_t* y_hi, uint16_t* y_lo, int n_rows, int d, float eps,
+                          bool lo_off, hipStream_t s) {
   if (n_rows <= 0) return hipSuccess;
   if (d <= 4096)
-    rmsnorm_row_in_registers_kernel<4><<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
+    rmsnorm_row_in_registers_kernel<4><<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps, lo_off);
   else if (d <= 8192)
-    rmsnorm_row_in_registers_kernel<8><<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
+    rmsnorm_row_in_registers_kernel<8><<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps, lo_off);
   else
-    rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps);
+    rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps, lo_off);
   return hipGetLastError();
 }
 
@@ -192,7 +188,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
                                                           const float2* __restrict__ cs, BatchMeta m,
                                                           bf16_t* __restrict__ q, bf16_t* __restrict__ q_lo,
                                                           bf16_t* __restrict__ k_layer, bf16_t* __restrict__ v_layer,
-                                                          int Hq, int Hkv, int hd) {
+                                                          int Hq, int Hkv, int hd, bool lo_off) {
   const int t = blockIdx.x;
   const int r = m.tok_req[t];
   const int pos = m.ctx_len[r] + (t - m.cu_tok[r]);
@@ -219,7 +215,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
         const uint32_t hi = pack_bf2(r0, r1);
         const size_t at = ((size_t)t * Hq + head) * hd + 2 * i;
         *reinterpret_cast<uint32_t*>(q + at) = hi;
-        *reinterpret_cast<uint32_t*>(q_lo + at) = pack_bf2(r0 - bf2f(hi & 0xFFFF), r1 - bf2f(hi >> 16));
+        *reinterpret_cast<uint32_t*>(q_lo + at) = lo_off ? 0u : pack_bf2(r0 - bf2f(hi & 0xFFFF), r1 - bf2f(hi >> 16));
       } else {
         const int kh = head - Hq;
         bf16_t* dst = k_layer + (((size_t)page * Hkv + kh) * SY_PAGE + slot) * hd + 2 * i;
@@ -236,9 +232,9 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float* __restric
 
 hipError_t launch_rope_append(const float* qkv, int n_parts, size_t part_stride, const float2* cs, const BatchMeta& m,
                               bf16_t* q_hi, bf16_t* q_lo, bf16_t* k_layer, bf16_t* v_layer, int T, int Hq, int Hkv,
-                              int hd, hipStream_t s) {
+                              int hd, bool lo_off, hipStream_t s) {
   if (T <= 0) return hipSuccess;
-  rope_append_kernel<<<dim3(T, 4), 256, 0, s>>>(qkv, n_parts, part_stride, cs, m, q_hi, q_lo, k_layer, v_layer, Hq, Hkv, hd);
+  rope_append_kernel<<<dim3(T, 4), 256, 0, s>>>(qkv, n_parts, part_stride, cs, m, q_hi, q_lo, k_layer, v_layer, Hq, Hkv, hd, lo_off);
   return hipGetLastError();
 }
 

@@ -1,0 +1,304 @@
+// The projection GEMM of the decoder: C[M][N] = A[M][K] * W[N][K]^T on the matrix cores with fp32 accumulation
+// (v_mfma_f32_16x16x32_f16).  Both operands are K-major, so an MFMA operand fragment (8 consecutive k of one
+// row) is one 16-byte read.
+//
+// Operand formats.  Activations arrive as an fp16 pair (hi, lo), hi = fp16(v), lo = fp16(v - hi): 22 mantissa
+// bits of the fp32 value, and the kernel accumulates A_hi * W and A_lo * W into the same accumulators.  Weights
+// are bf16 in memory (8 mantissa bits: exact in fp16) and are turned into fp16 in registers, four vector
+// instructions per packed pair, with their exponents raised by SY_W_SHIFT so that small weights stay in fp16's
+// normal range (2^-14 2^-SY_W_SHIFT .. 65504 2^-SY_W_SHIFT); the epilogue multiplies the accumulators by
+// GemmArgs::out_scale, which takes that factor and the producer's activation scale out again (powers of two:
+// exact).  The lo term reuses the weight fragments already in registers, so it costs MFMA issue slots but no
+// extra weight traffic from HBM, L2 or LDS.  (The same pair in bf16 carries 16 bits; its rounding noise, amplified
+// layer by layer through bf16 KV-cache roundings that fall the other way, put the logits of an 80-layer decoder
+// of width 8192 at 5e-2 from the exact result.)
+//
+// Tile: BM = 16 MT rows x BN = 64 NF columns, four wavefronts (one per SIMD), each owning all BM rows of 16 NF
+// columns.  BK = 32 is exactly one MFMA K step: lane l holds row l % 16 and the 8 k values of chunk l / 16 for
+// both operands.  The weight fragment is the MFMA's first operand, so a lane ends up with 4 consecutive output
+// columns of one row and the epilogue stores 16 bytes per lane.  Per K step a wavefront reads its NF weight
+// fragments once and streams the 2 MT activation fragments (hi, lo) through them; each activation fragment feeds
+// NF independent accumulators, which is what this 4-pass MFMA needs to issue back to back.  Accumulators 0..255
+// live in AGPRs, the rest in VGPRs.
+//
+// Data movement: the rows [A_hi | A_lo | W] of K step s+2 stream straight from global memory into LDS
+// (global_load_lds_dwordx4: no staging registers, no LDS store instructions) while step s is multiplied; three
+// LDS stages.  A copy instruction of one wavefront fills 1 KB = 16 tile rows; the XOR swizzle that keeps the
+// fragment reads bank-conflict free is applied on the global side (lane i fetches the chunk that belongs at LDS
+// position i).  Per K step each wavefront waits for its own copies of the step (s_waitcnt vmcnt) and one
+// s_barrier makes every wavefront's copies visible and certifies that the stage about to be overwritten is no
+// longer read.  The copies of step s+2 are spread between the MFMAs of step s: issued in a burst they queue on
+// the compute unit's one address unit and delay every wavefront's first MFMA.
+//
+// The MFMAs and the weight conversion are inline assembly.  MFMAs: with the accumulator tied to the destination
+// (left to the compiler, accumulators migrate between registers from one K step to the next, and spill once
+// they need more than the 256 AGPRs).  Conversion: so that it sits exactly between the MFMAs whose shadow hides
+// it -- the first four row blocks run column fragment by column fragment, and fragment j+1 is converted, one
+// register after each MFMA, while fragment j multiplies; only fragment 0's conversion is exposed.
+// The price of inline MFMAs: the compiler does not know the accumulators are matrix-core results and may copy
+// or spill one right behind the MFMA, which the hardware does not interlock.  Every basic block of the K loop
+// therefore ends with explicit wait states, the epilogue pins its accumulator reads behind a final wait, and the
+// build reads the generated assembly and fails on any access that comes too early (mfma_hazards.py).
+//
+// K may be split over blockIdx.z in units of BK; slice z is stored plainly to c_parts[z] and the kernel that
+// reads the result next adds the slices in order (no atomics, fixed summation order).
+#pragma once
+#include "common.h"
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+// Asynchronous 16-byte-per-lane copy global -> LDS; m0 carries the wavefront-uniform LDS address, lane i lands
+// at that address + 16 i.  (Through the compiler builtin every later LDS read is preceded by a wait for ALL
+// copies in flight, which would serialise the pipeline.)
+__device__ __forceinline__ void glds16_at(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
+// Element offset of 16-byte chunk `chunk` of tile row `row` (rows of 4 chunks).  A fragment read (lane = row
+// l % 16, chunk l / 16) is served 16 lanes per cycle over the 64 banks: the chunk position varies with the
+// row's bits 1..2, which spreads the 16 rows of a fragment over all banks.
+__device__ __forceinline__ int swz16(int row, int chunk) { return (row * 4 + (chunk ^ ((row >> 1) & 3))) * 8; }
+
+template <int MT, int NF, int EPI>
+__global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
+  constexpr int BM = 16 * MT, BN = 64 * NF, BK = 32;
+  static_assert(NF == 2 || NF == 4, "SwiGLU pairs the fragments (gate, up): NF must be even");
+  static_assert(MT >= 1 && MT <= 17, "accumulators: 4 NF MT registers per lane, stages: 3 (2 BM + BN) x 64 B of LDS");
+  constexpr int A_INS = 2 * MT;                  // copy instructions (16 tile rows each) for [A_hi | A_lo]
+  constexpr int A_IPW = (A_INS + 3) / 4;         // per wavefront; a surplus one repeats the last group
+  constexpr int W_IPW = BN / 16 / 4;
+  constexpr int IPW = A_IPW + W_IPW;
+  constexpr int R = 2 * BM + BN;
+  constexpr int PA = MT < 4 ? MT : 4;            // row blocks of the fragment-by-fragment opening phase
+  __shared__ __attribute__((aligned(16))) uint16_t st0[R * BK];
+  __shared__ __attribute__((aligned(16))) uint16_t st1[R * BK];
+  __shared__ __attribute__((aligned(16))) uint16_t st2[R * BK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so block b
+  // runs on XCD b % 8.  Within an XCD consecutive blocks walk the M tiles of one N tile: the blocks that share
+  // a weight tile run together on one L2 and the weights leave HBM once.
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / BN;
+  const int xcd = blockIdx.x & 7, within = blockIdx.x >> 3;
+  const int n_tile = (within / m_tiles) * 8 + xcd;
+  if (n_tile >= n_tiles) return;
+  const int m0 = (within % m_tiles) * BM, n0 = n_tile * BN;
+  const int K = g.K, M = g.M;
+  const int total_steps = K / BK;
+  const int step_begin = (int)((long)blockIdx.z * total_steps / g.split_k);
+  const int n_steps = (int)((long)(blockIdx.z + 1) * total_steps / g.split_k) - step_begin;
+  if (n_steps <= 0) return;
+
+  const uint16_t* src[IPW];
+  uint32_t dst[IPW];                             // byte offset of the copy's 16 rows inside a stage
+#pragma unroll
+  for (int j = 0; j < IPW; ++j) {
+    int grp;                                     // 16-row group of the stage
+    if (j < A_IPW) {
+      grp = wave + 4 * j;
+      grp = grp < A_INS ? grp : A_INS - 1;       // same bytes to the same place: harmless
+    } else {
+      grp = A_INS + wave * W_IPW + (j - A_IPW);
+    }
+    const int r = grp * 16 + lane / 4;
+    const int ch = (lane % 4) ^ ((r >> 1) & 3);
+    const uint16_t* base;
+    if (r < 2 * BM) {
+      int am = m0 + (r < BM ? r : r - BM);
+      am = am < M ? am : M - 1;                  // rows past M are copied (clamped) and never stored
+      base = (r < BM ? g.a : g.a_lo) + (size_t)am * K;
+    } else {
+      const int col = r - 2 * BM;
+      int wrow;
+      const bf16_t* wbase;
+      if (EPI == GEMM_SWIGLU) {                  // 16-column groups alternate gate, up
+        wrow = (n0 >> 1) + ((col >> 5) << 4) + (col & 15);
+        wbase = ((col >> 4) & 1) ? g.w[1] : g.w[0];
+      } else {
+        wrow = n0 + col;
+        wbase = g.w[0];
+        if (wrow >= g.w_rows[0]) {
+          wrow -= g.w_rows[0];
+          wbase = g.w[1];
+          if (wrow >= g.w_rows[1]) {
+            wrow -= g.w_rows[1];
+            wbase = g.w[2];
+          }
+        }
+      }
+      base = wbase + (size_t)wrow * K;
+    }
+    src[j] = base + (size_t)step_begin * BK + ch * 8;
+    dst[j] = grp * 16 * BK * 2;
+  }
+
+  f32x4 acc[MT][NF];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NF; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int l16 = lane & 15, kc = lane >> 4;
+  const int a_off = swz16(l16, kc);                               // + i * 16 rows; + BM rows: lo
+  const int w_off = 2 * BM * BK + swz16(wave * 16 * NF + l16, kc);   // + j * 16 rows
+  // bf16 pair -> fp16 pair: exponent raised on both halves at once, each half widened to fp32 (a shift, a mask),
+  // and the two packed again (exact: 8 mantissa bits into 11).  A zero becomes 2^(SY_W_SHIFT - 127) in fp32 and
+  // goes back to zero in the packing.
+  const uint32_t exp_add = ((uint32_t)SY_W_SHIFT << 7) * 0x00010001u, hi_mask = 0xFFFF0000u;
+#define SY_COPY(J_, NXT, STEP) glds16_at(src[J_] + (size_t)(STEP) * BK, NXT + dst[J_]);
+#define SY_ISSUE(NXT, STEP) _Pragma("unroll") for (int j = 0; j < IPW; ++j) SY_COPY(j, NXT, STEP)
+#define SY_MFMA(ACC, FW, FA, I_)                                                                  \
+  {                                                                                               \
+    if (((I_) + 1) * NF * 4 <= 256) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(ACC) : "v"(FW), "v"(FA)); \
+    else asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(ACC) : "v"(FW), "v"(FA));   \
+  }
+#define SY_CVT1(FW, Q_)                                                                           \
+  {                                                                                               \
+    uint32_t x_ = (FW)[Q_], ta_, tb_;                                                             \
+    asm volatile("v_add_u32 %0, %3, %0\n\tv_lshlrev_b32 %1, 16, %0\n\tv_and_b32 %2, %4, %0\n\t"   \
+                 "v_cvt_pkrtz_f16_f32 %0, %1, %2"                                                 \
+                 : "+v"(x_), "=&v"(ta_), "=&v"(tb_) : "s"(exp_add), "s"(hi_mask));                \
+    (FW)[Q_] = x_;                                                                                \
+  }
+// One K step.  Opening phase: row blocks 0..PA-1, one column fragment after the other, while the next fragment's
+// weights are converted; then the remaining row blocks, each through all fragments.
+#define SY_MULT(STAGE, NXT, NSTEP)                                                                \
+  {                                                                                               \
+    u32x4 fw[NF];                                                                                 \
+    _Pragma("unroll") for (int j = 0; j < NF; ++j)                                                \
+        fw[j] = *reinterpret_cast<const u32x4*>(STAGE + w_off + j * 16 * BK);                     \
+    u32x4 fa[MT + 2], fl[MT + 2];                                                                 \
+    _Pragma("unroll") for (int i = 0; i < PA + 2 && i < MT; ++i) {                                \
+      fa[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + i * 16 * BK);                       \
+      fl[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + i * 16) * BK);                \
+    }                                                                                             \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) SY_CVT1(fw[0], q)                               \
+    asm volatile("s_nop 1" ::: "memory");                                                         \
+    _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                              \
+      _Pragma("unroll") for (int i = 0; i < PA; ++i) {                                            \
+        SY_MFMA(acc[i][j], fw[j], fa[i], i)                                                       \
+        if (j + 1 < NF) {                                                                         \
+          if (PA == 4) { SY_CVT1(fw[j + 1], i) }                                                  \
+          else if (i == PA - 1) { _Pragma("unroll") for (int q = 0; q < 4; ++q) SY_CVT1(fw[j + 1], q) } \
+        }                                                                                         \
+      }                                                                                           \
+      if (j < IPW) SY_COPY(j, NXT, NSTEP)                                                         \
+      _Pragma("unroll") for (int i = 0; i < PA; ++i) SY_MFMA(acc[i][j], fw[j], fl[i], i)          \
+    }                                                                                             \
+    _Pragma("unroll") for (int i = PA; i < MT; ++i) {                                             \
+      if (i + 2 < MT) {                                                                           \
+        fa[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (i + 2) * 16 * BK);           \
+        fl[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + (i + 2) * 16) * BK);    \
+      }                                                                                           \
+      if (NF + i - PA < IPW) SY_COPY(NF + i - PA, NXT, NSTEP)                                     \
+      _Pragma("unroll") for (int j = 0; j < NF; ++j) SY_MFMA(acc[i][j], fw[j], fa[i], i)          \
+      _Pragma("unroll") for (int j = 0; j < NF; ++j) SY_MFMA(acc[i][j], fw[j], fl[i], i)          \
+    }                                                                                             \
+    _Pragma("unroll") for (int j = (MT > PA ? NF + MT - PA : NF); j < IPW; ++j) SY_COPY(j, NXT, NSTEP) \
+  }
+// CUR holds step s; NXT (the stage read in step s-1) receives step s+2.  Past the end the last step is copied
+// again (never read): exactly one younger copy group is then always in flight, so the wait count is a constant
+// and no branch surrounds the copies.
+#define SY_STEP(CUR, NXT, S_, SETTLE)                                                             \
+  {                                                                                               \
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(IPW) : "memory");                         \
+    asm volatile("s_barrier" ::: "memory");                                                       \
+    const int nxt_ = (S_) + 2 < n_steps ? (S_) + 2 : n_steps - 1;                                 \
+    SY_MULT(CUR, NXT, nxt_)                                                                       \
+    if (SETTLE) asm volatile("s_nop 15" ::: "memory");                                            \
+  }
+
+  const uint32_t l0 = lds_addr_of(st0), l1 = lds_addr_of(st1), l2 = lds_addr_of(st2);
+  SY_ISSUE(l0, 0)
+  {
+    const int one_ = n_steps > 1 ? 1 : 0;
+    SY_ISSUE(l1, one_)
+  }
+  int s = 0;
+  // SETTLE: the last step of every basic block ends with wait states that let its final MFMAs finish.  The
+  // compiler does not know that the accumulators are MFMA results and is free to copy one to another register
+  // where control flow joins -- at the loop's back edge and exits -- where it would read a result the matrix
+  // core has not written yet.
+  for (; s + 3 <= n_steps; s += 3) {
+    SY_STEP(st0, l2, s, false)
+    SY_STEP(st1, l0, s + 1, false)
+    SY_STEP(st2, l1, s + 2, true)
+  }
+  if (s < n_steps) {
+    SY_STEP(st0, l2, s, true)
+    if (s + 1 < n_steps) SY_STEP(st1, l0, s + 1, true)
+  }
+#undef SY_COPY
+#undef SY_ISSUE
+#undef SY_MFMA
+#undef SY_CVT1
+#undef SY_MULT
+#undef SY_STEP
+  // The surplus copies of the last steps are still in flight: let them land before the block's LDS is released;
+  // MFMA results settle before they are read.  The empty statements "rewrite" each accumulator: every later read
+  // of one depends on them, and they stay behind the wait, so the compiler cannot hoist an accumulator read over it.
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int j = 0; j < NF; ++j) {
+      if ((i + 1) * NF * 4 <= 256) asm volatile("" : "+a"(acc[i][j]));
+      else asm volatile("" : "+v"(acc[i][j]));
+    }
+
+  const int nq = kc * 4;                         // this lane's 4 consecutive columns inside a 16-column fragment
+  const float os = g.out_scale;
+#pragma unroll
+  for (int i = 0; i < MT; ++i) {
+    const int m = m0 + i * 16 + l16;
+    if (m >= M) continue;
+    if (EPI == GEMM_SWIGLU) {
+#pragma unroll
+      for (int j = 0; j < NF; j += 2) {
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float gate = acc[i][j][r] * os, up = acc[i][j + 1][r] * os;
+          v[r] = gate / (1.0f + __expf(-gate)) * up * g.c_scale;
+        }
+        uint32_t h0, l0_, h1, l1_;
+        split_f16x2(v[0], v[1], h0, l0_);
+        split_f16x2(v[2], v[3], h1, l1_);
+        const size_t at = (size_t)m * (g.N >> 1) + (n0 >> 1) + (wave * (NF / 2) + (j >> 1)) * 16 + nq;
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c) + at) = make_uint2(h0, h1);
+        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c_lo) + at) = make_uint2(l0_, l1_);
+      }
+    } else {
+      float* c = (g.split_k > 1 ? g.c_parts + (size_t)blockIdx.z * M * g.N : reinterpret_cast<float*>(g.c)) +
+                 (size_t)m * g.N + n0 + wave * 16 * NF + nq;
+#pragma unroll
+      for (int j = 0; j < NF; ++j) {
+        float4 o = make_float4(acc[i][j][0] * os, acc[i][j][1] * os, acc[i][j][2] * os, acc[i][j][3] * os);
+        if (EPI == GEMM_ADD_F32 && g.split_k == 1) {
+          const float4 old = *reinterpret_cast<float4*>(c + j * 16);
+          o.x += old.x;
+          o.y += old.y;
+          o.z += old.z;
+          o.w += old.w;
+        }
+        *reinterpret_cast<float4*>(c + j * 16) = o;
+      }
+    }
+  }
+}
+
+template <int MT, int NF>
+static hipError_t launch_proj(const GemmArgs& g, hipStream_t s) {
+  constexpr int BM = 16 * MT;
+  const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / (64 * NF);
+  const dim3 grid(8 * ((n_tiles + 7) / 8) * m_tiles, 1, g.split_k);
+  switch (g.epilogue) {
+    case GEMM_STORE_F32: proj_kernel<MT, NF, GEMM_STORE_F32><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_ADD_F32: proj_kernel<MT, NF, GEMM_ADD_F32><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_SWIGLU: proj_kernel<MT, NF, GEMM_SWIGLU><<<grid, 256, 0, s>>>(g); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}

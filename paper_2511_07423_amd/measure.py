@@ -59,16 +59,15 @@ def gemm():
     for M in [int(v) for v in sys.argv[2:]] or [532, 1152, 2048]:
         for name, N, K in shapes:
             x = torch.randn((M, K), generator=torch.Generator(device="cuda:0").manual_seed(7), device="cuda:0")
-            a = x.to(torch.bfloat16)
-            al = (x - a.float()).to(torch.bfloat16)
+            a, al = synera.split_pair(x)
             if name not in ws:                                 # three copies, rotated: no cache reuse
                 ws[name] = [wl.draw_normal_bf16((N, K), 0.02, 100 + i, "cuda:0") for i in range(3)]
             w3 = ws[name]
             c = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
             it = iter(range(10 ** 9))
-            ms = _time(lambda: synera.gemm_bf16(a, w3[next(it) % 3], a_lo=al, out=c), n=18)
+            ms = _time(lambda: synera.gemm_pair(a, al, w3[next(it) % 3], out=c), n=18)
             fl = 2.0 * M * N * K
-            print(json.dumps({"kernel": "synera_gemm_bf16", "shape": name, "M": M, "N": N, "K": K, "avg_launch_ms": ms,
+            print(json.dumps({"kernel": "synera_gemm_pair", "shape": name, "M": M, "N": N, "K": K, "avg_launch_ms": ms,
                               "bound": "mfma", "achieved_TFLOPs": fl / ms / 1e9, "executed_TFLOPs": 2 * fl / ms / 1e9,
                               "peak_TFLOPs": 2500.0, "frac": fl / ms / 1e9 / 2500.0}))
 

@@ -10,7 +10,10 @@ wait states; this module reads the generated assembly and verifies that the resu
 
   after an MFMA that writes registers D, no instruction other than an MFMA that accumulates onto exactly D
   may name a register of D until `passes + 3` wait states have gone by (one per instruction, N + 1 for
-  `s_nop N`), `passes` being 4 for the 16x16x32 and 8 for the 32x32x16 bf16 instruction.
+  `s_nop N`), `passes` being 4 for the 16x16x32 and 8 for the 32x32x16 instructions;
+
+  an MFMA may not read, as its first or second operand, a register that a vector-ALU instruction (the weight
+  conversion, also inline assembly) wrote fewer than 2 wait states earlier.
 
 Control flow is followed one level: at a branch, the instructions at the target are checked against the
 MFMAs still settling at the branch.
@@ -18,7 +21,8 @@ MFMAs still settling at the branch.
 import re
 import sys
 
-_PASSES = {"v_mfma_f32_16x16x32_bf16": 4, "v_mfma_f32_32x32x16_bf16": 8}
+_PASSES = {"v_mfma_f32_16x16x32_bf16": 4, "v_mfma_f32_32x32x16_bf16": 8, "v_mfma_f32_16x16x32_f16": 4}
+_VALU_TO_MFMA_SRC = 2     # wait states between a vector-ALU write and an MFMA reading it as a source
 _REG = re.compile(r"\b([av])(?:\[(\d+):(\d+)\]|(\d+))")
 
 
@@ -84,9 +88,20 @@ def check_kernel(name, lines):
     """Hazard messages for one kernel's assembly (list of lines; reported line numbers count from its label)."""
     ins, labels = _parse(lines)
     report, pending = [], []
+    fresh = []                                    # (registers a vector-ALU instruction just wrote, states left, line)
     for entry in ins:
         mn, ops, no = entry
         _touch(entry, pending, report, name)
+        if mn in _PASSES:
+            fields = [f.strip() for f in ops.split(",")]
+            srcs = _regs(fields[1]) | _regs(fields[2])
+            for regs, left, at in fresh:
+                if regs & srcs:
+                    report.append(f"{name}: line {no}: {mn} {ops} reads a source written by the vector instruction "
+                                  f"at line {at} with {left} wait states to go")
+        fresh = _age(fresh, entry)
+        if mn.startswith("v_") and mn not in _PASSES and not mn.startswith("v_cmp"):
+            fresh.append((_regs(ops.split(",")[0]), _VALU_TO_MFMA_SRC, no))
         if mn.startswith(("s_cbranch", "s_branch")) and ops.strip() in labels and pending:
             ahead = list(pending)                 # the same MFMAs, seen from the branch target
             for target in ins[labels[ops.strip()]:]:
@@ -100,7 +115,7 @@ def check_kernel(name, lines):
     return report
 
 
-def check_file(path, name_filter="gemm_tall"):
+def check_file(path, name_filter="proj_kernel"):
     """Check every kernel of the assembly file whose symbol contains `name_filter` (a string or several).
     -> (number of kernels checked, number of inline MFMAs seen, hazard messages)"""
     with open(path) as f:

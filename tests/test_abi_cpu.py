@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(synera.lib_path())
     names = _declared_symbols()
     assert {"synera_verify", "synera_confidence", "synera_kv_append", "synera_create", "synera_destroy",
-            "synera_validate_batch", "synera_gemm_bf16", "synera_version", "synera_strerror",
+            "synera_validate_batch", "synera_gemm_pair", "synera_version", "synera_strerror",
             "synera_sched_create", "synera_sched_next", "synera_sched_commit"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None, n

@@ -25,6 +25,16 @@ def test_small_batches_take_the_narrow_tiles():
         assert synera.debug_gemm_plan(144, n, k, e)[1] == 128
 
 
+def test_decode_sized_batches_use_tiles_of_their_own_height_and_never_atomics():
+    """Below 128 rows the tile is as tall as the batch (one M tile); K may only be split into stored slices,
+    and without a slice buffer (the stand-alone mode) it is not split at all: no path adds with atomics."""
+    for M in (1, 8, 16, 17, 64, 96):
+        for n, k, e in ((QKV, D, STORE), (D, D, ADD), (2 * F, D, SWIGLU), (D, F, ADD), (VOCAB, D, STORE)):
+            bm, bn, split = synera.debug_gemm_plan(M, n, k, e)
+            assert bm == (M + 15) // 16 * 16
+            assert synera.debug_gemm_plan(M, n, k, e, stored_slices=False)[2] == 1
+
+
 @pytest.mark.parametrize("stored", [True, False])
 @pytest.mark.parametrize("M", [1, 17, 96, 97, 130, 200, 333, 532, 777, 1030, 2048])
 @pytest.mark.parametrize("N,K,epi", [(QKV, D, STORE), (D, D, ADD), (2 * F, D, SWIGLU), (D, F, ADD), (VOCAB, D, STORE),
@@ -35,8 +45,9 @@ def test_plans_are_launchable(M, N, K, epi, stored):
     assert 1 <= split <= K // 32
     if epi == SWIGLU:
         assert split == 1
-    if stored and bm >= 128:                    # tall tiles store their K slices: SYNERA_MAX_GEMM_SLICES
-        assert split <= 8
+    assert split <= 8                           # SYNERA_MAX_GEMM_SLICES
+    if not stored:
+        assert split == 1
 
 
 def test_plan_rejects_bad_shapes():

@@ -139,51 +139,70 @@ def test_kv_append_is_bit_exact_and_touches_nothing_else():
                                    (544, 1024, 14336), (257, 32000, 256)])
 def test_gemm_matches_float64(M, N, K):
     synera = _synera()
-    a = wl.draw_normal_bf16((M, K), 1.0, 11 * M + K, DEV)
+    x = wl.draw_normal_bf16((M, K), 1.0, 11 * M + K, DEV).float() * 1.37
+    a, al = synera.split_pair(x)
     w = wl.draw_normal_bf16((N, K), 0.02, 13 * N + K, DEV)
-    c = synera.gemm_bf16(a, w)
+    c = synera.gemm_pair(a, al, w)
     torch.cuda.synchronize()
     rows = np.unique(np.concatenate([[0, M - 1], np.random.default_rng(M).integers(0, M, 6)]))
-    want = a[rows].double().cpu() @ w.double().cpu().T
+    want = (a[rows].double() + al[rows].double()).cpu() @ w.double().cpu().T
     got = c[rows].double().cpu()
     scale = 0.02 * math.sqrt(K)
     assert torch.isfinite(c).all()
-    assert (got - want).abs().max().item() < 2e-5 * scale * math.sqrt(K) + 1e-6
+    assert (got - want).abs().max().item() < 6e-9 * K + 2e-7
     # full comparison against the fp32 library product on the device (looser: its own rounding)
-    ref = a.float() @ w.float().T
+    ref = x @ w.float().T
     assert (c - ref).abs().max().item() < 1e-3 * scale + 1e-5
 
 
-def _split_pair(x):
-    hi = x.to(torch.bfloat16)
-    return hi, (x - hi.float()).to(torch.bfloat16)
+def test_pair_carries_22_bits_and_weights_of_any_magnitude_below_256_are_exact():
+    """The fp16 pair must reproduce an fp32 activation to 2^-22 (elements far below the row's scale included: their
+    low parts are subnormal in fp16), and the weight's path bf16 -> fp16 with a raised exponent must be exact
+    from 2^-22 up to 255."""
+    synera = _synera()
+    M, N, K = 48, 256, 512
+    g = torch.Generator(device=DEV).manual_seed(5)
+    x = torch.randn((M, K), generator=g, device=DEV) * torch.exp2(torch.randint(-12, 6, (M, K), generator=g, device=DEV).float())
+    a, al = synera.split_pair(x)
+    assert ((a.double() + al.double()) - x.double()).abs().max().item() <= 2.0 ** -22 * x.abs().max().item()
+    mag = torch.exp2(torch.randint(-21, 8, (N, K), generator=g, device=DEV).float())
+    w = (mag * (1 + torch.rand((N, K), generator=g, device=DEV) * 0.99) * (torch.randint(0, 2, (N, K), generator=g, device=DEV) * 2 - 1)).to(torch.bfloat16)
+    w[0, :] = 0
+    w[1, 0] = 255.0
+    c = synera.gemm_pair(a, al, w)
+    torch.cuda.synchronize()
+    xd, wd = a.double() + al.double(), w.double()
+    want = xd @ wd.T
+    bound = 2e-6 * (xd.abs() @ wd.abs().T) + 1e-30       # fp32 accumulation of K terms; nothing of order 2^-8 (a bf16 step)
+    assert ((c.double() - want).abs() <= bound).all()
+    assert (c[:, 0] == 0).all()
 
 
-# tile configurations: 11, 13, 14 = 128x128 / 128x256 / 64x256 asynchronous-copy kernels, 18..23 = tall tiles of 128..288 rows (32-row blocks), 24..28 = 144..272 rows and 29..33 = 128..256 rows (16-row blocks), 34..38 = 128..192 rows x 128 columns
-@pytest.mark.parametrize("variant", [-1, 11, 13, 14] + list(range(18, 39)))
+# tiles: rows / 16 (1..17) with 256 columns, 100 + rows / 16 (1..12) with 128 columns; -1 = the planner's choice
+@pytest.mark.parametrize("tile", [-1] + list(range(1, 18)) + list(range(101, 113)))
 @pytest.mark.parametrize("M,N,K", [(1, 256, 64), (97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (600, 4096, 1792),
                                    (532, 1792, 1024), (97, 1792, 320), (545, 1792, 512)])
-def test_gemm_pair_activations_every_tile_and_epilogue(variant, M, N, K):
-    """(hi, lo) activations through each tile configuration: store (K split included), residual add,
-    SwiGLU; compared with the float64 product of the same bf16 operands."""
+def test_gemm_every_tile_and_epilogue(tile, M, N, K):
+    """(hi, lo) activations through each tile configuration: store, residual add, SwiGLU; compared with the
+    float64 product of the same operands."""
     synera = _synera()
     g = torch.Generator(device=DEV).manual_seed(1000 * M + N + K)
     x = torch.randn((M, K), generator=g, device=DEV)
-    a, al = _split_pair(x)
+    a, al = synera.split_pair(x)
     w = wl.draw_normal_bf16((N, K), 0.02, 17 * N + K, DEV)
     xd = a.double() + al.double()
     want = xd @ w.double().T
     # fp32 accumulation of 2K products of size ~0.02: measured ~1.7e-9 K; one missing term of the lo half of
-    # one K step (an accumulator read before its last MFMA landed) is ~1e-4 and must not pass
+    # one K step (an accumulator read before its last MFMA landed) is ~1e-5 and must not pass
     tol = 6e-9 * K + 2e-7
-    synera.debug_set_gemm_tile(variant)
+    synera.debug_set_gemm_tile(tile)
     try:
-        c = synera.gemm_bf16(a, w, a_lo=al)
+        c = synera.gemm_pair(a, al, w)
         base = torch.randn((M, N), generator=g, device=DEV)
         c_add = base.clone()
         synera.debug_gemm_epilogue(a, al, w, None, c_add, None, 1)
         half = N // 2
-        act_hi = torch.empty((M, half), dtype=torch.bfloat16, device=DEV)
+        act_hi = torch.empty((M, half), dtype=torch.float16, device=DEV)
         act_lo = torch.empty_like(act_hi)
         synera.debug_gemm_epilogue(a, al, w[:half].contiguous(), w[half:].contiguous(), act_hi, act_lo, 2)
         torch.cuda.synchronize()
@@ -193,39 +212,44 @@ def test_gemm_pair_activations_every_tile_and_epilogue(variant, M, N, K):
     assert (c_add.double() - (base.double() + want)).abs().max().item() < tol + 1e-6
     gate, up = want[:, :half], want[:, half:]
     glu = gate / (1 + torch.exp(-gate)) * up
-    got = act_hi.double() + act_lo.double()
-    # elementwise: d(silu(g) u) <= 1.1 |u| dg + |g| du, fast-exp error, and the bf16 pair's 2^-17 relative rounding
-    bound = tol * (1.1 * up.abs() + gate.abs()) + (2.0 ** -17 + 2e-6) * glu.abs() + 1e-7
+    got = (act_hi.double() + act_lo.double()) / 8.0
+    # elementwise: d(silu(g) u) <= 1.1 |u| dg + |g| du, fast-exp error, and the fp16 pair's 2^-22 relative rounding
+    # (its low part goes subnormal for tiny products: 2^-25 / 8 absolute)
+    bound = tol * (1.1 * up.abs() + gate.abs()) + (2.0 ** -21 + 2e-6) * glu.abs() + 1e-8
     assert ((got - glu).abs() - bound).max().item() < 0
 
 
-@pytest.mark.parametrize("variant", [-1, 18, 21, 23] + list(range(24, 39)))
-@pytest.mark.parametrize("M,N,K", [(97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (545, 4096, 1792), (532, 1792, 2048)])
-def test_gemm_stored_k_slices_sum_to_the_product(variant, M, N, K):
-    """K split into stored slices (the mode the decoder layers use on tall tiles): the slices, added in
-    order, give the product; a planner that does not split returns it whole."""
+@pytest.mark.parametrize("tile", [-1, 4, 8, 9, 13, 17, 104, 108, 112])
+@pytest.mark.parametrize("M,N,K", [(97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (545, 4096, 1792), (532, 1792, 2048),
+                                   (24, 1792, 4096)])
+def test_gemm_stored_k_slices_sum_to_the_product(tile, M, N, K):
+    """K split into stored slices (the mode the decoder layers use): the slices, added in order, give the
+    product; a planner that does not split returns it whole.  The slices are stored, never accumulated, so two
+    runs agree bit for bit."""
     synera = _synera()
     g = torch.Generator(device=DEV).manual_seed(7 * M + N + K)
     x = torch.randn((M, K), generator=g, device=DEV)
-    a, al = _split_pair(x)
+    a, al = synera.split_pair(x)
     w = wl.draw_normal_bf16((N, K), 0.02, 13 * N + K, DEV)
     want = (a.double() + al.double()) @ w.double().T
-    synera.debug_set_gemm_tile(variant)
+    synera.debug_set_gemm_tile(tile)
     try:
-        parts = synera.debug_gemm_deferred(a, al, w)
+        parts = synera.debug_gemm_slices(a, al, w).clone()
+        again = synera.debug_gemm_slices(a, al, w)
         torch.cuda.synchronize()
     finally:
         synera.debug_set_gemm_tile(-1)
     assert 1 <= parts.shape[0] <= 8
-    if 18 <= variant < 34 and K >= 1024:
-        assert parts.shape[0] > 1          # few tiles, at least 32 K steps: every tall tile splits here
+    if tile > 0 and K >= 1024 and (M + 16 * (tile % 100) - 1) // (16 * (tile % 100)) * (N // (128 if tile > 100 else 256)) <= 128:
+        assert parts.shape[0] > 1          # few tiles, at least 32 K steps: a forced tile splits here
+    assert torch.equal(parts, again)
     assert (parts.double().sum(0) - want).abs().max().item() < 6e-9 * K + 2e-7
 
 
 def test_gemm_rejects_unsupported_shapes():
     synera = _synera()
-    a = torch.zeros((4, 96), dtype=torch.bfloat16, device=DEV)
+    a = torch.zeros((4, 96), dtype=torch.float16, device=DEV)
     w = torch.zeros((128, 96), dtype=torch.bfloat16, device=DEV)
     with pytest.raises(synera.SyneraError) as e:
-        synera.gemm_bf16(a, w)
+        synera.gemm_pair(a, a, w)
     assert e.value.status == synera.EUNSUP
