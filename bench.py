@@ -138,6 +138,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-stage times to stderr")
     ap.add_argument("--stage", default="gate_up", help="kernel stage the roofline object reports")
+    ap.add_argument("--gemm-tile", type=int, default=-1,
+                    help="tuning: force one projection tile for the timed steps (rows/16, +100 for 128 columns)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain 1 GiB device copy (a known-size dispatch to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters by)")
@@ -173,6 +175,7 @@ def main():
     def step():
         ver.verify_into(ctx, zeros, nd, w["tokens"], w["anchor"], bt, b["n_pages"], w["k_pool"], w["v_pool"], out)
 
+    synera.debug_set_gemm_tile(args.gemm_tile)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -8,6 +8,8 @@
 // associatively, first inside a wavefront by lane shuffles, then across the four
 // wavefronts of the block through LDS.  At the end p_top1 = 1/Z and
 // H = ln Z - S/Z.  HBM-bound: rows*vocab*sizeof(elem) bytes are read exactly once.
+// Entries of -inf (tokens masked out by a top-k / top-p filter, Section 4.5) carry probability 0 and add
+// nothing to the entropy; a row needs at least one finite entry.
 #include "common.h"
 
 #define LOG2E 1.4426950408889634f
@@ -50,7 +52,8 @@ __device__ __forceinline__ void conf_chunk(ConfState& st, const float (&v)[N], i
   }
 #pragma unroll
   for (int i = 0; i < N; ++i) {
-    const float t = v[i] - st.m;
+    // bounded below: a masked logit (-inf) has weight e = 0 and must add 0 to S, not 0 * -inf
+    const float t = fmaxf(v[i] - st.m, -1e30f);
     const float e = fast_exp2(t * LOG2E);
     st.Z += e;
     st.S = fmaf(e, t, st.S);

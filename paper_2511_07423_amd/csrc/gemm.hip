@@ -19,12 +19,12 @@ static bool tile_fits(const GemmArgs& g, int mt, int nf) {
   return true;
 }
 
-// Modelled time of one K step (32 of K) of one block, us.  Fits of MI355X timings at M = 200..1030 on 256-column
-// tiles: 0.12 us plus 0.0825 us per 16-row block; a 128-column tile pays the activation-fragment reads of a
-// 256-column one for half the MFMAs: 0.6x, not 0.5x.  A short tile is bound by its weight stream instead: BN rows
-// x 64 bytes per K step at the ~24 GB/s one compute unit pulls from HBM.
+// Modelled time of one K step (32 of K) of one block, us.  Fit of MI355X timings of the 8B gate/up projection at
+// M = 532 on 256-column tiles of 128, 144 and 272 rows: 0.17 us plus 0.086 us per 16-row block; a 128-column tile
+// pays the activation-fragment reads of a 256-column one for half the MFMAs: 0.6x, not 0.5x.  A short tile is
+// bound by its weight stream instead: BN rows x 64 bytes per K step at the ~24 GB/s one compute unit pulls from HBM.
 static double step_us(int mt, int nf) {
-  const double mfma = 0.12 + 0.0825 * mt * (nf == 4 ? 1.0 : 0.6);
+  const double mfma = 0.17 + 0.086 * mt * (nf == 4 ? 1.0 : 0.6);
   const double stream = 64 * nf * 64 / 24e3;
   return mfma > stream ? mfma : stream;
 }
@@ -38,12 +38,13 @@ static int max_split(const GemmArgs& g, int mt, int nf) {
   return split < 1 ? 1 : (int)split;
 }
 // Blocks are equal-sized and one runs per compute unit, so a launch takes ceil(blocks / 256) rounds of
-// K steps per block x step_us, plus per stored K slice and 2.2 M outputs ~3 us to store it and read it back.
+// K steps per block x step_us, plus per stored K slice and 2.2 M outputs ~2.4 us to store it and read it back
+// (QKV and down projection at M = 532 on 272-row tiles with 5 and 8 slices: 18 - 19 us beyond their K steps).
 static double plan_cost(const GemmArgs& g, int mt, int nf, int split) {
   const long tiles = (long)((g.M + 16 * mt - 1) / (16 * mt)) * (g.N / (64 * nf));
   const long rounds = (tiles * split + 255) / 256;
   const double steps = (double)(g.K / 32) / split;
-  const double merge = split > 1 ? 3.0 * split * ((double)g.M * g.N / 2.2e6) : 0.0;
+  const double merge = split > 1 ? 2.4 * split * ((double)g.M * g.N / 2.2e6) : 0.0;
   return rounds * steps * step_us(mt, nf) + merge;
 }
 

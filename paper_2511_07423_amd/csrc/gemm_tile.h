@@ -33,8 +33,9 @@
 // The MFMAs and the weight conversion are inline assembly.  MFMAs: with the accumulator tied to the destination
 // (left to the compiler, accumulators migrate between registers from one K step to the next, and spill once
 // they need more than the 256 AGPRs).  Conversion: so that it sits exactly between the MFMAs whose shadow hides
-// it -- the first four row blocks run column fragment by column fragment, and fragment j+1 is converted, one
-// register after each MFMA, while fragment j multiplies; only fragment 0's conversion is exposed.
+// it.  A wavefront copies the weight rows of its own columns itself, so it can read the weights of step s+1 as
+// soon as its own copies have landed, before the barrier: it does so during the last four row blocks of step
+// s and converts them, two instructions after each MFMA; step s+1 then starts with its weight fragments in registers.
 // The price of inline MFMAs: the compiler does not know the accumulators are matrix-core results and may copy
 // or spill one right behind the MFMA, which the hardware does not interlock.  Every basic block of the K loop
 // therefore ends with explicit wait states, the epilogue pins its accumulator reads behind a final wait, and the
@@ -71,7 +72,8 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
   constexpr int W_IPW = BN / 16 / 4;
   constexpr int IPW = A_IPW + W_IPW;
   constexpr int R = 2 * BM + BN;
-  constexpr int PA = MT < 4 ? MT : 4;            // row blocks of the fragment-by-fragment opening phase
+  constexpr int C_END = MT > 4 ? MT - 4 : 1;     // the copies of step s+2 go out during row blocks 0 .. C_END-1
+  constexpr int CPB = (IPW + C_END - 1) / C_END; // copies per row block
   __shared__ __attribute__((aligned(16))) uint16_t st0[R * BK];
   __shared__ __attribute__((aligned(16))) uint16_t st1[R * BK];
   __shared__ __attribute__((aligned(16))) uint16_t st2[R * BK];
@@ -162,51 +164,74 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
                  : "+v"(x_), "=&v"(ta_), "=&v"(tb_) : "s"(exp_add), "s"(hi_mask));                \
     (FW)[Q_] = x_;                                                                                \
   }
-// One K step.  Opening phase: row blocks 0..PA-1, one column fragment after the other, while the next fragment's
-// weights are converted; then the remaining row blocks, each through all fragments.
-#define SY_MULT(STAGE, NXT, NSTEP)                                                                \
+// The same conversion for the next step's fragments fwn, cut into single instructions so that two of them fit
+// behind each MFMA without holding up the next one: operation P of 16 NF = fragment P / 16, stage (P % 16) / 4
+// (raise the exponents; low half to fp32; high half to fp32, in place; pack), register P % 4.  Consecutive
+// operations touch different registers: no instruction waits for the one before it.
+#define SY_CVT_OP(P_)                                                                             \
+  if ((P_) < 16 * NF) {                                                                           \
+    uint32_t x_ = fwn[(P_) / 16][(P_) % 4];                                                       \
+    if (((P_) % 16) / 4 == 0) asm volatile("v_add_u32 %0, %1, %0" : "+v"(x_) : "s"(exp_add));     \
+    else if (((P_) % 16) / 4 == 1) asm volatile("v_lshlrev_b32 %0, 16, %1" : "=v"(tq[(P_) % 4]) : "v"(x_)); \
+    else if (((P_) % 16) / 4 == 2) asm volatile("v_and_b32 %0, %1, %0" : "+v"(x_) : "s"(hi_mask)); \
+    else asm volatile("v_cvt_pkrtz_f16_f32 %0, %1, %0" : "+v"(x_) : "v"(tq[(P_) % 4]));           \
+    fwn[(P_) / 16][(P_) % 4] = x_;                                                                \
+  }
+// A wavefront copies exactly the weight rows of its own columns, so it may read them as soon as its own copies
+// have landed, ahead of the barrier that publishes the other wavefronts' activation rows.
+#define SY_NEXT_W(NEXTSTAGE)                                                                      \
   {                                                                                               \
-    u32x4 fw[NF];                                                                                 \
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IPW) : "memory");                                    \
     _Pragma("unroll") for (int j = 0; j < NF; ++j)                                                \
-        fw[j] = *reinterpret_cast<const u32x4*>(STAGE + w_off + j * 16 * BK);                     \
-    u32x4 fa[MT + 2], fl[MT + 2];                                                                 \
-    _Pragma("unroll") for (int i = 0; i < PA + 2 && i < MT; ++i) {                                \
+        fwn[j] = *reinterpret_cast<const u32x4*>(NEXTSTAGE + w_off + j * 16 * BK);                \
+  }
+// One K step on the stage CUR with this step's weight fragments fw already converted in registers.  The copies
+// of step s+2 go out during the first row blocks; during the last four the weights of step s+1 (NEXTSTAGE) are
+// read and converted, two instructions after each MFMA, in the shadow of the matrix core.
+#define SY_MULT(STAGE, NXT, NSTEP, NEXTSTAGE)                                                     \
+  {                                                                                               \
+    u32x4 fa[MT + 2], fl[MT + 2], fwn[NF];                                                        \
+    uint32_t tq[4];                                                                               \
+    _Pragma("unroll") for (int i = 0; i < 2 && i < MT; ++i) {                                     \
       fa[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + i * 16 * BK);                       \
       fl[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + i * 16) * BK);                \
     }                                                                                             \
-    _Pragma("unroll") for (int q = 0; q < 4; ++q) SY_CVT1(fw[0], q)                               \
-    asm volatile("s_nop 1" ::: "memory");                                                         \
-    _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                              \
-      _Pragma("unroll") for (int i = 0; i < PA; ++i) {                                            \
-        SY_MFMA(acc[i][j], fw[j], fa[i], i)                                                       \
-        if (j + 1 < NF) {                                                                         \
-          if (PA == 4) { SY_CVT1(fw[j + 1], i) }                                                  \
-          else if (i == PA - 1) { _Pragma("unroll") for (int q = 0; q < 4; ++q) SY_CVT1(fw[j + 1], q) } \
-        }                                                                                         \
-      }                                                                                           \
-      if (j < IPW) SY_COPY(j, NXT, NSTEP)                                                         \
-      _Pragma("unroll") for (int i = 0; i < PA; ++i) SY_MFMA(acc[i][j], fw[j], fl[i], i)          \
-    }                                                                                             \
-    _Pragma("unroll") for (int i = PA; i < MT; ++i) {                                             \
+    _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                              \
       if (i + 2 < MT) {                                                                           \
         fa[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (i + 2) * 16 * BK);           \
         fl[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + (i + 2) * 16) * BK);    \
       }                                                                                           \
-      if (NF + i - PA < IPW) SY_COPY(NF + i - PA, NXT, NSTEP)                                     \
-      _Pragma("unroll") for (int j = 0; j < NF; ++j) SY_MFMA(acc[i][j], fw[j], fa[i], i)          \
-      _Pragma("unroll") for (int j = 0; j < NF; ++j) SY_MFMA(acc[i][j], fw[j], fl[i], i)          \
+      _Pragma("unroll") for (int c = 0; c < CPB; ++c)                                             \
+          if (i < C_END && i * CPB + c < IPW) SY_COPY(i * CPB + c, NXT, NSTEP)                    \
+      if (i == C_END) SY_NEXT_W(NEXTSTAGE)                                                        \
+      _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                            \
+        SY_MFMA(acc[i][j], fw[j], fa[i], i)                                                       \
+        if (i >= C_END) {                                                                         \
+          SY_CVT_OP(((i - C_END) * 2 * NF + j) * 2)                                               \
+          SY_CVT_OP(((i - C_END) * 2 * NF + j) * 2 + 1)                                           \
+        }                                                                                         \
+      }                                                                                           \
+      _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                            \
+        SY_MFMA(acc[i][j], fw[j], fl[i], i)                                                       \
+        if (i >= C_END) {                                                                         \
+          SY_CVT_OP(((i - C_END) * 2 * NF + NF + j) * 2)                                          \
+          SY_CVT_OP(((i - C_END) * 2 * NF + NF + j) * 2 + 1)                                      \
+        }                                                                                         \
+      }                                                                                           \
     }                                                                                             \
-    _Pragma("unroll") for (int j = (MT > PA ? NF + MT - PA : NF); j < IPW; ++j) SY_COPY(j, NXT, NSTEP) \
+    if (C_END >= MT) SY_NEXT_W(NEXTSTAGE)                                                         \
+    _Pragma("unroll") for (int p = (MT > C_END ? (MT - C_END) * 4 * NF : 0); p < 16 * NF; ++p) SY_CVT_OP(p) \
+    _Pragma("unroll") for (int j = 0; j < NF; ++j) fw[j] = fwn[j];                                \
   }
 // CUR holds step s; NXT (the stage read in step s-1) receives step s+2.  Past the end the last step is copied
-// again (never read): exactly one younger copy group is then always in flight, so the wait count is a constant
+// again (never used): exactly one younger copy group is then always in flight, so the wait count is a constant
 // and no branch surrounds the copies.
-#define SY_STEP(CUR, NXT, S_, SETTLE)                                                             \
+#define SY_STEP(CUR, NXT, S_, SETTLE, NEXTSTAGE)                                                  \
   {                                                                                               \
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(IPW) : "memory");                         \
     asm volatile("s_barrier" ::: "memory");                                                       \
     const int nxt_ = (S_) + 2 < n_steps ? (S_) + 2 : n_steps - 1;                                 \
-    SY_MULT(CUR, NXT, nxt_)                                                                       \
+    SY_MULT(CUR, NXT, nxt_, NEXTSTAGE)                                                            \
     if (SETTLE) asm volatile("s_nop 15" ::: "memory");                                            \
   }
 
@@ -216,24 +241,35 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
     const int one_ = n_steps > 1 ? 1 : 0;
     SY_ISSUE(l1, one_)
   }
+  // the first step's weights: own copies of stage 0 have landed once at most the IPW younger ones are in flight
+  u32x4 fw[NF];
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IPW) : "memory");
+#pragma unroll
+  for (int j = 0; j < NF; ++j) fw[j] = *reinterpret_cast<const u32x4*>(st0 + w_off + j * 16 * BK);
+#pragma unroll
+  for (int j = 0; j < NF; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) SY_CVT1(fw[j], q)
   int s = 0;
   // SETTLE: the last step of every basic block ends with wait states that let its final MFMAs finish.  The
   // compiler does not know that the accumulators are MFMA results and is free to copy one to another register
   // where control flow joins -- at the loop's back edge and exits -- where it would read a result the matrix
   // core has not written yet.
   for (; s + 3 <= n_steps; s += 3) {
-    SY_STEP(st0, l2, s, false)
-    SY_STEP(st1, l0, s + 1, false)
-    SY_STEP(st2, l1, s + 2, true)
+    SY_STEP(st0, l2, s, false, st1)
+    SY_STEP(st1, l0, s + 1, false, st2)
+    SY_STEP(st2, l1, s + 2, true, st0)
   }
   if (s < n_steps) {
-    SY_STEP(st0, l2, s, true)
-    if (s + 1 < n_steps) SY_STEP(st1, l0, s + 1, true)
+    SY_STEP(st0, l2, s, true, st1)
+    if (s + 1 < n_steps) SY_STEP(st1, l0, s + 1, true, st2)
   }
 #undef SY_COPY
 #undef SY_ISSUE
 #undef SY_MFMA
 #undef SY_CVT1
+#undef SY_CVT_OP
+#undef SY_NEXT_W
 #undef SY_MULT
 #undef SY_STEP
   // The surplus copies of the last steps are still in flight: let them land before the block's LDS is released;

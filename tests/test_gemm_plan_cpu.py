@@ -10,13 +10,13 @@ D, F, QKV, VOCAB = 4096, 14336, 6144, 32000
 
 
 def test_headline_batch_plans():
-    """532 draft rows: every projection on 256-column tall tiles; the two long-K / few-tile ones split K."""
+    """532 draft rows: every projection on 256-column tall tiles; the few-tile ones split K into stored slices."""
     T = 532
-    assert synera.debug_gemm_plan(T, QKV, D, STORE) == (128, 256, 2)
+    assert synera.debug_gemm_plan(T, QKV, D, STORE) == (272, 256, 5)
     assert synera.debug_gemm_plan(T, D, D, ADD) == (144, 256, 4)
     assert synera.debug_gemm_plan(T, 2 * F, D, SWIGLU) == (272, 256, 1)
-    assert synera.debug_gemm_plan(T, D, F, ADD) == (144, 256, 4)
-    assert synera.debug_gemm_plan(T, VOCAB, D, STORE) == (272, 256, 1)
+    assert synera.debug_gemm_plan(T, D, F, ADD) == (272, 256, 8)
+    assert synera.debug_gemm_plan(T, VOCAB, D, STORE, stored_slices=False) == (272, 256, 1)
 
 
 def test_small_batches_take_the_narrow_tiles():

@@ -76,6 +76,29 @@ def test_rows_without_finite_entries_report_token_zero():
     assert ids[0] == 0 and ids[2] == 0 and 0 <= ids[1] < 4096
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_masked_logits_carry_probability_zero_and_finite_entropy(dtype):
+    """Rows filtered by top-k / top-p masking hold -inf almost everywhere: most threads of the block see nothing but
+    -inf, others a mix; probability and entropy must be those of the finite entries alone."""
+    synera = _synera()
+    g = torch.Generator(device=DEV).manual_seed(17)
+    x = (torch.randn((6, 32000), generator=g, device=DEV) * 3).to(dtype)
+    keep = [torch.tensor([5]), torch.tensor([31999, 0]), torch.arange(100, 140), torch.randint(0, 32000, (50,), generator=g, device=DEV).cpu(),
+            torch.arange(0, 32000, 7), torch.arange(31990, 32000)]
+    for r, idx in enumerate(keep):
+        m = torch.full((32000,), float("-inf"), device=DEV, dtype=dtype)
+        m[idx.to(DEV)] = x[r, idx.to(DEV)]
+        x[r] = m
+    _check_conf(x, "masked rows")
+    ids, p, H = synera.confidence(x)
+    assert p[0].item() == 1.0 and H[0].item() == 0.0
+    tk_id, tk_p, margin, Hk = synera.confidence_topk(x, 4)
+    torch.cuda.synchronize()
+    assert torch.isfinite(Hk).all() and torch.allclose(Hk, H, rtol=1e-5, atol=1e-6)
+    assert tk_id[1].cpu().tolist()[:2] == sorted([0, 31999], key=lambda i: (-float(x[1, i]), i))
+    assert tk_p[0].cpu().tolist() == [1.0, 0.0, 0.0, 0.0]
+
+
 def test_confidence_rejects_bad_arguments():
     synera = _synera()
     x = torch.zeros((4, 1001), device=DEV, dtype=torch.bfloat16)   # row stride not 16-byte aligned
