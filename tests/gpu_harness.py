@@ -107,9 +107,9 @@ def draw_weights(shape, seed, device, oracle_dtype=None, lazy_oracle=False):
     configs with one model shape may share the result.  lazy_oracle: the oracle widens one layer at a
     time from the device copy (for models whose fp32 copy does not fit in host memory)."""
     if oracle_dtype is None:
-        # float64: at the 70B shape a float32 run of the oracle strays from its own float64 run by up to
-        # 3e-2 in single logits (bf16 KV-cache rounding decisions flip and peaked attention amplifies
-        # them), which is beyond the parity tolerance; the float64 run is the reference.
+        # float64, the exact arithmetic of the definition: a float32 run of the oracle is no arbiter for a deep
+        # decoder (bf16 KV-cache rounding decisions flip and attention carries them on; measured at the 70B
+        # shape, float32 run vs float64 run: 3e-2 at 8 layers, 4e-3 to 1e-1 at 80 layers depending on the requests)
         oracle_dtype = np.float64
     head = wl.draw_head_weights(shape, seed, device)
     layers = [wl.draw_layer_weights(shape, seed, l, device) for l in range(shape.n_layers)]

@@ -123,7 +123,7 @@ def test_config4_70b_all_80_layers():
     flip from layer to layer)."""
     rec = wl.config(4)
     weights = gh.draw_weights(rec.shape, rec.seed, DEV, lazy_oracle=True)
-    rep, kv = gh.one_pass_parity(rec, weights, DEV, n_requests=int(os.environ.get("SYNERA_C4_REQUESTS", "4")),
+    rep, kv = gh.one_pass_parity(rec, weights, DEV, n_requests=int(os.environ.get("SYNERA_C4_REQUESTS", "6")),
                                  float32_too=True, tag="c4 80 layers")
     assert rep["ok"], rep["fail"]
     assert kv["ok"], kv["fail"]
