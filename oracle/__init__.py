@@ -14,9 +14,9 @@ parity runs use float64, the exact arithmetic of the definition.  A float32 run
 of the same code is not a usable reference for a deep decoder: bf16 KV-cache
 rounding decisions flip where a value sits near a rounding boundary, attention
 carries each flip into the next layer, and the distance between the two runs
-depends on the requests looked at.  Measured at the 70B shape (width 8192),
-max |dlogit| float32 run vs float64 run: 3e-2 on 4 requests at 8 layers;
-at all 80 layers 4.2e-3 on one pair of requests and 1.1e-1 on a sample of six.
+depends on the requests looked at.  Measured at the 70B shape (width 8192, all
+80 layers), max |dlogit| float32 run vs float64 run: 4.2e-3 on one pair of
+requests, 1.1e-1 on a sample of six.
 Parameters and the KV cache hold bf16 values (the cache format is part of the
 method's state), widened exactly.
 

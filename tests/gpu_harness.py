@@ -109,7 +109,7 @@ def draw_weights(shape, seed, device, oracle_dtype=None, lazy_oracle=False):
     if oracle_dtype is None:
         # float64, the exact arithmetic of the definition: a float32 run of the oracle is no arbiter for a deep
         # decoder (bf16 KV-cache rounding decisions flip and attention carries them on; measured at the 70B
-        # shape, float32 run vs float64 run: 3e-2 at 8 layers, 4e-3 to 1e-1 at 80 layers depending on the requests)
+        # shape with all 80 layers, float32 run vs float64 run: 4e-3 to 1e-1 depending on the requests looked at)
         oracle_dtype = np.float64
     head = wl.draw_head_weights(shape, seed, device)
     layers = [wl.draw_layer_weights(shape, seed, l, device) for l in range(shape.n_layers)]
