@@ -13,6 +13,8 @@
 extern "C" {
 #endif
 
+#define SYNERA_MAX_GEMM_SLICES 8 /* K slices a projection may be stored in (synera_debug_gemm_slices) */
+
 /*
  * Stage timing, for the roofline measurement of the kernels inside a verify
  * (the paper gives no breakdown of where the forward pass spends its time;
@@ -47,6 +49,19 @@ int32_t synera_profile_end(synera_ctx* ctx, int32_t* n_launches, float* total_ms
  */
 int32_t synera_gemm_pair(const void* d_a, const void* d_a_lo, const void* d_w, float* d_c,
                          int32_t M, int32_t N, int32_t K, void* stream);
+
+/*
+ * The same contraction for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Arguments and result as
+ * synera_gemm_pair; the K slices that synera_debug_gemm_slices stores to the caller's buffer go to a static
+ * device array of SYNERA_MAX_GEMM_SLICES x SYNERA_STATIC_GEMM_MAX_OUT floats (16 MiB on every GPU the library
+ * runs on, held until the process ends) and are summed in order into d_c; the call allocates and frees
+ * nothing.  M x N beyond SYNERA_STATIC_GEMM_MAX_OUT: ENOSPC.  All calls on one GPU share that GPU's array:
+ * calls that overlap on one GPU (other streams, other threads) race.  Errors: EINVAL, EUNSUP, ENOSPC, EHIP.
+ */
+#define SYNERA_STATIC_GEMM_MAX_OUT 524288
+int32_t synera_gemm_pair_static(const void* d_a, const void* d_a_lo, const void* d_w, float* d_c,
+                                int32_t M, int32_t N, int32_t K, void* stream);
 
 /*
  * Measured ceilings: what this GPU gives the kernels above, taken in the same process as their timings.
@@ -141,7 +156,6 @@ int32_t synera_debug_gemm_epilogue(const void* d_a, const void* d_a_lo, const vo
  * x M x N floats; *h_n_parts (host) receives the number of slices written (1 when K was not split: the
  * whole product is then in slice 0).  N % 128 == 0, K % 64 == 0, else EUNSUP.
  */
-#define SYNERA_MAX_GEMM_SLICES 8
 int32_t synera_debug_gemm_slices(const void* d_a, const void* d_a_lo, const void* d_w, float* d_parts,
                                  int32_t M, int32_t N, int32_t K, int32_t* h_n_parts, void* stream);
 

@@ -75,6 +75,8 @@ _lib.synera_profile_end.restype = C.c_int32
 _lib.synera_profile_end.argtypes = [_vp, C.POINTER(C.c_int32), C.POINTER(C.c_float)]
 _lib.synera_gemm_pair.restype = C.c_int32
 _lib.synera_gemm_pair.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
+_lib.synera_gemm_pair_static.restype = C.c_int32
+_lib.synera_gemm_pair_static.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, _vp]
 _lib.synera_debug_set_lo_off.restype = C.c_int32
 _lib.synera_debug_set_lo_off.argtypes = [_vp, C.c_int32]
 _lib.synera_debug_set_attention_plan.restype = C.c_int32
@@ -222,6 +224,20 @@ def gemm_pair(a, a_lo, w, out=None):
                                c.data_ptr(), M, N, K, _stream())
     _check(st, "synera_gemm_pair")
     return c
+
+
+STATIC_GEMM_MAX_OUT = 524288
+
+
+def gemm_pair_static(a, a_lo, w, out):
+    """synera_gemm_pair for callers that cannot allocate: K slices go through the library's static device array.
+    `out` (f32 [M,N]) is the caller's; nothing is allocated here or in the library."""
+    M, K = a.shape
+    N = w.shape[0]
+    st = _lib.synera_gemm_pair_static(_dev(a, torch.float16), _dev(a_lo, torch.float16), _dev(w, torch.bfloat16),
+                                      _dev(out, torch.float32), M, N, K, _stream())
+    _check(st, "synera_gemm_pair_static")
+    return out
 
 
 def debug_gemm_epilogue(a, a_lo, w0, w1, c, c_lo, epilogue):

@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsynera.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["gemm_nf4_high.hip", "gemm_nf4_low.hip", "gemm_nf2.hip", "api.hip", "elementwise.hip", "confidence.hip", "attention.hip",
-           "importance.hip", "gemm.hip", "ceilings.hip", "scheduler.cpp"]
+           "importance.hip", "gemm.hip", "gemm_static.hip", "ceilings.hip", "scheduler.cpp"]
 # sources whose kernels issue MFMAs from inline assembly: their device assembly is kept and checked
 ASM_CHECKED = {"gemm_nf4_high.hip": "proj_kernel", "gemm_nf4_low.hip": "proj_kernel", "gemm_nf2.hip": "proj_kernel"}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
