@@ -33,7 +33,7 @@ No function here is "parity unpinned".
 """
 from .numerics import bf16_round, bf16_bits, bf16_from_bits  # noqa: F401
 from .confidence import confidence_row, confidence  # noqa: F401
-from .dispatch import softmax_probs, topk_row, topk, margin_row, topp_count, p_conf, p_imp, chunk_dispatch  # noqa: F401
+from .dispatch import softmax_probs, topk_row, topk, margin_row, topp_count, nucleus_row, p_conf, p_imp, chunk_dispatch  # noqa: F401
 from .decoder import (  # noqa: F401
     OracleModel, PagedKV, rmsnorm, rope, attention_one_query, decode_token, forward_tokens,
     lm_head,

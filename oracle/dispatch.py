@@ -2,7 +2,8 @@
 inputs and the compressed distribution a device sends with a chunk):
 
 * top-k entries of a token's softmax distribution, the compressed form transmitted instead of the full
-  vector ("Compression before transmission", Section 4.2);
+  vector ("Compression before transmission", Section 4.2), and the top-p (nucleus) cut over the full
+  vocabulary;
 * the margin score, top-1 minus top-2 probability (layer-wise early exit, Section 4.3);
 * the mean confidence of a chunk and the dispatch probability P_conf(c), a scaled sigmoid above a
   threshold c_th and 1 at or below it (first equation of Section 4.2);
@@ -63,6 +64,23 @@ def topp_count(probs_desc, top_p, dtype=np.float32):
         if acc >= dtype(top_p):
             break
     return n, float(acc)
+
+
+def nucleus_row(x, top_p, dtype=np.float64):
+    """Full-vocabulary top-p (nucleus) truncation of one row of logits (Section 4.2 lists top-p beside top-1
+    and top-k as the sampling methods whose lists are transmitted; the standard definition is taken): sort the
+    softmax probabilities, most probable first (equal logits by the lower id), and keep the smallest prefix
+    whose sum reaches top_p.  Returns (n, mass of the n kept, cut logit = the smallest logit kept,
+    gap = how close the running sum passes to top_p at the two candidates for the cut: an integer decision
+    taken within `gap` of a tie is not unique to rounding)."""
+    x = np.asarray(x, dtype=dtype)
+    p = softmax_probs(x, dtype)
+    order = sorted(range(x.size), key=lambda j: (-x[j], j))
+    cum = np.cumsum(p[order], dtype=dtype)
+    n = int(np.searchsorted(cum, dtype(top_p), side="left")) + 1
+    n = min(n, x.size)                       # rounding may leave the total a hair under top_p = 1
+    near = [abs(float(cum[n - 1]) - top_p)] + ([abs(float(cum[n - 2]) - top_p)] if n > 1 else [])
+    return n, float(cum[n - 1]), float(x[order[n - 1]]), min(near)
 
 
 def p_conf(c, c_th, k=10.0):

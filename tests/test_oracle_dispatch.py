@@ -115,6 +115,57 @@ def test_topp_count_closed_forms_and_brute_force():
         assert mass >= p - 1e-6 and (n == 1 or mass - float(pr32[n - 1]) < p + 1e-6)
 
 
+def test_topk_at_the_sizes_of_a_transmitted_list():
+    """"Compression before transmission" cuts a 32000-entry distribution by over 99.5 %: lists of up to 160
+    entries.  The same definition at k = 64, 160, 256: against numpy's stable sort, on rows with many exact ties
+    (bf16-rounded logits), and the mass the list holds against the complement's."""
+    rng = np.random.default_rng(8)
+    for V, k in ((32000, 64), (32000, 160), (4096, 256), (300, 256)):
+        x = oracle.bf16_round(rng.normal(4.0, 0.05 if V == 4096 else 3.0, V)).astype(np.float64)
+        ids, p = oracle.topk_row(x, k)
+        order = np.argsort(-x, kind="stable")[:k]
+        assert np.array_equal(ids, order)
+        assert len(set(ids.tolist())) == k and np.all(np.diff(p) <= 0)
+        full = oracle.softmax_probs(x)
+        rest = np.delete(full, order)
+        assert p.sum() + rest.sum() == pytest.approx(1.0, abs=1e-12)
+        assert rest.max() <= p[-1]
+
+
+def test_nucleus_closed_forms_and_brute_force():
+    """Full-vocabulary top-p: uniform over V -> ceil(p V) tokens; a geometric distribution p_i = (1 - r) r^i ->
+    the smallest n with 1 - r^n >= top_p; one-hot -> 1; and against the float32 list form on a sorted vector."""
+    V = 64
+    for tp in (0.25, 0.5, 0.515625, 1.0):
+        n, mass, cut, gap = oracle.nucleus_row(np.zeros(V), tp)
+        assert n == math.ceil(tp * V) and mass == pytest.approx(n / V, abs=1e-14) and cut == 0.0
+    r, V = 0.9, 400                                      # logits i ln r: p_i = r^i (1 - r) / (1 - r^V)
+    x = np.arange(V) * math.log(r)
+    for tp in (0.1, 0.5, 0.9, 0.99):
+        n, mass, cut, gap = oracle.nucleus_row(x, tp)
+        want = math.ceil(math.log(1 - tp * (1 - r ** V)) / math.log(r) - 1e-12)
+        assert n == want
+        assert mass == pytest.approx((1 - r ** n) / (1 - r ** V), rel=1e-12)
+        assert cut == pytest.approx((n - 1) * math.log(r), rel=1e-12)
+    hot = np.zeros(100); hot[17] = 50.0
+    assert oracle.nucleus_row(hot, 0.999)[0] == 1
+    # permuting the vocabulary changes neither the size nor the mass; ties are kept in id order
+    rng = np.random.default_rng(4)
+    for _ in range(30):
+        x = rng.normal(0, 3, 500)
+        tp = float(rng.uniform(0.05, 0.999))
+        n, mass, cut, gap = oracle.nucleus_row(x, tp)
+        perm = rng.permutation(500)
+        n2, mass2, cut2, _ = oracle.nucleus_row(x[perm], tp)
+        assert (n, cut) == (n2, cut2) and mass == pytest.approx(mass2, rel=1e-12)
+        assert mass >= tp - 1e-12 and np.sum(x >= cut) == n
+        _, pr = oracle.topk_row(x, 500)
+        n32, _ = oracle.topp_count(pr.astype(np.float32), tp)
+        assert abs(n32 - n) <= (1 if gap < 1e-5 else 0)
+    t = np.array([1.0, 2.0, 2.0, 2.0, 0.0])               # three tied leaders: 2 of them reach 0.5
+    assert oracle.nucleus_row(t, 0.5)[0] == 2 and oracle.nucleus_row(t, 0.5)[2] == 2.0
+
+
 def test_golden_points_of_the_dispatch_curves():
     """tests/golden/dispatch_probabilities.txt: values worked by hand from the two printed equations."""
     import os
