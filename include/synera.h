@@ -193,22 +193,38 @@ int32_t synera_confidence(const void* d_logits, int32_t dtype, int64_t rows, int
                           float* d_entropy, void* stream);
 
 /*
- * The same vocabulary pass, keeping the k <= 8 most probable tokens of each row: the compressed
- * form of a distribution that is transmitted instead of the full vector (Section 4.2,
- * "Compression before transmission": top-1 / top-k of the sampling method in use), and the
- * margin score, top-1 minus top-2 probability, that drives the layer-wise early exit
- * (Section 4.3).  d_logits / dtype / rows / vocab / row_stride_elems as synera_confidence.
+ * The same vocabulary pass, keeping the k most probable tokens of each row: the compressed form of a
+ * distribution that is transmitted instead of the full vector (Section 4.2, "Compression before
+ * transmission": top-1 / top-k of the sampling method in use; a list that cuts 32000 entries by over 99.5 %
+ * has up to 160), and the margin score, top-1 minus top-2 probability, that drives the layer-wise early exit
+ * (Section 4.3).  1 <= k <= SYNERA_MAX_TOPK.  d_logits / dtype / rows / vocab / row_stride_elems as
+ * synera_confidence; entries may be -inf (probability 0), not NaN.
  * Outputs, device: d_topk_id i32 [rows][k] and d_topk_prob f32 [rows][k], most probable first,
  * equal logits by the lower token id first; d_margin f32 [rows] (NULL to skip), d_entropy f32
  * [rows] in nats (NULL to skip).  A row with fewer than k comparable entries (NaN) reports id 0,
- * probability 0 for the missing ones.  Errors: EINVAL; EUNSUP for k > 8 or k > vocab; EHIP.
+ * probability 0 for the missing ones.  Errors: EINVAL; EUNSUP for k > SYNERA_MAX_TOPK or k > vocab; EHIP.
  */
+#define SYNERA_MAX_TOPK 256
 int32_t synera_confidence_topk(const void* d_logits, int32_t dtype, int64_t rows, int64_t vocab,
                                int64_t row_stride_elems, int32_t k, int32_t* d_topk_id,
                                float* d_topk_prob, float* d_margin, float* d_entropy, void* stream);
 
 /*
- * Top-p (nucleus) cut of compressed distributions ("Compression before transmission", Section 4.2:
+ * Top-p (nucleus) cut over the FULL vocabulary (Section 4.2 names top-p beside top-1 and top-k as the sampling
+ * methods whose lists are transmitted; Section 4.5 verifies under it): per row the smallest number of tokens,
+ * most probable first (equal logits by the lower id), whose softmax probabilities sum to at least top_p.
+ * d_count i32 [rows]; d_mass f32 [rows] (NULL to skip) = the probability those tokens hold; d_cut_logit f32
+ * [rows] (NULL to skip) = the smallest logit kept: the nucleus is every token above it plus the first
+ * count - #{above} holders of it in id order, i.e. the first d_count entries of synera_confidence_topk's order.
+ * Logits finite or -inf.  Masses are summed in 40-bit fixed point (order-independent: the count is reproducible);
+ * a running sum that passes within ~1e-6 of top_p may fall either way against an exact evaluation.
+ * Errors: EINVAL (top_p outside (0, 1], null pointers, alignment as synera_confidence), EHIP.
+ */
+int32_t synera_nucleus(const void* d_logits, int32_t dtype, int64_t rows, int64_t vocab, int64_t row_stride_elems,
+                       float top_p, int32_t* d_count, float* d_mass, float* d_cut_logit, void* stream);
+
+/*
+ * Top-p (nucleus) cut INSIDE compressed distributions ("Compression before transmission", Section 4.2:
  * top-1 / top-k / top-p of the sampling method in use).  d_topk_prob: device f32 [rows][k], each row most
  * probable first (synera_confidence_topk's output).  d_count[r] = the smallest n whose float32 running
  * sum p_0 + ... + p_{n-1}, taken in that order, reaches top_p; all k if the window never does.
@@ -239,7 +255,7 @@ int32_t synera_chunk_dispatch(const float* d_top1_prob, const int32_t* d_cu_rows
  * follows the last draft.  q = softmax of the LM-head rows (temperature 1); p_j = the transmitted top-k list
  * of draft row j, renormalised to sum 1 (0 outside the list; a draft absent from its list is rejected).
  *   d_tokens    dev [T]            as given to synera_verify
- *   d_p_id / d_p_prob  dev [R][k_list], 1 <= k_list <= 8 (EUNSUP above): the lists, row order = draft rows
+ *   d_p_id / d_p_prob  dev [R][k_list], 1 <= k_list <= SYNERA_MAX_TOPK (EUNSUP above): the lists, row order = draft rows
  *   d_u_accept  dev f32 [R]        uniform numbers in [0, 1), one per draft row
  *   d_u_sample  dev f32 [B]        one per request, for the emitted token (smallest id whose inclusive
  *                                   cumulative weight, in id order, exceeds u * total)

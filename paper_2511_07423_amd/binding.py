@@ -64,6 +64,8 @@ _lib.synera_confidence.restype = C.c_int32
 _lib.synera_confidence.argtypes = [_vp, C.c_int32, C.c_int64, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp]
 _lib.synera_confidence_topk.restype = C.c_int32
 _lib.synera_confidence_topk.argtypes = [_vp, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_int32, _vp, _vp, _vp, _vp, _vp]
+_lib.synera_nucleus.restype = C.c_int32
+_lib.synera_nucleus.argtypes = [_vp, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_float, _vp, _vp, _vp, _vp]
 _lib.synera_chunk_dispatch.restype = C.c_int32
 _lib.synera_chunk_dispatch.argtypes = [_vp, _vp, C.c_int32, C.c_float, C.c_float, _vp, _vp, _vp]
 _lib.synera_kv_append.restype = C.c_int32
@@ -190,6 +192,23 @@ def confidence_topk(logits, k, want_margin=True, want_entropy=True):
                                      ids.data_ptr(), pr.data_ptr(), _dev(mg), _dev(h), _stream())
     _check(st, "synera_confidence_topk")
     return ids, pr, mg, h
+
+
+def nucleus(logits, top_p):
+    """Full-vocabulary top-p per row of a 2-D f32 or bf16 GPU tensor -> (count i32 [rows], mass f32 [rows],
+    cut logit f32 [rows])."""
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be 2-D with unit column stride")
+    dt = {torch.float32: 0, torch.bfloat16: 1}[logits.dtype]
+    rows, vocab = logits.shape
+    dev = logits.device
+    n = torch.empty(rows, dtype=torch.int32, device=dev)
+    mass = torch.empty(rows, dtype=torch.float32, device=dev)
+    cut = torch.empty(rows, dtype=torch.float32, device=dev)
+    st = _lib.synera_nucleus(logits.data_ptr(), dt, rows, vocab, logits.stride(0) if rows > 1 else vocab, float(top_p),
+                             n.data_ptr(), mass.data_ptr(), cut.data_ptr(), _stream())
+    _check(st, "synera_nucleus")
+    return n, mass, cut
 
 
 def chunk_dispatch(top1_prob, cu_rows, c_th, k_slope=10.0):

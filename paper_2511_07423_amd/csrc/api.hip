@@ -787,7 +787,7 @@ extern "C" int32_t synera_stochastic_accept(synera_ctx* c, const int32_t* d_toke
   if (!c || !d_tokens || !d_p_id || !d_p_prob || !d_u_accept || !d_u_sample || !d_accept_len || !d_token)
     return SYNERA_EINVAL;
   if (k_list < 1) return SYNERA_EINVAL;
-  if (k_list > 8) return SYNERA_EUNSUP;
+  if (k_list > SYNERA_MAX_TOPK) return SYNERA_EUNSUP;
   if (!c->last.valid) return SYNERA_EINVAL;                  // no verification to take the distributions from
   if (!c->last.all_rows_kept) return SYNERA_EUNSUP;          // a request without an uncached token has no q(x | prefix)
   HIP_TRY(launch_stochastic_accept(c->logits, c->desc.vocab, c->lm_ids, c->lm_p, d_tokens, c->last.meta, c->last.B,
@@ -881,14 +881,28 @@ extern "C" int32_t synera_confidence_topk(const void* d_logits, int32_t dtype, i
                                           int64_t row_stride_elems, int32_t k, int32_t* d_topk_id,
                                           float* d_topk_prob, float* d_margin, float* d_entropy, void* stream) {
   if (rows < 0 || vocab < 1 || (dtype != 0 && dtype != 1) || k < 1) return SYNERA_EINVAL;
-  if (k > 8 || k > vocab) return SYNERA_EUNSUP;
+  if (k > SYNERA_MAX_TOPK || k > vocab) return SYNERA_EUNSUP;
   if (rows == 0) return SYNERA_OK;
   if (!d_logits || !d_topk_id || !d_topk_prob || row_stride_elems < vocab) return SYNERA_EINVAL;
-  if (rows > 0x7FFFFFFF / 8 || vocab > 0x7FFFFFFF) return SYNERA_EINVAL;
+  if (rows > 0x7FFFFFFF / SYNERA_MAX_TOPK || vocab > 0x7FFFFFFF) return SYNERA_EINVAL;
   const int64_t align = dtype == 1 ? 8 : 4;
   if (row_stride_elems % align != 0 || (reinterpret_cast<uintptr_t>(d_logits) & 15) != 0) return SYNERA_EINVAL;
   HIP_TRY(launch_confidence_topk(d_logits, dtype, rows, vocab, row_stride_elems, k, d_topk_id, d_topk_prob, d_margin,
                                  d_entropy, static_cast<hipStream_t>(stream)));
+  return SYNERA_OK;
+}
+
+extern "C" int32_t synera_nucleus(const void* d_logits, int32_t dtype, int64_t rows, int64_t vocab,
+                                  int64_t row_stride_elems, float top_p, int32_t* d_count, float* d_mass,
+                                  float* d_cut_logit, void* stream) {
+  if (rows < 0 || vocab < 1 || (dtype != 0 && dtype != 1) || !(top_p > 0.0f && top_p <= 1.0f)) return SYNERA_EINVAL;
+  if (rows == 0) return SYNERA_OK;
+  if (!d_logits || !d_count || row_stride_elems < vocab) return SYNERA_EINVAL;
+  if (rows > 0x7FFFFFFF || vocab > 0x7FFFFFFF) return SYNERA_EINVAL;
+  const int64_t align = dtype == 1 ? 8 : 4;
+  if (row_stride_elems % align != 0 || (reinterpret_cast<uintptr_t>(d_logits) & 15) != 0) return SYNERA_EINVAL;
+  HIP_TRY(launch_nucleus(d_logits, dtype, rows, vocab, row_stride_elems, top_p, d_count, d_mass, d_cut_logit,
+                         static_cast<hipStream_t>(stream)));
   return SYNERA_OK;
 }
 

@@ -80,6 +80,8 @@ hipError_t launch_confidence(const void* logits, int dtype, int64_t rows, int64_
 
 hipError_t launch_confidence_topk(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride, int k,
                                   int32_t* ids, float* probs, float* margin, float* H, hipStream_t s);
+hipError_t launch_nucleus(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride, float top_p,
+                          int32_t* count, float* mass, float* cut_logit, hipStream_t s);
 hipError_t launch_topp_count(const float* probs, int64_t rows, int k, float top_p, int32_t* n, float* mass,
                              hipStream_t s);
 hipError_t launch_stochastic_accept(const float* logits, int vocab, const int32_t* lm_ids, const float* lm_p,

@@ -265,13 +265,384 @@ __global__ __launch_bounds__(256) void confidence_topk_kernel(const void* __rest
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same for 8 < k <= 256, the size of a transmitted list ("Compression before transmission" cuts 32000
+// entries by over 99.5 %: up to 160).  Two levels.  Level 1: each wavefront keeps its k best (logit, id) sorted
+// across its LANES -- entry p lives in register p / 64 of lane p % 64 -- so an insertion is a handful of
+// wavefront-wide instructions whatever k is: a ballot counts the entries that come before the candidate, every
+// lane at or behind that position takes its left neighbour's entry (the entry of lane 63 crosses into lane 0 of
+// the next register), and the lane at the position takes the candidate.  Candidates are found as above (a
+// ballot against the list's k-th entry).  Level 2: the four sorted lists meet in LDS and every entry computes its
+// final rank as its position in its own list plus, by binary search, the number of entries of the other three
+// lists that come before it; ranks below k are the result, already in order.
+#define TOPK_WIDE_MAX 256
+
+template <bool BF16, int R>
+__global__ __launch_bounds__(256) void confidence_topk_wide_kernel(const void* __restrict__ logits, int64_t vocab,
+                                                                   int64_t stride, int k, int32_t* __restrict__ ids,
+                                                                   float* __restrict__ probs, float* __restrict__ margin,
+                                                                   float* __restrict__ H) {
+  constexpr int VEC = BF16 ? 8 : 4;
+  const int64_t row = blockIdx.x;
+  const char* base = reinterpret_cast<const char*>(logits) + row * stride * (BF16 ? 2 : 4);
+  const uint4* src = reinterpret_cast<const uint4*>(base);
+  const int n_vec = (int)(vocab / VEC);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  ConfState st = {-1e30f, 0.f, 0.f, 0};
+  float ev[R];                                       // entry p = r * 64 + lane of the wavefront's sorted list
+  int ei[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    ev[r] = -INFINITY;
+    ei[r] = 0x7FFFFFFF;
+  }
+  float thr_v = -INFINITY;                           // the list's k-th entry (wavefront-uniform)
+  int thr_i = 0x7FFFFFFF;
+  const int kr = (k - 1) >> 6, kl = (k - 1) & 63;    // where entry k - 1 lives
+
+  auto insert = [&](float cv, int ci) {              // wavefront-uniform candidate that comes before the k-th entry
+    int pos = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      pos += __builtin_popcountll(__builtin_amdgcn_ballot_w64(top_before(ev[r], ei[r], cv, ci)));
+#pragma unroll
+    for (int r = R - 1; r >= 0; --r) {
+      float upv = __shfl_up(ev[r], 1);
+      int upi = __shfl_up(ei[r], 1);
+      if (r > 0) {
+        const float cross_v = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(ev[r - 1]), 63));
+        const int cross_i = __builtin_amdgcn_readlane(ei[r - 1], 63);
+        if (lane == 0) {
+          upv = cross_v;
+          upi = cross_i;
+        }
+      }
+      const int p = r * 64 + lane;
+      ev[r] = p < pos ? ev[r] : (p == pos ? cv : upv);
+      ei[r] = p < pos ? ei[r] : (p == pos ? ci : upi);
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (r == kr) {
+        thr_v = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(ev[r]), kl));
+        thr_i = __builtin_amdgcn_readlane(ei[r], kl);
+      }
+  };
+  auto offer = [&](float v, int id) {
+    unsigned long long mask = __builtin_amdgcn_ballot_w64(top_before(v, id, thr_v, thr_i));
+    while (mask) {                                   // wavefront-uniform loop
+      const int l = __builtin_ctzll(mask);
+      mask &= mask - 1;
+      const float cv = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(v), l));
+      const int ci = __builtin_amdgcn_readlane(id, l);
+      if (top_before(cv, ci, thr_v, thr_i)) insert(cv, ci);   // the k-th entry may have moved up meanwhile
+    }
+  };
+  // The list lives across the lanes, so EVERY lane of the wavefront walks through every insertion: the loop
+  // below has no divergent arm; a lane past the end of the row carries -inf entries that are never candidates.
+  auto consume = [&](const uint4& raw, int c, bool valid) {
+    float v[VEC];
+    if constexpr (BF16) {
+      v[0] = bf2f(raw.x & 0xFFFF); v[1] = bf2f(raw.x >> 16);
+      v[2] = bf2f(raw.y & 0xFFFF); v[3] = bf2f(raw.y >> 16);
+      v[4] = bf2f(raw.z & 0xFFFF); v[5] = bf2f(raw.z >> 16);
+      v[6] = bf2f(raw.w & 0xFFFF); v[7] = bf2f(raw.w >> 16);
+    } else {
+      v[0] = __uint_as_float(raw.x); v[1] = __uint_as_float(raw.y);
+      v[2] = __uint_as_float(raw.z); v[3] = __uint_as_float(raw.w);
+    }
+    float cmax = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) cmax = fmaxf(cmax, valid ? v[i] : -INFINITY);
+    if (__builtin_amdgcn_ballot_w64(cmax >= thr_v) != 0) {   // wavefront-uniform
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) offer(valid ? v[i] : -INFINITY, valid ? c * VEC + i : 0x7FFFFFFF);
+    }
+    if (valid) conf_chunk<VEC>(st, v, c * VEC);        // per-lane state: may diverge
+  };
+  const int rounds = (n_vec + 255) / 256;
+  for (int it = 0; it < rounds; ++it) {
+    const int c = it * 256 + threadIdx.x;
+    const bool valid = c < n_vec;
+    const uint4 raw = valid ? src[c] : make_uint4(0u, 0u, 0u, 0u);
+    consume(raw, c, valid);
+  }
+  {
+    const int64_t tail0 = (int64_t)n_vec * VEC;
+    const int n_tail = (int)(vocab - tail0);         // < VEC
+    if (n_tail > 0) {                                // block-uniform
+      const int e = threadIdx.x;
+      float v[1] = {-INFINITY};
+      if (e < n_tail)
+        v[0] = BF16 ? bf2f(reinterpret_cast<const bf16_t*>(base)[tail0 + e]) : reinterpret_cast<const float*>(base)[tail0 + e];
+      offer(e < n_tail ? v[0] : -INFINITY, e < n_tail ? (int)(tail0 + e) : 0x7FFFFFFF);
+      if (e < n_tail) conf_chunk<1>(st, v, (int)(tail0 + e));
+    }
+  }
+
+  for (int o = 1; o < 64; o <<= 1) {
+    ConfState other;
+    other.m = __shfl_xor(st.m, o);
+    other.Z = __shfl_xor(st.Z, o);
+    other.S = __shfl_xor(st.S, o);
+    other.id = __shfl_xor(st.id, o);
+    conf_merge(st, other);
+  }
+  __shared__ ConfState red[4];
+  __shared__ float cv_[4][TOPK_WIDE_MAX];
+  __shared__ int ci_[4][TOPK_WIDE_MAX];
+  __shared__ int n_valid[4];
+  __shared__ float sh_m, sh_z;
+  if (lane == 0) red[wave] = st;
+  int mine = 0;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    cv_[wave][r * 64 + lane] = ev[r];
+    ci_[wave][r * 64 + lane] = ei[r];
+    mine += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ei[r] != 0x7FFFFFFF && r * 64 + lane < k));
+  }
+  if (lane == 0) n_valid[wave] = mine;
+  // defaults for a row with fewer than k comparable entries
+  for (int e = threadIdx.x; e < k; e += 256) {
+    ids[row * k + e] = 0;
+    probs[row * k + e] = 0.f;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    ConfState a = red[0];
+    conf_merge(a, red[1]);
+    conf_merge(a, red[2]);
+    conf_merge(a, red[3]);
+    if (H) H[row] = logf(a.Z) - a.S / a.Z;
+    sh_m = a.m;
+    sh_z = a.Z;
+  }
+  __syncthreads();
+  const float m = sh_m, Z = sh_z;
+  __shared__ float p_top[2];
+  if (threadIdx.x < 2) p_top[threadIdx.x] = 0.f;
+  __syncthreads();
+  for (int w = 0; w < 4; ++w) {
+    const int e = threadIdx.x;                       // entry e of list w
+    if (e >= n_valid[w]) continue;
+    const float v = cv_[w][e];
+    const int id = ci_[w][e];
+    int rank = e;
+    for (int o = 0; o < 4; ++o) {
+      if (o == w) continue;
+      int lo = 0, hi = n_valid[o];                   // first entry of list o that does not come before (v, id)
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (top_before(cv_[o][mid], ci_[o][mid], v, id)) lo = mid + 1; else hi = mid;
+      }
+      rank += lo;
+    }
+    if (rank < k) {
+      const float pr = fast_exp2((v - m) * LOG2E) / Z;
+      ids[row * k + rank] = id;
+      probs[row * k + rank] = pr;
+      if (rank < 2) p_top[rank] = pr;
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0 && margin) margin[row] = p_top[0] - p_top[1];
+}
+
 hipError_t launch_confidence_topk(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride, int k,
                                   int32_t* ids, float* probs, float* margin, float* H, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
+  const unsigned grid = (unsigned)rows;
+  if (k <= TOPK_MAX) {
+    if (dtype == 1)
+      confidence_topk_kernel<true><<<grid, 256, 0, s>>>(logits, vocab, stride, k, ids, probs, margin, H);
+    else
+      confidence_topk_kernel<false><<<grid, 256, 0, s>>>(logits, vocab, stride, k, ids, probs, margin, H);
+    return hipGetLastError();
+  }
+  if (k > TOPK_WIDE_MAX) return hipErrorInvalidValue;
+#define SY_WIDE(R_)                                                                                              \
+  if (dtype == 1)                                                                                                \
+    confidence_topk_wide_kernel<true, R_><<<grid, 256, 0, s>>>(logits, vocab, stride, k, ids, probs, margin, H); \
+  else                                                                                                           \
+    confidence_topk_wide_kernel<false, R_><<<grid, 256, 0, s>>>(logits, vocab, stride, k, ids, probs, margin, H);
+  if (k <= 64) { SY_WIDE(1) } else if (k <= 128) { SY_WIDE(2) } else if (k <= 192) { SY_WIDE(3) } else { SY_WIDE(4) }
+#undef SY_WIDE
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Full-vocabulary top-p (nucleus): per row the smallest number of tokens, most probable first (equal logits by
+// the lower id), whose probabilities sum to top_p, their mass, and the smallest logit kept.  One block per row.
+// After the statistics pass (m, Z) the cut is found by a radix search over the 32-bit order-preserving key of the
+// logits, 8 bits per pass from the top: every pass re-reads the row (from L2), adds each element whose key
+// matches the prefix found so far to one of 256 bins -- its count and its probability mass -- and the bin in which
+// the running mass, taken from the largest keys down, reaches top_p extends the prefix.  Masses are summed as
+// 40-bit fixed point with integer atomics, so the sums do not depend on the order in which the threads arrive and
+// the integer result is reproducible.  After four passes the prefix is one logit value; of its holders (ties) only
+// as many as needed are counted.
+__device__ __forceinline__ uint32_t order_key(float v) {
+  const uint32_t u = __float_as_uint(v);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_value(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7FFFFFFFu) : ~key);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void nucleus_kernel(const void* __restrict__ logits, int64_t vocab, int64_t stride,
+                                                      float top_p, int32_t* __restrict__ count, float* __restrict__ mass,
+                                                      float* __restrict__ cut_logit) {
+  constexpr int VEC = BF16 ? 8 : 4;
+  const int64_t row = blockIdx.x;
+  const char* base = reinterpret_cast<const char*>(logits) + row * stride * (BF16 ? 2 : 4);
+  const uint4* src = reinterpret_cast<const uint4*>(base);
+  const int n_vec = (int)(vocab / VEC);
+  auto load = [&](int c, float (&v)[VEC]) {
+    const uint4 raw = src[c];
+    if constexpr (BF16) {
+      v[0] = bf2f(raw.x & 0xFFFF); v[1] = bf2f(raw.x >> 16);
+      v[2] = bf2f(raw.y & 0xFFFF); v[3] = bf2f(raw.y >> 16);
+      v[4] = bf2f(raw.z & 0xFFFF); v[5] = bf2f(raw.z >> 16);
+      v[6] = bf2f(raw.w & 0xFFFF); v[7] = bf2f(raw.w >> 16);
+    } else {
+      v[0] = __uint_as_float(raw.x); v[1] = __uint_as_float(raw.y);
+      v[2] = __uint_as_float(raw.z); v[3] = __uint_as_float(raw.w);
+    }
+  };
+  auto tail_value = [&](int64_t e) {
+    return BF16 ? bf2f(reinterpret_cast<const bf16_t*>(base)[e]) : reinterpret_cast<const float*>(base)[e];
+  };
+  // ---- statistics
+  ConfState st = {-1e30f, 0.f, 0.f, 0};
+  for (int c = threadIdx.x; c < n_vec; c += 256) {
+    float v[VEC];
+    load(c, v);
+    conf_chunk<VEC>(st, v, c * VEC);
+  }
+  for (int64_t e = (int64_t)n_vec * VEC + threadIdx.x; e < vocab; e += 256) {
+    float v[1] = {tail_value(e)};
+    conf_chunk<1>(st, v, (int)e);
+  }
+  for (int o = 1; o < 64; o <<= 1) {
+    ConfState other;
+    other.m = __shfl_xor(st.m, o);
+    other.Z = __shfl_xor(st.Z, o);
+    other.S = __shfl_xor(st.S, o);
+    other.id = __shfl_xor(st.id, o);
+    conf_merge(st, other);
+  }
+  __shared__ ConfState red[4];
+  __shared__ unsigned long long bin_mass[256];
+  __shared__ unsigned int bin_count[256];
+  __shared__ uint32_t sh_prefix;
+  __shared__ unsigned long long sh_mass_above;
+  __shared__ unsigned int sh_count_above;
+  __shared__ float sh_m, sh_inv_z;
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = st;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    ConfState a = red[0];
+    conf_merge(a, red[1]);
+    conf_merge(a, red[2]);
+    conf_merge(a, red[3]);
+    sh_m = a.m;
+    sh_inv_z = 1.0f / a.Z;
+    sh_prefix = 0;
+    sh_mass_above = 0;
+    sh_count_above = 0;
+  }
+  __syncthreads();
+  const float m = sh_m, inv_z = sh_inv_z;
+  const double FIX = 1099511627776.0;                // 2^40
+  auto fixed_mass = [&](float v) {
+    const float p = fast_exp2(fmaxf(v - m, -1e30f) * LOG2E) * inv_z;
+    return (unsigned long long)((double)p * FIX + 0.5);
+  };
+  // the target in the same fixed point, against the mass the row really sums to in it is not needed: p sums to
+  // 1 within rounding, and top_p = 1 is met by the last element at the latest (the search then ends at the
+  // smallest key present)
+  const unsigned long long target = (unsigned long long)((double)top_p * FIX);
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    bin_mass[threadIdx.x] = 0;
+    bin_count[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t prefix = sh_prefix;
+    const uint32_t pmask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    auto add = [&](float v) {
+      const uint32_t key = order_key(v);
+      if ((key & pmask) != prefix) return;
+      const int b = (key >> shift) & 255;
+      atomicAdd(&bin_mass[b], fixed_mass(v));
+      atomicAdd(&bin_count[b], 1u);
+    };
+    for (int c = threadIdx.x; c < n_vec; c += 256) {
+      float v[VEC];
+      load(c, v);
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) add(v[i]);
+    }
+    for (int64_t e = (int64_t)n_vec * VEC + threadIdx.x; e < vocab; e += 256) add(tail_value(e));
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      unsigned long long acc = sh_mass_above;
+      unsigned int cnt = sh_count_above;
+      int b = -1, last = -1;
+      unsigned long long acc_last = acc;             // the sums as they stood before bin `last` was added
+      unsigned int cnt_last = cnt;
+      for (int t = 255; t >= 0; --t) {
+        if (bin_count[t] == 0) continue;
+        if (acc + bin_mass[t] >= target) {
+          b = t;
+          break;
+        }
+        if (bin_mass[t] > 0 || last < 0) {           // the smallest keys that still carry probability
+          last = t;
+          acc_last = acc;
+          cnt_last = cnt;
+        }
+        acc += bin_mass[t];
+        cnt += bin_count[t];
+      }
+      if (b < 0) {                                   // rounding left the whole row below the target (top_p ~ 1): the cut
+        b = last < 0 ? 0 : last;                     // is the smallest key that carries probability (masked tokens,
+        acc = acc_last;                              // -inf, are never part of a nucleus)
+        cnt = cnt_last;
+      }
+      sh_mass_above = acc;
+      sh_count_above = cnt;
+      sh_prefix = prefix | ((uint32_t)b << shift);
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    // the prefix is now one key: bin_count / bin_mass of its last-pass bin are its holders
+    const uint32_t key = sh_prefix;
+    const int b = key & 255;
+    const unsigned int holders = bin_count[b];
+    const unsigned long long each = holders ? bin_mass[b] / holders : 0;
+    unsigned long long acc = sh_mass_above;
+    unsigned int need = holders;
+    if (each > 0 && acc < target) {
+      const unsigned long long want = (target - acc + each - 1) / each;
+      need = want < holders ? (unsigned int)want : holders;
+    } else if (acc >= target) {
+      need = 0;                                      // cannot happen: the bin was chosen because acc < target
+    }
+    if (need == 0) need = 1;
+    count[row] = (int32_t)(sh_count_above + need);
+    if (mass) mass[row] = (float)((double)(acc + each * need) / FIX);
+    if (cut_logit) cut_logit[row] = key_value(key);
+  }
+}
+
+hipError_t launch_nucleus(const void* logits, int dtype, int64_t rows, int64_t vocab, int64_t stride, float top_p,
+                          int32_t* count, float* mass, float* cut_logit, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
   if (dtype == 1)
-    confidence_topk_kernel<true><<<(unsigned)rows, 256, 0, s>>>(logits, vocab, stride, k, ids, probs, margin, H);
+    nucleus_kernel<true><<<(unsigned)rows, 256, 0, s>>>(logits, vocab, stride, top_p, count, mass, cut_logit);
   else
-    confidence_topk_kernel<false><<<(unsigned)rows, 256, 0, s>>>(logits, vocab, stride, k, ids, probs, margin, H);
+    nucleus_kernel<false><<<(unsigned)rows, 256, 0, s>>>(logits, vocab, stride, top_p, count, mass, cut_logit);
   return hipGetLastError();
 }
 
@@ -344,6 +715,9 @@ __global__ __launch_bounds__(256) void stochastic_accept_kernel(
   __shared__ int sh_n, sh_slice, sh_token;
   __shared__ double sh_sum[256];
   __shared__ double sh_before;
+  __shared__ int l_id[TOPK_WIDE_MAX];                // the list to subtract at the rejected position
+  __shared__ float l_p[TOPK_WIDE_MAX];               // its probabilities, renormalised to 1
+  __shared__ float l_sum;
   const int i = blockIdx.x, tid = threadIdx.x;
   const int r0 = m.cu_draft[i], k = m.cu_draft[i + 1] - r0;
   const int32_t* d = tokens + m.cu_tok[i] + m.n_unc[i];
@@ -372,31 +746,39 @@ __global__ __launch_bounds__(256) void stochastic_accept_kernel(
   const int row = (n == 0) ? m.first_row[i] : r0 + n - 1;      // n == k: the row after the last draft
   const float* l = logits + (size_t)row * vocab;
   const float l_max = l[lm_ids[row]], p_top = lm_p[row];
-  // the list to subtract (none after a full accept)
-  int ids[8];
-  float pr[8];
-  float list_sum = 0.f;
-  const int n_list = n < k ? k_list : 0;
-  for (int e = 0; e < 8; ++e) {
-    ids[e] = -1;
-    pr[e] = 0.f;
-    if (e < n_list) {
-      ids[e] = p_id[(size_t)(r0 + n) * k_list + e];
-      pr[e] = p_prob[(size_t)(r0 + n) * k_list + e];
-      list_sum += pr[e];
-    }
+  const int n_list = n < k ? k_list : 0;                       // nothing to subtract after a full accept
+  if (tid == 0) {
+    float sum = 0.f;
+    for (int e = 0; e < n_list; ++e) sum += p_prob[(size_t)(r0 + n) * k_list + e];   // in list order, as above
+    l_sum = sum;
   }
-  const float list_inv = list_sum > 0.f ? 1.0f / list_sum : 0.f;   // an all-zero list subtracts nothing
-  auto weight = [&](int v) {
-    float w = __expf(l[v] - l_max) * p_top;
-    for (int e = 0; e < 8; ++e)
-      if (ids[e] == v) w -= pr[e] * list_inv;
+  __syncthreads();
+  const float list_inv = l_sum > 0.f ? 1.0f / l_sum : 0.f;     // an all-zero list subtracts nothing
+  for (int e = tid; e < n_list; e += 256) {
+    l_id[e] = p_id[(size_t)(r0 + n) * k_list + e];
+    l_p[e] = p_prob[(size_t)(r0 + n) * k_list + e] * list_inv;
+  }
+  __syncthreads();
+  auto q_of = [&](int v) { return __expf(l[v] - l_max) * p_top; };
+  auto weight = [&](int v) {                                   // max(0, q - p) at token v
+    float w = q_of(v);
+    for (int e = 0; e < n_list; ++e)
+      if (l_id[e] == v) w -= l_p[e];
     return w > 0.f ? w : 0.f;
   };
+  // Slice sums of max(0, q - p): every thread sums q over its slice of the vocabulary; the (few) tokens of the
+  // list are then corrected one by one, in list order, by the thread that owns the slice they fall in.
   const int seg = (vocab + 255) / 256;
   const int v0 = tid * seg, v1 = min(vocab, v0 + seg);
   double mine = 0.0;
-  for (int v = v0; v < v1; ++v) mine += (double)weight(v);
+  for (int v = v0; v < v1; ++v) mine += (double)q_of(v);
+  for (int e = 0; e < n_list; ++e) {
+    const int v = l_id[e];
+    if (v < v0 || v >= v1) continue;
+    bool first = true;                                         // a token listed twice is corrected once, by its total
+    for (int f = 0; f < e; ++f) first = first && l_id[f] != v;
+    if (first) mine += (double)weight(v) - (double)q_of(v);
+  }
   sh_sum[tid] = mine;
   __syncthreads();
   if (tid == 0) {

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-@pytest.mark.parametrize("vocab,k_list", [(256, 4), (2048, 8), (2048, 1)])
+@pytest.mark.parametrize("vocab,k_list", [(256, 4), (2048, 8), (2048, 1), (2048, 64), (4096, 160), (4096, 256)])
 def test_stochastic_accept_matches_the_oracle(vocab, k_list):
     import paper_2511_07423_amd as synera
     shape = wl.ModelShape("mini_sampling", 2, 128, 4, 2, 64, 256, vocab)
@@ -98,9 +98,9 @@ def test_stochastic_accept_matches_the_oracle(vocab, k_list):
         checked += 1
     assert checked >= B * 3 // 4
     assert 0 < np.mean(np.asarray(lens) == k) < 1 and min(lens) == 0      # full accepts and early rejections both occur
-    with pytest.raises(synera.SyneraError) as e:               # lists longer than 8 entries are not supported
-        ver.stochastic_accept(tokens, torch.zeros((R, 9), dtype=torch.int32, device=DEV),
-                              torch.ones((R, 9), dtype=torch.float32, device=DEV), torch.from_numpy(u_acc).to(DEV),
+    with pytest.raises(synera.SyneraError) as e:               # lists longer than 256 entries are not supported
+        ver.stochastic_accept(tokens, torch.zeros((R, 257), dtype=torch.int32, device=DEV),
+                              torch.ones((R, 257), dtype=torch.float32, device=DEV), torch.from_numpy(u_acc).to(DEV),
                               torch.from_numpy(u_smp).to(DEV))
     assert e.value.status == synera.EUNSUP
     # a request without an uncached token has no first distribution: refused
