@@ -11,6 +11,8 @@ own small metadata upload is part of the step).  Drafts come from the library's 
 Prints ONE JSON line: verified draft tokens/s, plus
   roofline     - the dominant kernel (gate/up projection + SiLU*mul) timed with HIP events inside
                  the timed region, its algorithmic FLOPs against the dense bf16 MFMA peak;
+  stages       - the same fields for every projection, the attention kernel and the vocabulary
+                 reduction, each timed with HIP events in a few further steps of the same process;
   cpu_baseline - the CPU oracle timed on a bounded sample of the same workload (this leg is the
                  only place the benchmark touches the oracle).
 """
@@ -29,14 +31,29 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (read + written) of the stage kernels on the default workload, from the two rocprofv3
 # --pmc passes (FETCH_SIZE, WRITE_SIZE) whose summary, commands and copy-kernel calibration are in
 # profiles/gemm_attention_c3_8b_b64_hbm_traffic.md.  Counters cannot be read from inside this process, so the
-# roofline object carries the profiled figure for this exact workload and kernel, and null for any other.
-MEASURED_TRAFFIC_BYTES = {
-    ("c3_8b_b64_ragged", "gate_up"): 407.1e6 + 30.5e6,
-    ("c3_8b_b64_ragged", "down"): 361.8e6 + 34.9e6,
-    ("c3_8b_b64_ragged", "qkv"): 120.2e6 + 26.1e6,
-    ("c3_8b_b64_ragged", "o"): 103.5e6 + 34.9e6,
-    ("c3_8b_b64_ragged", "attention"): 332.8e6 + 15.7e6,
-}
+# roofline objects carry the profiled figure -- but only while the build being timed still launches what was
+# profiled: PROFILED_PLAN is the tile plan of the five projections and the attention work plan on that
+# workload as they were when the counters were read; if the planners of the library being timed answer
+# differently, the traffic fields are null.
+PROFILED_WORKLOAD = "c3_8b_b64_ragged"
+PROFILED_PLAN = None       # filled in with the profile (see profiles/): plan_fingerprint() of that build
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def plan_fingerprint(synera, shape, b, T):
+    """What the library's planners launch for this workload: tile rows x columns / K slices of the five
+    projections, and shares / positions / cut streams of the attention work plan."""
+    import numpy as np
+    d, f, V, qkv = shape.d_model, shape.d_ffn, shape.vocab, shape.q_dim + 2 * shape.kv_dim
+    parts = []
+    for name, n, k, epi, stored in (("qkv", qkv, d, 0, True), ("o", d, shape.q_dim, 1, True), ("gate_up", 2 * f, d, 2, True),
+                                    ("down", d, f, 1, True), ("lm_head", V, d, 0, False)):
+        bm, bn, split = synera.debug_gemm_plan(T, n, k, epi, stored)
+        parts.append(f"{name}={bm}x{bn}/{split}")
+    plan = synera.debug_attention_plan(shape, 512, b["ctx_len"], np.zeros(len(b["ctx_len"]), np.int32), b["n_draft"],
+                                       b["block_table"])
+    parts.append(f"attention={len(plan['shares'])}sh/{len(plan['prog'])}pos/{len(plan['cuts'])}cut")
+    return ";".join(parts)
 
 
 def build_workload(cfg_no, device):
@@ -123,10 +140,26 @@ def cpu_baseline(w, device):
     t0 = time.perf_counter()
     oracle.verify_chunks(model, kv, reqs)
     dt = time.perf_counter() - t0
-    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    # the threads the oracle's matrix products really ran on: numpy's BLAS pool
+    blas, cores = "unknown BLAS", int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    try:
+        from threadpoolctl import threadpool_info
+        pools = [p for p in threadpool_info() if p.get("user_api") == "blas"]
+        if pools:
+            blas = f"{pools[0].get('internal_api')} {pools[0].get('version')}"
+            cores = int(pools[0].get("num_threads", cores))
+    except Exception:                                                           # noqa: BLE001 (reporting only)
+        pass
     return {"value": n_tok / dt, "unit": "verified draft tokens/s", "cores": cores, "kind": "oracle",
-            "sample": (f"oracle.verify_chunks (numpy float64) on {n_req} of {B} requests ({n_tok} draft tokens, their real "
-                       f"contexts), all {shape.n_layers} layers + LM head + verification: {dt:.1f}s")}
+            "sample": (f"oracle.verify_chunks (numpy float64, {blas}, {cores} threads) on {n_req} of {B} requests "
+                       f"({n_tok} draft tokens, their real contexts), all {shape.n_layers} layers + LM head + "
+                       f"verification: {dt:.1f}s")}
+
+
+def roof_fields(o):
+    keep = ("kernel", "bound", "achieved", "peak", "unit", "frac", "algorithmic", "algorithmic_unit", "traffic",
+            "avg_launch_ms", "launches")
+    return {k: o[k] for k in keep}
 
 
 def main():
@@ -138,6 +171,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also print per-stage times to stderr")
     ap.add_argument("--stage", default="gate_up", help="kernel stage the roofline object reports")
+    ap.add_argument("--stage-steps", type=int, default=5,
+                    help="further steps per stage for the `stages` array (each stage bracketed in its own steps)")
+    ap.add_argument("--print-plan", action="store_true", help="print the planners' fingerprint for this workload and exit")
     ap.add_argument("--gemm-tile", type=int, default=-1,
                     help="tuning: force one projection tile for the timed steps (rows/16, +100 for 128 columns)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -175,6 +211,9 @@ def main():
     def step():
         ver.verify_into(ctx, zeros, nd, w["tokens"], w["anchor"], bt, b["n_pages"], w["k_pool"], w["v_pool"], out)
 
+    if args.print_plan:
+        print(plan_fingerprint(synera, shape, b, T))
+        return
     synera.debug_set_gemm_tile(args.gemm_tile)
     for _ in range(args.warmup):
         step()
@@ -194,20 +233,33 @@ def main():
     qd, kd = shape.q_dim, shape.kv_dim
     stage_flops = {"qkv": 2.0 * T * d * (qd + 2 * kd), "o": 2.0 * T * qd * d, "gate_up": 2.0 * T * d * 2 * f,
                    "down": 2.0 * T * f * d, "lm_head": 2.0 * T * d * V}
-    kv_bytes_layer = float((b["ctx_len"] + b["n_draft"]).sum()) * 2 * shape.kv_dim * 2
-    avg_ms = stage_ms / max(n_launch, 1)
-    if args.stage in stage_flops:
-        ach = stage_flops[args.stage] / (avg_ms * 1e-3) / 1e12
-        roof = {"kernel": args.stage, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
-                "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
-                "avg_launch_ms": avg_ms, "launches": n_launch,
-                "note": "algorithmic FLOPs 2*T*params; the kernel issues twice that (bf16 hi+lo activation pairs)"}
-    else:
-        nbytes = {"attention": kv_bytes_layer, "confidence": float(T) * V * 4}[args.stage]
-        ach = nbytes / (avg_ms * 1e-3) / 1e9
-        roof = {"kernel": args.stage, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": ach / HBM_PEAK_GBS, "traffic": None, "avg_launch_ms": avg_ms, "launches": n_launch}
+    stage_bytes = {"attention": float((b["ctx_len"] + b["n_draft"]).sum()) * 2 * shape.kv_dim * 2,
+                   "confidence": float(T) * V * 4}
+    fingerprint = plan_fingerprint(synera, shape, b, T)
+    traffic_valid = w["rec"].name == PROFILED_WORKLOAD and fingerprint == PROFILED_PLAN and args.gemm_tile < 0
 
+    def stage_object(name, n_launch, total_ms):
+        """The roofline fields of one stage from its HIP-event time: algorithmic FLOPs (2 T params) against the dense
+        bf16 MFMA peak for the projections, algorithmic bytes (K/V read once per KV head; the logits once)
+        against the HBM peak for attention and the vocabulary reduction."""
+        avg_ms = total_ms / max(n_launch, 1)
+        if name in stage_flops:
+            ach = stage_flops[name] / (avg_ms * 1e-3) / 1e12
+            o = {"kernel": name, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                 "frac": ach / MFMA_BF16_PEAK_TFLOPS, "algorithmic": stage_flops[name], "algorithmic_unit": "FLOP per launch"}
+        else:
+            ach = stage_bytes[name] / (avg_ms * 1e-3) / 1e9
+            o = {"kernel": name, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                 "frac": ach / HBM_PEAK_GBS, "algorithmic": stage_bytes[name], "algorithmic_unit": "bytes per launch"}
+        o["traffic"] = MEASURED_TRAFFIC_BYTES.get(name) if traffic_valid else None
+        o["avg_launch_ms"] = avg_ms
+        o["launches"] = n_launch
+        return o
+
+    roof = stage_object(args.stage, n_launch, stage_ms)
+    if roof["bound"] == "mfma":
+        roof["note"] = ("algorithmic FLOPs 2*T*params; the kernel issues twice that (fp16 hi + lo activation pairs "
+                        "against bf16 weights widened to fp16)")
     # the same ceiling measured on this box, in this process (published peak stays the denominator of frac)
     from paper_2511_07423_amd.measure import measured_ceilings
     meas = measured_ceilings()
@@ -219,10 +271,21 @@ def main():
         roof["peak_measured"] = meas["hbm_read_GBs"]
         roof["peak_measured_note"] = ("read-only stream over 1 GiB (plain device copy, read + written bytes: %.0f)"
                                       % meas["hbm_copy_GBs"])
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((w["rec"].name, args.stage))
     roof["traffic_unit"] = "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-kernel calibrated)"
-    roof["algorithmic"] = stage_flops[args.stage] if args.stage in stage_flops else nbytes
-    roof["algorithmic_unit"] = "FLOP per launch" if args.stage in stage_flops else "bytes per launch"
+    roof["traffic_plan"] = {"profiled": PROFILED_PLAN, "this_build": fingerprint,
+                            "note": "traffic is null unless the planners still launch what the counters were read on"}
+    # the other kernels of the step, each bracketed by HIP events in a few further steps of the same process
+    stages = []
+    for name in ("qkv", "attention", "o", "gate_up", "down", "lm_head", "confidence"):
+        if name == args.stage:
+            stages.append(dict(roof_fields(roof)))
+            continue
+        ver.profile_begin(synera.STAGES[name])
+        for _ in range(args.stage_steps):
+            step()
+        torch.cuda.synchronize()
+        n, ms = ver.profile_end()
+        stages.append(stage_object(name, n, ms))
     res = {"metric": "verified draft tokens/sec (8B-shape bf16, batch 64) + % of HBM/MFMA roofline",
            "value": T / (ms_per_step * 1e-3), "unit": "verified draft tokens/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
@@ -230,7 +293,7 @@ def main():
            "config": {"workload": w["rec"].name, "requests": B, "draft_tokens": T,
                       "context_tokens": int(b["ctx_len"].sum()), "accepted_plus_correction_tokens": accepted + B,
                       "shape": shape.name},
-           "roofline": roof}
+           "roofline": roof, "stages": stages}
     if args.breakdown:                      # extra passes, one stage bracketed at a time (stderr, not the JSON line)
         total = 0.0
         for name, sid in synera.STAGES.items():

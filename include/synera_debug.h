@@ -44,7 +44,8 @@ int32_t synera_profile_end(synera_ctx* ctx, int32_t* n_launches, float* total_ms
  * C = (A_hi + A_lo) * W^T on the matrix cores, the contraction every projection of the decoder uses
  * (Section 3.4's partial prefill is a stack of these; exported for tests and the GEMM roofline sweep).
  * d_a, d_a_lo: fp16 [M][K] row-major, the (hi, lo) pair of the activations (hi = fp16(v), lo = fp16(v - hi):
- * 22 mantissa bits of v); d_w bf16 [N][K] row-major; d_c f32 [M][N].
+ * 22 mantissa bits of v); d_w bf16 [N][K] row-major; d_c f32 [M][N].  d_a_lo may be NULL: the high part alone is
+ * multiplied (11 mantissa bits, half the matrix-core work: the form the LM head runs in).
  * K must be a multiple of 64 and N of 128 (else EUNSUP).  Errors: EINVAL, EUNSUP, EHIP.
  */
 int32_t synera_gemm_pair(const void* d_a, const void* d_a_lo, const void* d_w, float* d_c,
@@ -173,7 +174,8 @@ int32_t synera_debug_read_scratch(synera_ctx* ctx, int32_t which, void* d_dst, i
  * set in `sites` makes later synera_verify calls on this context write the low part of that site as zeros
  * (numerically: the second matrix-core term of that product dropped).  1 normed rows -> QKV, 2 normed rows ->
  * gate/up, 4 SiLU*mul output -> down, 8 attention output -> O, 16 final normed rows -> LM head, 32 rotated q,
- * 64 attention probabilities.  0 restores full pairs.  Errors: EINVAL.
+ * 64 attention probabilities.  The LM head runs on the high part alone by default (its bit, 16, changes
+ * nothing); 128 gives it the pair.  0 restores the defaults.  Errors: EINVAL.
  */
 #define SYNERA_LO_QKV_IN 1
 #define SYNERA_LO_GATE_UP_IN 2
@@ -182,6 +184,7 @@ int32_t synera_debug_read_scratch(synera_ctx* ctx, int32_t which, void* d_dst, i
 #define SYNERA_LO_LM_HEAD_IN 16
 #define SYNERA_LO_Q 32
 #define SYNERA_LO_P 64
+#define SYNERA_LO_KEEP_LM_HEAD 128
 int32_t synera_debug_set_lo_off(synera_ctx* ctx, int32_t sites);
 
 #ifdef __cplusplus

@@ -223,7 +223,8 @@ def chunk_dispatch(top1_prob, cu_rows, c_th, k_slope=10.0):
     return mean, pc
 
 
-LO_SITES = {"qkv_in": 1, "gate_up_in": 2, "down_in": 4, "o_in": 8, "lm_head_in": 16, "q": 32, "p": 64}
+LO_SITES = {"qkv_in": 1, "gate_up_in": 2, "down_in": 4, "o_in": 8, "lm_head_in": 16, "q": 32, "p": 64,
+            "keep_lm_head": 128}      # the LM head runs on the high part alone unless keep_lm_head is set
 
 
 def split_pair(x, scale=1.0):
@@ -235,7 +236,7 @@ def split_pair(x, scale=1.0):
 
 
 def gemm_pair(a, a_lo, w, out=None):
-    """C = (A + A_lo) W^T on the matrix cores; a, a_lo fp16 [M,K], w bf16 [N,K] -> f32 [M,N]."""
+    """C = (A + A_lo) W^T on the matrix cores; a, a_lo fp16 [M,K] (a_lo None: A alone), w bf16 [N,K] -> f32 [M,N]."""
     M, K = a.shape
     N = w.shape[0]
     c = torch.empty((M, N), dtype=torch.float32, device=a.device) if out is None else out

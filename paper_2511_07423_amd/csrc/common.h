@@ -168,7 +168,7 @@ hipError_t launch_importance_dispatch(const float* importance, const int32_t* cu
 enum GemmEpilogue { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU = 2 };
 struct GemmArgs {
   const uint16_t* a;     // [M][K], high part of the activation's fp16 pair
-  const uint16_t* a_lo;  // [M][K], low part
+  const uint16_t* a_lo;  // [M][K], low part; nullptr (STORE only): the high part alone is multiplied
   const bf16_t* w[3];    // up to three row segments of the bf16 weight (each [rows][K])
   int32_t w_rows[3];     // rows per segment (multiples of the N tile); unused = 0
   void* c;               // f32 [M][N] (STORE/ADD) or the high part of an fp16 pair [M][N/2] (SWIGLU: w[0] = gate, w[1] = up)

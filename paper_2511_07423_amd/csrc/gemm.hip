@@ -23,8 +23,8 @@ static bool tile_fits(const GemmArgs& g, int mt, int nf) {
 // M = 532 on 256-column tiles of 128, 144 and 272 rows: 0.17 us plus 0.086 us per 16-row block; a 128-column tile
 // pays the activation-fragment reads of a 256-column one for half the MFMAs: 0.6x, not 0.5x.  A short tile is
 // bound by its weight stream instead: BN rows x 64 bytes per K step at the ~24 GB/s one compute unit pulls from HBM.
-static double step_us(int mt, int nf) {
-  const double mfma = 0.17 + 0.086 * mt * (nf == 4 ? 1.0 : 0.6);
+static double step_us(int mt, int nf, bool lo) {
+  const double mfma = 0.17 + 0.086 * mt * (nf == 4 ? 1.0 : 0.6) * (lo ? 1.0 : 0.55);   // hi alone: half the MFMAs
   const double stream = 64 * nf * 64 / 24e3;
   return mfma > stream ? mfma : stream;
 }
@@ -45,7 +45,7 @@ static double plan_cost(const GemmArgs& g, int mt, int nf, int split) {
   const long rounds = (tiles * split + 255) / 256;
   const double steps = (double)(g.K / 32) / split;
   const double merge = split > 1 ? 2.4 * split * ((double)g.M * g.N / 2.2e6) : 0.0;
-  return rounds * steps * step_us(mt, nf) + merge;
+  return rounds * steps * step_us(mt, nf, g.a_lo != nullptr) + merge;
 }
 
 static void pick(const GemmArgs& g, int* mt_out, int* nf_out, int* split_out) {
@@ -96,12 +96,13 @@ int gemm_pick_split(const GemmArgs& g) {
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   if (g.M <= 0) return hipSuccess;
-  if (!g.a || !g.a_lo || !g.w[0] || !g.c || g.N < 128 || g.K < 64 || g.K % 64 != 0 || g.split_k < 1)
+  if (!g.a || !g.w[0] || !g.c || g.N < 128 || g.K < 64 || g.K % 64 != 0 || g.split_k < 1)
     return hipErrorInvalidValue;
   int mt, nf, split;
   pick(g, &mt, &nf, &split);
   if (mt < 0 || g.split_k > g.K / 32 || g.split_k > SY_MAX_K_SLICES) return hipErrorInvalidValue;
   if (g.split_k > 1 && (!g.c_parts || g.epilogue == GEMM_SWIGLU)) return hipErrorInvalidValue;
+  if (!g.a_lo && g.epilogue != GEMM_STORE_F32) return hipErrorInvalidValue;
   if (g.epilogue == GEMM_SWIGLU) {
     if (!g.c_lo || !g.w[1]) return hipErrorInvalidValue;
   } else {

@@ -9,7 +9,9 @@
 // normal range (2^-14 2^-SY_W_SHIFT .. 65504 2^-SY_W_SHIFT); the epilogue multiplies the accumulators by
 // GemmArgs::out_scale, which takes that factor and the producer's activation scale out again (powers of two:
 // exact).  The lo term reuses the weight fragments already in registers, so it costs MFMA issue slots but no
-// extra weight traffic from HBM, L2 or LDS.  (The same pair in bf16 carries 16 bits; its rounding noise, amplified
+// extra weight traffic from HBM, L2 or LDS.  A contraction whose result tolerates 11-bit activations (the LM head:
+// its rounding reaches the logits once, not through 32 layers) is launched without a low part (a_lo = nullptr)
+// and skips those copies and MFMAs.  (The same pair in bf16 carries 16 bits; its rounding noise, amplified
 // layer by layer through bf16 KV-cache roundings that fall the other way, put the logits of an 80-layer decoder
 // of width 8192 at 5e-2 from the exact result.)
 //
@@ -62,17 +64,20 @@ __device__ __forceinline__ void glds16_at(const void* gptr, uint32_t lds_addr) {
 // row's bits 1..2, which spreads the 16 rows of a fragment over all banks.
 __device__ __forceinline__ int swz16(int row, int chunk) { return (row * 4 + (chunk ^ ((row >> 1) & 3))) * 8; }
 
-template <int MT, int NF, int EPI>
+template <int MT, int NF, int EPI, bool LO = true>
 __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
   constexpr int BM = 16 * MT, BN = 64 * NF, BK = 32;
   static_assert(NF == 2 || NF == 4, "SwiGLU pairs the fragments (gate, up): NF must be even");
   static_assert(MT >= 1 && MT <= 17, "accumulators: 4 NF MT registers per lane, stages: 3 (2 BM + BN) x 64 B of LDS");
-  constexpr int A_INS = 2 * MT;                  // copy instructions (16 tile rows each) for [A_hi | A_lo]
+  constexpr int TERMS = LO ? 2 : 1;              // activation terms: (hi, lo), or hi alone (LO = false: the low part is
+                                                 // neither copied nor multiplied; 11 mantissa bits, half the MFMAs)
+  constexpr int A_INS = TERMS * MT;              // copy instructions (16 tile rows each) for [A_hi | A_lo]
   constexpr int A_IPW = (A_INS + 3) / 4;         // per wavefront; a surplus one repeats the last group
   constexpr int W_IPW = BN / 16 / 4;
   constexpr int IPW = A_IPW + W_IPW;
-  constexpr int R = 2 * BM + BN;
-  constexpr int C_END = MT > 4 ? MT - 4 : 1;     // the copies of step s+2 go out during row blocks 0 .. C_END-1
+  constexpr int R = TERMS * BM + BN;
+  constexpr int CVT_RB = LO ? 4 : 8;             // row blocks whose MFMAs give the 16 NF conversion instructions cover
+  constexpr int C_END = MT > CVT_RB ? MT - CVT_RB : 1;   // the copies of step s+2 go out during row blocks 0 .. C_END-1
   constexpr int CPB = (IPW + C_END - 1) / C_END; // copies per row block
   __shared__ __attribute__((aligned(16))) uint16_t st0[R * BK];
   __shared__ __attribute__((aligned(16))) uint16_t st1[R * BK];
@@ -107,12 +112,12 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
     const int r = grp * 16 + lane / 4;
     const int ch = (lane % 4) ^ ((r >> 1) & 3);
     const uint16_t* base;
-    if (r < 2 * BM) {
+    if (r < TERMS * BM) {
       int am = m0 + (r < BM ? r : r - BM);
       am = am < M ? am : M - 1;                  // rows past M are copied (clamped) and never stored
       base = (r < BM ? g.a : g.a_lo) + (size_t)am * K;
     } else {
-      const int col = r - 2 * BM;
+      const int col = r - TERMS * BM;
       int wrow;
       const bf16_t* wbase;
       if (EPI == GEMM_SWIGLU) {                  // 16-column groups alternate gate, up
@@ -144,7 +149,7 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
 
   const int l16 = lane & 15, kc = lane >> 4;
   const int a_off = swz16(l16, kc);                               // + i * 16 rows; + BM rows: lo
-  const int w_off = 2 * BM * BK + swz16(wave * 16 * NF + l16, kc);   // + j * 16 rows
+  const int w_off = TERMS * BM * BK + swz16(wave * 16 * NF + l16, kc);   // + j * 16 rows
   // bf16 pair -> fp16 pair: exponent raised on both halves at once, each half widened to fp32 (a shift, a mask),
   // and the two packed again (exact: 8 mantissa bits into 11).  A zero becomes 2^(SY_W_SHIFT - 127) in fp32 and
   // goes back to zero in the packing.
@@ -194,12 +199,12 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
     uint32_t tq[4];                                                                               \
     _Pragma("unroll") for (int i = 0; i < 2 && i < MT; ++i) {                                     \
       fa[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + i * 16 * BK);                       \
-      fl[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + i * 16) * BK);                \
+      if (LO) fl[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + i * 16) * BK);        \
     }                                                                                             \
     _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                              \
       if (i + 2 < MT) {                                                                           \
         fa[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (i + 2) * 16 * BK);           \
-        fl[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + (i + 2) * 16) * BK);    \
+        if (LO) fl[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + (i + 2) * 16) * BK); \
       }                                                                                           \
       _Pragma("unroll") for (int c = 0; c < CPB; ++c)                                             \
           if (i < C_END && i * CPB + c < IPW) SY_COPY(i * CPB + c, NXT, NSTEP)                    \
@@ -207,20 +212,22 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
       _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                            \
         SY_MFMA(acc[i][j], fw[j], fa[i], i)                                                       \
         if (i >= C_END) {                                                                         \
-          SY_CVT_OP(((i - C_END) * 2 * NF + j) * 2)                                               \
-          SY_CVT_OP(((i - C_END) * 2 * NF + j) * 2 + 1)                                           \
+          SY_CVT_OP(((i - C_END) * TERMS * NF + j) * 2)                                           \
+          SY_CVT_OP(((i - C_END) * TERMS * NF + j) * 2 + 1)                                       \
         }                                                                                         \
       }                                                                                           \
-      _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                            \
-        SY_MFMA(acc[i][j], fw[j], fl[i], i)                                                       \
-        if (i >= C_END) {                                                                         \
-          SY_CVT_OP(((i - C_END) * 2 * NF + NF + j) * 2)                                          \
-          SY_CVT_OP(((i - C_END) * 2 * NF + NF + j) * 2 + 1)                                      \
+      if (LO) {                                                                                   \
+        _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                          \
+          SY_MFMA(acc[i][j], fw[j], fl[i], i)                                                     \
+          if (i >= C_END) {                                                                       \
+            SY_CVT_OP(((i - C_END) * 2 * NF + NF + j) * 2)                                        \
+            SY_CVT_OP(((i - C_END) * 2 * NF + NF + j) * 2 + 1)                                    \
+          }                                                                                       \
         }                                                                                         \
       }                                                                                           \
     }                                                                                             \
     if (C_END >= MT) SY_NEXT_W(NEXTSTAGE)                                                         \
-    _Pragma("unroll") for (int p = (MT > C_END ? (MT - C_END) * 4 * NF : 0); p < 16 * NF; ++p) SY_CVT_OP(p) \
+    _Pragma("unroll") for (int p = (MT > C_END ? (MT - C_END) * 2 * TERMS * NF : 0); p < 16 * NF; ++p) SY_CVT_OP(p) \
     _Pragma("unroll") for (int j = 0; j < NF; ++j) fw[j] = fwn[j];                                \
   }
 // CUR holds step s; NXT (the stage read in step s-1) receives step s+2.  Past the end the last step is copied
@@ -330,6 +337,11 @@ static hipError_t launch_proj(const GemmArgs& g, hipStream_t s) {
   constexpr int BM = 16 * MT;
   const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / (64 * NF);
   const dim3 grid(8 * ((n_tiles + 7) / 8) * m_tiles, 1, g.split_k);
+  if (!g.a_lo) {                                 // single-term activations: the plain store form only
+    if (g.epilogue != GEMM_STORE_F32) return hipErrorInvalidValue;
+    proj_kernel<MT, NF, GEMM_STORE_F32, false><<<grid, 256, 0, s>>>(g);
+    return hipGetLastError();
+  }
   switch (g.epilogue) {
     case GEMM_STORE_F32: proj_kernel<MT, NF, GEMM_STORE_F32><<<grid, 256, 0, s>>>(g); break;
     case GEMM_ADD_F32: proj_kernel<MT, NF, GEMM_ADD_F32><<<grid, 256, 0, s>>>(g); break;

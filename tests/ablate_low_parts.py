@@ -28,9 +28,9 @@ def main():
     weights = gh.draw_weights(rec.shape, wl.config(2).seed if rec.shape.name == wl.LLAMA_8B.name else rec.seed, "cuda:0")
     case = gh.build_case(rec, "cuda:0", n_oracle=n_oracle, weights=weights, verbose=True)
     sites = ["qkv_in", "gate_up_in", "down_in", "o_in", "lm_head_in", "q", "p"]
-    runs = [("full pairs", [])] + [(f"no lo at {s}", [s]) for s in sites] + \
+    runs = [("default (pairs; LM head: high part)", [])] + [(f"no lo at {s}", [s]) for s in sites] + \
            [("no lo at any projection input", ["qkv_in", "gate_up_in", "down_in", "o_in", "lm_head_in"]),
-            ("no lo at q and p", ["q", "p"]), ("full pairs again", [])]
+            ("no lo at q and p", ["q", "p"]), ("lo kept at the LM head too", ["keep_lm_head"]), ("default again", [])]
     print(f"config {n} ({rec.name}): {len(case.sampled)} requests followed by the oracle, "
           f"{int(sum(case.batch['n_draft'][i] for i in case.sampled))} rows", flush=True)
     print(f"{'variant':34s} {'max|dlogit|':>12s} {'rms dlogit':>12s} {'argmax rows differing':>22s}", flush=True)

@@ -201,6 +201,24 @@ def test_pair_carries_22_bits_and_weights_of_any_magnitude_below_256_are_exact()
     assert (c[:, 0] == 0).all()
 
 
+@pytest.mark.parametrize("tile", [-1, 1, 5, 8, 9, 12, 17, 103, 112])
+@pytest.mark.parametrize("M,N,K", [(1, 256, 64), (97, 512, 1024), (532, 1024, 4096), (545, 1792, 512), (272, 32000, 256)])
+def test_gemm_on_the_high_part_alone(tile, M, N, K):
+    """The single-term form (the LM head's): exactly the product of the fp16 high part with the weights."""
+    synera = _synera()
+    g = torch.Generator(device=DEV).manual_seed(3 * M + N + K)
+    a = torch.randn((M, K), generator=g, device=DEV).to(torch.float16)
+    w = wl.draw_normal_bf16((N, K), 0.02, 19 * N + K, DEV)
+    synera.debug_set_gemm_tile(tile)
+    try:
+        c = synera.gemm_pair(a, None, w)
+        torch.cuda.synchronize()
+    finally:
+        synera.debug_set_gemm_tile(-1)
+    want = a.double() @ w.double().T
+    assert (c.double() - want).abs().max().item() < 6e-9 * K + 2e-7
+
+
 # tiles: rows / 16 (1..17) with 256 columns, 100 + rows / 16 (1..12) with 128 columns; -1 = the planner's choice
 @pytest.mark.parametrize("tile", [-1] + list(range(1, 18)) + list(range(101, 113)))
 @pytest.mark.parametrize("M,N,K", [(1, 256, 64), (97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (600, 4096, 1792),

@@ -74,4 +74,4 @@ def test_assembly_of_the_last_build_is_clean():
         assert rep == []
         kernels += n_kernels
         mfmas += n_mfma
-    assert kernels == 87 and mfmas > 10000
+    assert kernels == 116 and mfmas > 10000
