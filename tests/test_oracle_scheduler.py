@@ -235,3 +235,64 @@ def test_a_submission_arriving_while_the_iteration_still_runs_waits_for_the_next
     it = calls[-1][0]
     assert (it.request_id, it.ctx_len, it.n_uncached, it.n_draft) == (1, 206, 1, 6)
     assert len(it.pages) == 14                       # 213 tokens
+
+
+def _golden_session():
+    """tests/golden/scheduler_trace.txt parsed into steps."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "scheduler_trace.txt")
+    steps = []
+    for line in open(path):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            steps.append(line.split())
+    return steps
+
+
+def test_golden_session_worked_from_the_listing_of_algorithm_1():
+    """Prefill priority, B <- B_prefill U B, the iteration that ends before remove_completed, L_uncached in
+    batch order, a request that waits for pages, and pages of removed requests reused: the oracle against a
+    session worked by hand from the listing (tests/golden/scheduler_trace.txt)."""
+    steps = _golden_session()
+    assert steps[0][0] == "pool"
+    s = SchedulerOracle(*[int(v) for v in steps[0][1:]])
+    accept, owners, n_iter = {}, {}, 0
+
+    def engine(call):
+        return [accept[it.request_id] if it.final_verify else None for it in call]
+
+    for st in steps[1:]:
+        if st[0] == "prefill":
+            s.submit_prefill(int(st[1]), int(st[2]))
+        elif st[0] == "verify":
+            s.submit_verify(int(st[1]), int(st[2]), int(st[3]))
+        elif st[0] == "finish":
+            s.finish(int(st[1]))
+        elif st[0] == "accept":
+            accept = {int(a): int(b) for a, b in zip(st[1::2], st[2::2])}
+        else:
+            assert st[0] == "iter"
+            kind = st[1]
+            f = dict(x.split("=") for x in st[2:])
+            n_log = len(s.log)
+            assert s.iteration(engine) == kind, st
+            ids = [] if f["ids"] == "-" else [int(v) for v in f["ids"].split(",")]
+            if kind == "idle":
+                assert len(s.log) == n_log
+            else:
+                unc = None if f["unc"] == "-" else [int(v) for v in f["unc"].split(",")]
+                assert s.log[-1] == (kind, ids, unc), st
+            assert s.B == [int(v) for v in f["B"].split(",")], st
+            assert len(s.free_pages) == int(f["free"]), st
+            for item in f["len"].split(","):
+                rid, L = item.split(":")
+                assert s.requests[int(rid)].cached == int(L), st
+            # a page belongs to one live request at a time, and freed pages do come back into use
+            held = [p for r in s.requests.values() for p in r.pages]
+            assert len(held) == len(set(held)) and not set(held) & set(s.free_pages)
+            for r in s.requests.values():
+                for p in r.pages:
+                    owners.setdefault(p, set()).add(r.rid if hasattr(r, "rid") else id(r))
+            n_iter += 1
+    assert n_iter == 9
+    assert any(len(v) > 1 for v in owners.values())          # some page served two requests in turn

@@ -190,3 +190,54 @@ def test_scripted_session_gives_the_same_engine_calls():
             replay()
             s.commit([0 if a is None else a for a in call.accept_len])
     assert n_call == len(sc.calls) > 30
+
+
+def test_golden_session_worked_from_the_listing_of_algorithm_1():
+    """The hand-worked session of tests/golden/scheduler_trace.txt through the C-ABI scheduler: iteration kinds,
+    requests and uncached counts per engine call, cached lengths after every iteration, free pages and the active
+    batch at the end."""
+    from test_oracle_scheduler import _golden_session
+    steps = _golden_session()
+    s = synera.Scheduler(*[int(v) for v in steps[0][1:]])
+    accept = {}
+    for st in steps[1:]:
+        if st[0] == "prefill":
+            s.submit_prefill(int(st[1]), int(st[2]))
+        elif st[0] == "verify":
+            s.submit_verify(int(st[1]), int(st[2]), int(st[3]))
+        elif st[0] == "finish":
+            s.finish(int(st[1]))
+        elif st[0] == "accept":
+            accept = {int(a): int(b) for a, b in zip(st[1::2], st[2::2])}
+        else:
+            f = dict(x.split("=") for x in st[2:])
+            want_len = {int(a): int(b) for a, b in (item.split(":") for item in f["len"].split(","))}
+            if st[1] == "idle":
+                kind, out = s.next()
+                assert kind == synera.SCHED_IDLE and len(out["request_id"]) == 0, st
+            else:
+                ids = [int(v) for v in f["ids"].split(",")]
+                seen = []
+                for _ in range(4):                      # an iteration is one engine call per 32-token chunk
+                    kind, out = s.next()
+                    assert kind == KIND[st[1]], st
+                    for i in out["request_id"].tolist():
+                        if i not in seen:
+                            seen.append(i)
+                    if st[1] == "verify":
+                        assert out["n_uncached"].tolist() == [int(v) for v in f["unc"].split(",")], st
+                        s.commit([accept[int(i)] for i in out["request_id"]])
+                    else:
+                        s.commit()
+                    if all(s.cached_len(i) == L for i, L in want_len.items() if i in ids):
+                        break
+                assert seen == ids, st
+            for rid, L in want_len.items():
+                assert s.cached_len(rid) == L, st
+            last = f
+    # the module closes an iteration (B <- B_prefill U B, remove_completed) when the next one is asked for: the
+    # session ends on an idle iteration, after which its counters are those of the last line
+    assert s.next()[0] == synera.SCHED_IDLE
+    stats = s.stats()
+    assert stats["free_pages"] == int(last["free"]) and stats["active_requests"] == len(last["B"].split(","))
+    assert stats["iterations_prefill"] == 3 and stats["iterations_verify"] == 3
