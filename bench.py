@@ -36,8 +36,14 @@ HBM_PEAK_GBS = 8000.0
 # workload as they were when the counters were read; if the planners of the library being timed answer
 # differently, the traffic fields are null.
 PROFILED_WORKLOAD = "c3_8b_b64_ragged"
-PROFILED_PLAN = None       # filled in with the profile (see profiles/): plan_fingerprint() of that build
-MEASURED_TRAFFIC_BYTES = {}
+PROFILED_PLAN = "qkv=272x256/5;o=144x256/4;gate_up=272x256/1;down=272x256/8;lm_head=272x256/1;attention=512sh/21270pos/258cut"
+MEASURED_TRAFFIC_BYTES = {          # read + written, per launch
+    "gate_up": 405.0e6 + 30.5e6,
+    "down": 361.9e6 + 69.7e6,
+    "qkv": 124.2e6 + 65.4e6,
+    "o": 103.6e6 + 34.9e6,
+    "attention": 332.8e6 + 15.7e6,
+}
 
 
 def plan_fingerprint(synera, shape, b, T):
@@ -276,7 +282,7 @@ def main():
                             "note": "traffic is null unless the planners still launch what the counters were read on"}
     # the other kernels of the step, each bracketed by HIP events in a few further steps of the same process
     stages = []
-    for name in ("qkv", "attention", "o", "gate_up", "down", "lm_head", "confidence"):
+    for name in ("qkv", "attention", "o", "gate_up", "down", "lm_head", "confidence") if args.stage_steps > 0 else ():
         if name == args.stage:
             stages.append(dict(roof_fields(roof)))
             continue

@@ -5,9 +5,10 @@ bench.py at the repository root):
     python -m paper_2511_07423_amd.measure gemm [M ...] # the four projection shapes of the 8B decoder at M = 532, 1152, 2048
     python -m paper_2511_07423_amd.measure sched        # host time of the scheduler per iteration (no GPU needed)
     python -m paper_2511_07423_amd.measure ceilings     # what this GPU gives: device copy (HBM), register-resident MFMA loop
+    python -m paper_2511_07423_amd.measure blocks       # the gate/up tile (272 x 256, K = 4096) on 2 .. 448 blocks, random and zero activations
 
 Each line gives the average launch time over HIP events on the launch stream and the achieved rate
-against MI355X's peak (HBM 8 TB/s; dense bf16 MFMA 2.5 PFLOP/s, algorithmic FLOPs).  Inputs are seeded
+against MI355X's peak (HBM 8 TB/s; dense fp16 / bf16 MFMA 2.5 PFLOP/s, algorithmic FLOPs).  Inputs are seeded
 and synthetic (workloads/)."""
 import json
 import os
@@ -44,8 +45,13 @@ def confidence():
         print(json.dumps({"kernel": "synera_confidence", "rows": shapes.C5B_ROWS, "vocab": shapes.C5B_VOCAB,
                           "dtype": name, "bytes": nbytes, "avg_launch_ms": ms, "bound": "hbm",
                           "achieved_GBs": nbytes / ms / 1e6, "peak_GBs": 8000.0, "frac": nbytes / ms / 1e6 / 8000.0}))
-        ms = _time(lambda: synera.confidence_topk(x, 8))
-        print(json.dumps({"kernel": "synera_confidence_topk (k = 8)", "rows": shapes.C5B_ROWS, "vocab": shapes.C5B_VOCAB,
+        for k in (8, 64, 256):
+            ms = _time(lambda: synera.confidence_topk(x, k))
+            print(json.dumps({"kernel": f"synera_confidence_topk (k = {k})", "rows": shapes.C5B_ROWS, "vocab": shapes.C5B_VOCAB,
+                              "dtype": name, "bytes": nbytes, "avg_launch_ms": ms, "bound": "hbm",
+                              "achieved_GBs": nbytes / ms / 1e6, "peak_GBs": 8000.0, "frac": nbytes / ms / 1e6 / 8000.0}))
+        ms = _time(lambda: synera.nucleus(x, 0.9))            # one read for the maximum and the sum, four for the radix search
+        print(json.dumps({"kernel": "synera_nucleus (top_p = 0.9)", "rows": shapes.C5B_ROWS, "vocab": shapes.C5B_VOCAB,
                           "dtype": name, "bytes": nbytes, "avg_launch_ms": ms, "bound": "hbm",
                           "achieved_GBs": nbytes / ms / 1e6, "peak_GBs": 8000.0, "frac": nbytes / ms / 1e6 / 8000.0}))
 
@@ -106,6 +112,47 @@ def measured_ceilings(copy_bytes=1 << 30, mfma_iters=20000):
     return res
 
 
+def blocks():
+    """What limits the gate/up projection: the same work per block (a 272 x 256 tile of the SwiGLU projection over
+    K = 4096, weights rotated over three copies) on 2, 56, 112, 224 and 448 blocks, with random activations and with
+    zero activations (same instruction stream, little switching power).  A lone pair of blocks shows what the
+    kernel's own structure costs on one compute unit; more blocks add the shared memory system and the chip's
+    power management."""
+    import torch
+    import paper_2511_07423_amd as synera
+    import workloads as wl
+    dev, K = "cuda:0", 4096
+    g = torch.Generator(device=dev).manual_seed(1)
+    synera.debug_set_gemm_tile(17)
+    try:
+        for M, N in ((272, 512), (272, 14336), (272, 28672), (272, 57344), (532, 28672), (544, 57344)):
+            x = torch.randn((M, K), generator=g, device=dev)
+            a, al = synera.split_pair(x, 64.0)
+            ws = [(wl.draw_normal_bf16((N // 2, K), 0.02, 5 + i, dev), wl.draw_normal_bf16((N // 2, K), 0.02, 50 + i, dev))
+                  for i in range(3)]
+            hi = torch.empty((M, N // 2), dtype=torch.float16, device=dev)
+            lo = torch.empty_like(hi)
+            for zero in (False, True):
+                if zero:
+                    a.zero_()
+                    al.zero_()
+                it = iter(range(10 ** 9))
+
+                def launch():
+                    w = ws[next(it) % 3]
+                    synera.debug_gemm_epilogue(a, al, w[0], w[1], hi, lo, 2)
+                ms = _time(launch, n=60, warm=5)
+                tiles = ((M + 271) // 272) * (N // 256)
+                executed = 4.0 * 272 * ((M + 271) // 272) * N * K        # padded rows, both terms
+                print(json.dumps({"kernel": "proj_kernel<17, 4, 2, true>", "M": M, "N": N, "K": K, "blocks": tiles,
+                                  "activations": "zero" if zero else "random", "avg_launch_us": ms * 1e3,
+                                  "executed_TFLOPs": executed / ms / 1e9,
+                                  "executed_TFLOPs_per_busy_CU": executed / ms / 1e9 / min(tiles, 256),
+                                  "peak_TFLOPs_per_CU": 2500.0 / 256}), flush=True)
+    finally:
+        synera.debug_set_gemm_tile(-1)
+
+
 def ceilings():
     print(json.dumps({"what": "measured ceilings (device copy and read-only stream of 1 GiB; 256 blocks x 4 wavefronts x 20000 x 16 MFMA 32x32x16 bf16)",
                       **measured_ceilings()}))
@@ -149,4 +196,4 @@ def sched():
 
 if __name__ == "__main__":
     which = sys.argv[1] if len(sys.argv) > 1 else "confidence"
-    {"confidence": confidence, "gemm": gemm, "sched": sched, "ceilings": ceilings}[which]()
+    {"confidence": confidence, "gemm": gemm, "sched": sched, "ceilings": ceilings, "blocks": blocks}[which]()
