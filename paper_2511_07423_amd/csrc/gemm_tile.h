@@ -79,6 +79,7 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
   constexpr int CVT_RB = LO ? 4 : 8;             // row blocks whose MFMAs give the 16 NF conversion instructions cover
   constexpr int C_END = MT > CVT_RB ? MT - CVT_RB : 1;   // the copies of step s+2 go out during row blocks 0 .. C_END-1
   constexpr int CPB = (IPW + C_END - 1) / C_END; // copies per row block
+  constexpr int SLOTS = TERMS * NF;              // MFMAs per row block
   __shared__ __attribute__((aligned(16))) uint16_t st0[R * BK];
   __shared__ __attribute__((aligned(16))) uint16_t st1[R * BK];
   __shared__ __attribute__((aligned(16))) uint16_t st2[R * BK];
@@ -201,33 +202,26 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
       fa[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + i * 16 * BK);                       \
       if (LO) fl[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + i * 16) * BK);        \
     }                                                                                             \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
     _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                              \
-      if (i + 2 < MT) {                                                                           \
-        fa[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (i + 2) * 16 * BK);           \
-        if (LO) fl[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + (i + 2) * 16) * BK); \
-      }                                                                                           \
-      _Pragma("unroll") for (int c = 0; c < CPB; ++c)                                             \
-          if (i < C_END && i * CPB + c < IPW) SY_COPY(i * CPB + c, NXT, NSTEP)                    \
       if (i == C_END) SY_NEXT_W(NEXTSTAGE)                                                        \
-      _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                            \
-        SY_MFMA(acc[i][j], fw[j], fa[i], i)                                                       \
+      _Pragma("unroll") for (int t = 0; t < SLOTS; ++t) {                                         \
+        if (t < NF) SY_MFMA(acc[i][t], fw[t], fa[i], i)                                           \
+        else SY_MFMA(acc[i][t - NF], fw[t - NF], fl[i], i)                                        \
         if (i >= C_END) {                                                                         \
-          SY_CVT_OP(((i - C_END) * TERMS * NF + j) * 2)                                           \
-          SY_CVT_OP(((i - C_END) * TERMS * NF + j) * 2 + 1)                                       \
+          SY_CVT_OP(((i - C_END) * SLOTS + t) * 2)                                                \
+          SY_CVT_OP(((i - C_END) * SLOTS + t) * 2 + 1)                                            \
         }                                                                                         \
-      }                                                                                           \
-      if (LO) {                                                                                   \
-        _Pragma("unroll") for (int j = 0; j < NF; ++j) {                                          \
-          SY_MFMA(acc[i][j], fw[j], fl[i], i)                                                     \
-          if (i >= C_END) {                                                                       \
-            SY_CVT_OP(((i - C_END) * 2 * NF + NF + j) * 2)                                        \
-            SY_CVT_OP(((i - C_END) * 2 * NF + NF + j) * 2 + 1)                                    \
-          }                                                                                       \
-        }                                                                                         \
+        if (t == 0 && i + 2 < MT) fa[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (i + 2) * 16 * BK); \
+        if (LO && t == NF && i + 2 < MT)                                                          \
+          fl[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + (i + 2) * 16) * BK);  \
+        _Pragma("unroll") for (int c = 0; c < CPB; ++c)                                           \
+            if ((c + 1) % SLOTS == t && i < C_END && i * CPB + c < IPW) SY_COPY(i * CPB + c, NXT, NSTEP) \
+        __builtin_amdgcn_sched_barrier(0);                                                        \
       }                                                                                           \
     }                                                                                             \
     if (C_END >= MT) SY_NEXT_W(NEXTSTAGE)                                                         \
-    _Pragma("unroll") for (int p = (MT > C_END ? (MT - C_END) * 2 * TERMS * NF : 0); p < 16 * NF; ++p) SY_CVT_OP(p) \
+    _Pragma("unroll") for (int p = (MT > C_END ? (MT - C_END) * 2 * SLOTS : 0); p < 16 * NF; ++p) SY_CVT_OP(p) \
     _Pragma("unroll") for (int j = 0; j < NF; ++j) fw[j] = fwn[j];                                \
   }
 // CUR holds step s; NXT (the stage read in step s-1) receives step s+2.  Past the end the last step is copied

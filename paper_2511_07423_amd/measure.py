@@ -121,9 +121,11 @@ def blocks():
     import torch
     import paper_2511_07423_amd as synera
     import workloads as wl
-    dev, K = "cuda:0", 4096
+    dev = "cuda:0"
     g = torch.Generator(device=dev).manual_seed(1)
-    synera.debug_set_gemm_tile(17)
+    tile = int(sys.argv[2]) if len(sys.argv) > 2 else 17          # 17: four wavefronts; 217: the same tile on eight
+    K = int(sys.argv[3]) if len(sys.argv) > 3 else 4096           # row pitch of both operands = 2 K bytes
+    synera.debug_set_gemm_tile(tile)
     try:
         for M, N in ((272, 512), (272, 14336), (272, 28672), (272, 57344), (532, 28672), (544, 57344)):
             x = torch.randn((M, K), generator=g, device=dev)
@@ -144,7 +146,7 @@ def blocks():
                 ms = _time(launch, n=60, warm=5)
                 tiles = ((M + 271) // 272) * (N // 256)
                 executed = 4.0 * 272 * ((M + 271) // 272) * N * K        # padded rows, both terms
-                print(json.dumps({"kernel": "proj_kernel<17, 4, 2, true>", "M": M, "N": N, "K": K, "blocks": tiles,
+                print(json.dumps({"kernel": "proj_kernel<17, 4, 2, true>" if tile == 17 else f"tile {tile}", "M": M, "N": N, "K": K, "blocks": tiles,
                                   "activations": "zero" if zero else "random", "avg_launch_us": ms * 1e3,
                                   "executed_TFLOPs": executed / ms / 1e9,
                                   "executed_TFLOPs_per_busy_CU": executed / ms / 1e9 / min(tiles, 256),
