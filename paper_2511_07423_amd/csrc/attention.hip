@@ -120,7 +120,7 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
 
   // ---- copies: of a K/V position this wavefront copies page tile `wave` (K page a, K page b, V page a,
   //      V page b), of a query position 16 rows of the hi (wave 0, 1) or lo (wave 2, 3) part; IPP
-  //      instructions of one kilobyte each.  K chunks are swizzled by slot, V and Q are copied straight.
+  //      instructions of one kilobyte each.  K chunks are swizzled by slot, Q chunks by row, V halves by row.
   int c_off[IPP];
 #pragma unroll
   for (int j = 0; j < IPP; ++j) {
@@ -128,7 +128,10 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
       const int slot = j * (1024 / (HD * 2)) + lane / CPS;
       c_off[j] = slot * HD + (((lane % CPS) ^ kswz<HD>(slot)) << 3);
     } else {
-      c_off[j] = j * 512 + lane * 8;
+      // V rows ([dim][16 slots], 32 bytes) keep their place; the two 16-byte halves of every second group of
+      // 8 rows are swapped, so that rows d and d + 8, which share banks, are read from different ones
+      const int pos = j * 64 + lane, vrow = pos >> 1;
+      c_off[j] = (vrow * 2 + ((pos & 1) ^ ((vrow >> 3) & 1))) * 8;
     }
   }
   const size_t page_elems = (size_t)Hkv * SY_PAGE * HD;
@@ -151,7 +154,8 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
       for (int j = 0; j < IPP; ++j) {
         int row = row0 + j * RPC + lane / CPS;
         row = row < nrows ? row : nrows - 1;          // rows past the group: copies of its last row, never stored
-        const bf16_t* src = my_q + ((size_t)(e[1] + row / G) * Hq + kh * G + row % G) * HD + (lane % CPS) * 8;
+        const int chunk = (lane % CPS) ^ kswz<HD>((j * RPC + lane / CPS) & 15);   // swizzled like the K slots
+        const bf16_t* src = my_q + ((size_t)(e[1] + row / G) * Hq + kh * G + row % G) * HD + chunk * 8;
         copy_to_lds(src, dst + j * 1024);
       }
     }
@@ -224,8 +228,9 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
         const int r32 = (rb * 16 + n16) & 31;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-          qh[s] = *reinterpret_cast<const bf16x8*>(slot + r32 * (HD * 2) + (4 * s + g) * 16);
-          ql[s] = *reinterpret_cast<const bf16x8*>(slot + 32 * (HD * 2) + r32 * (HD * 2) + (4 * s + g) * 16);
+          const int ch = ((4 * s + g) ^ kswz<HD>(n16)) << 4;
+          qh[s] = *reinterpret_cast<const bf16x8*>(slot + r32 * (HD * 2) + ch);
+          ql[s] = *reinterpret_cast<const bf16x8*>(slot + 32 * (HD * 2) + r32 * (HD * 2) + ch);
         }
       }
       if (row0 == 0) {
@@ -267,8 +272,9 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
       uint4 vf[DB];
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const uint2 va = *reinterpret_cast<const uint2*>(tile + 2 * PAGE_B + (db * 16 + n16) * 32 + 8 * g);
-        const uint2 vb = *reinterpret_cast<const uint2*>(tile + 3 * PAGE_B + (db * 16 + n16) * 32 + 8 * g);
+        const int piece = 16 * ((g >> 1) ^ (n16 >> 3)) + 8 * (g & 1);      // see the copy: halves swapped in rows 8..15
+        const uint2 va = *reinterpret_cast<const uint2*>(tile + 2 * PAGE_B + (db * 16 + n16) * 32 + piece);
+        const uint2 vb = *reinterpret_cast<const uint2*>(tile + 3 * PAGE_B + (db * 16 + n16) * 32 + piece);
         vf[db] = make_uint4(va.x, va.y, vb.x, vb.y);
       }
       __builtin_amdgcn_sched_barrier(0);

@@ -114,8 +114,8 @@ def measured_ceilings(copy_bytes=1 << 30, mfma_iters=20000):
 
 def blocks():
     """What limits the gate/up projection: the same work per block (a 272 x 256 tile of the SwiGLU projection over
-    K = 4096, weights rotated over three copies) on 2, 56, 112, 224 and 448 blocks, with random activations and with
-    zero activations (same instruction stream, little switching power).  A lone pair of blocks shows what the
+    K = 4096, weights rotated over three copies) on 2, 56, 112, 224 and 448 blocks, with random operands, with zero
+    activations and with all operands zero (same instruction stream and memory traffic, less and less switching power).  A lone pair of blocks shows what the
     kernel's own structure costs on one compute unit; more blocks add the shared memory system and the chip's
     power management."""
     import torch
@@ -134,10 +134,14 @@ def blocks():
                   for i in range(3)]
             hi = torch.empty((M, N // 2), dtype=torch.float16, device=dev)
             lo = torch.empty_like(hi)
-            for zero in (False, True):
-                if zero:
+            for operands in ("random", "zero activations", "all zero"):
+                if operands != "random":
                     a.zero_()
                     al.zero_()
+                if operands == "all zero":
+                    for w in ws:
+                        w[0].zero_()
+                        w[1].zero_()
                 it = iter(range(10 ** 9))
 
                 def launch():
@@ -146,8 +150,8 @@ def blocks():
                 ms = _time(launch, n=60, warm=5)
                 tiles = ((M + 271) // 272) * (N // 256)
                 executed = 4.0 * 272 * ((M + 271) // 272) * N * K        # padded rows, both terms
-                print(json.dumps({"kernel": "proj_kernel<17, 4, 2, true>" if tile == 17 else f"tile {tile}", "M": M, "N": N, "K": K, "blocks": tiles,
-                                  "activations": "zero" if zero else "random", "avg_launch_us": ms * 1e3,
+                print(json.dumps({"kernel": "proj_kernel<17, 4, 2, true>" if tile == 17 else f"tile {tile}", "M": M,
+                                  "N": N, "K": K, "blocks": tiles, "operands": operands, "avg_launch_us": ms * 1e3,
                                   "executed_TFLOPs": executed / ms / 1e9,
                                   "executed_TFLOPs_per_busy_CU": executed / ms / 1e9 / min(tiles, 256),
                                   "peak_TFLOPs_per_CU": 2500.0 / 256}), flush=True)
