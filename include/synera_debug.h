@@ -84,12 +84,18 @@ int32_t synera_gemm_pair_static(const void* d_a, const void* d_a_lo, const void*
  * the clock drops under the switching activity), 0 with constants.  d_out (device, blocks x 256 floats)
  * receives one accumulator sum per lane -- with constant operands exactly 2 x iters.  *h_flops (host, may be
  * NULL) receives the FLOPs of the launch.  1 <= blocks <= 4096, 1 <= iters <= 200000, else EINVAL.
+ *
+ * synera_measure_mfma_f16: the same on the instruction the projection kernel issues: iters x 32
+ * v_mfma_f32_16x16x32_f16 per wavefront on 8 independent accumulators; with constant operands every lane's sum is
+ * exactly 8 x iters.  Same arguments and errors.
  */
 #define SYNERA_MEASURE_READ_BLOCKS 4096
 int32_t synera_measure_hbm_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream);
 int32_t synera_measure_hbm_read(uint32_t* d_out, const void* d_src, int64_t bytes, void* stream);
 int32_t synera_measure_mfma_bf16(float* d_out, int32_t blocks, int32_t iters, int32_t random_operands,
                                  int64_t* h_flops, void* stream);
+int32_t synera_measure_mfma_f16(float* d_out, int32_t blocks, int32_t iters, int32_t random_operands,
+                                int64_t* h_flops, void* stream);
 
 /*
  * Tuning hook for the GEMM sweep: force the tile for every later contraction whose shape it fits

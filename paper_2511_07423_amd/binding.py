@@ -101,6 +101,8 @@ _lib.synera_measure_hbm_read.restype = C.c_int32
 _lib.synera_measure_hbm_read.argtypes = [_vp, _vp, C.c_int64, _vp]
 _lib.synera_measure_mfma_bf16.restype = C.c_int32
 _lib.synera_measure_mfma_bf16.argtypes = [_vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int64), _vp]
+_lib.synera_measure_mfma_f16.restype = C.c_int32
+_lib.synera_measure_mfma_f16.argtypes = [_vp, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int64), _vp]
 _lib.synera_debug_attention_plan.restype = C.c_int32
 _lib.synera_debug_attention_plan.argtypes = [_vp, C.c_int32, C.c_int32, _i32p, _i32p, _i32p, _i32p, C.c_int32,
                                              _i32p, _i32p, C.c_int64, _i32p, C.c_int64, _i32p, C.c_int64, _i32p]
@@ -324,6 +326,18 @@ def measure_mfma_bf16(out, blocks, iters, random_operands=True):
     st = _lib.synera_measure_mfma_bf16(_dev(out, torch.float32), blocks, iters, 1 if random_operands else 0,
                                        C.byref(flops), _stream())
     _check(st, "synera_measure_mfma_bf16")
+    return flops.value
+
+
+def measure_mfma_f16(out, blocks, iters, random_operands=True):
+    """Measurement tool: register-resident loop of the projection kernel's MFMA (16x16x32 fp16); returns the FLOPs
+    of the launch."""
+    if out.numel() < blocks * 256:
+        raise ValueError("measure_mfma_f16: out needs blocks x 256 floats")
+    flops = C.c_int64(0)
+    st = _lib.synera_measure_mfma_f16(_dev(out, torch.float32), blocks, iters, 1 if random_operands else 0,
+                                      C.byref(flops), _stream())
+    _check(st, "synera_measure_mfma_f16")
     return flops.value
 
 

@@ -89,6 +89,46 @@ __global__ __launch_bounds__(256) void ceiling_mfma_kernel(float* __restrict__ o
   out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// The same loop on the instruction the projection kernel issues, v_mfma_f32_16x16x32_f16 (4 passes): 8 A fragments,
+// 4 B fragments, 8 independent accumulators (one is reused every eighth MFMA).  Inline assembly with the
+// accumulator tied to its register, as in the projection kernel: through the builtin the compiler moves the
+// accumulators between registers in every iteration and the loop measures those moves.  The build checks the
+// generated assembly for accumulator accesses that come too early (mfma_hazards.py).
+// RANDOM: fp16 values with random signs and mantissas in [0.5, 1); else 1.0 against 2^-7.
+template <bool RANDOM>
+__global__ __launch_bounds__(256) void ceiling_mfma_f16_kernel(float* __restrict__ out, int iters) {
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+  u32x4 a[8], b[4];
+#pragma unroll
+  for (int q = 0; q < 8; ++q)
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t h = ceiling_hash(threadIdx.x * 131 + q * 17 + i + blockIdx.x * 7919);
+      a[q][i] = RANDOM ? ((0x38003800u + (h & 0x03ff03ffu)) ^ (h & 0x80008000u)) : 0x3c003c00u;
+    }
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t h = ceiling_hash(threadIdx.x * 257 + q * 29 + i + 99991);
+      b[q][i] = RANDOM ? ((0x38003800u + (h & 0x03ff03ffu)) ^ (h & 0x80008000u)) : 0x20002000u;
+    }
+  f32x4 acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int n = 0; n < 32; ++n)
+      asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(acc[n % 8]) : "v"(a[n & 7]), "v"(b[(n >> 3) & 3]));
+    asm volatile("s_nop 7" ::: "memory");          // the back edge: the last MFMAs settle before anything may move
+  }
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int i = 0; i < 8; ++i) asm volatile("" : "+v"(acc[i]));
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) s += acc[i][0];
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 extern "C" int32_t synera_measure_hbm_copy(void* d_dst, const void* d_src, int64_t bytes, void* stream) {
   if (!d_dst || !d_src || bytes < 16 || bytes % 16 != 0) return SYNERA_EINVAL;
   if (((uintptr_t)d_dst | (uintptr_t)d_src) % 16 != 0) return SYNERA_EINVAL;
@@ -115,5 +155,15 @@ extern "C" int32_t synera_measure_mfma_bf16(float* d_out, int32_t blocks, int32_
   if (random_operands) ceiling_mfma_kernel<true><<<blocks, 256, 0, s>>>(d_out, iters);
   else ceiling_mfma_kernel<false><<<blocks, 256, 0, s>>>(d_out, iters);
   if (h_flops) *h_flops = (int64_t)blocks * 4 * iters * 16 * (2LL * 32 * 32 * 16);
+  return hipGetLastError() == hipSuccess ? SYNERA_OK : SYNERA_EHIP;
+}
+
+extern "C" int32_t synera_measure_mfma_f16(float* d_out, int32_t blocks, int32_t iters, int32_t random_operands,
+                                           int64_t* h_flops, void* stream) {
+  if (!d_out || blocks < 1 || blocks > 4096 || iters < 1 || iters > 200000) return SYNERA_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (random_operands) ceiling_mfma_f16_kernel<true><<<blocks, 256, 0, s>>>(d_out, iters);
+  else ceiling_mfma_f16_kernel<false><<<blocks, 256, 0, s>>>(d_out, iters);
+  if (h_flops) *h_flops = (int64_t)blocks * 4 * iters * 32 * (2LL * 16 * 16 * 32);
   return hipGetLastError() == hipSuccess ? SYNERA_OK : SYNERA_EHIP;
 }

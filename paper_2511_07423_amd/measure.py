@@ -109,6 +109,14 @@ def measured_ceilings(copy_bytes=1 << 30, mfma_iters=20000):
         ms = _time(loop, n=5, warm=2)
         res[key] = flops[0] / ms / 1e9
     res["mfma_bf16_peak_TFLOPs"] = 2500.0
+    # the instruction the projection kernel issues (16x16x32 fp16, 4 passes), 32 per iteration
+    for key, rnd in (("mfma_f16_constant_operands_TFLOPs", False), ("mfma_f16_random_operands_TFLOPs", True)):
+        flops = [0]
+
+        def loop16():
+            flops[0] = synera.measure_mfma_f16(out, 256, mfma_iters // 2, rnd)
+        ms = _time(loop16, n=5, warm=2)
+        res[key] = flops[0] / ms / 1e9
     return res
 
 
@@ -160,7 +168,7 @@ def blocks():
 
 
 def ceilings():
-    print(json.dumps({"what": "measured ceilings (device copy and read-only stream of 1 GiB; 256 blocks x 4 wavefronts x 20000 x 16 MFMA 32x32x16 bf16)",
+    print(json.dumps({"what": "measured ceilings (device copy and read-only stream of 1 GiB; 256 blocks x 4 wavefronts x 20000 x 16 MFMA 32x32x16 bf16, x 10000 x 32 MFMA 16x16x32 fp16)",
                       **measured_ceilings()}))
 
 

@@ -58,6 +58,27 @@ def test_mfma_loop_constant_operands(blocks, iters):
     assert torch.equal(out, torch.full_like(out, 2.0 * iters))
 
 
+@pytest.mark.parametrize("blocks,iters", [(1, 1), (3, 7), (256, 1000)])
+def test_mfma_f16_loop_constant_operands(blocks, iters):
+    """The loop on the projection kernel's own MFMA: 1.0 x 2^-7 over K = 32, four MFMAs per accumulator and
+    iteration, eight accumulators summed per lane."""
+    out = torch.full((blocks * 256,), -1.0, dtype=torch.float32, device="cuda:0")
+    flops = synera.measure_mfma_f16(out, blocks, iters, random_operands=False)
+    torch.cuda.synchronize()
+    assert flops == blocks * 4 * iters * 32 * 2 * 16 * 16 * 32
+    assert torch.equal(out, torch.full_like(out, 8.0 * iters))
+
+
+def test_mfma_f16_loop_random_operands_is_finite_and_deterministic():
+    a = torch.empty(8 * 256, dtype=torch.float32, device="cuda:0")
+    b = torch.empty_like(a)
+    synera.measure_mfma_f16(a, 8, 500, random_operands=True)
+    synera.measure_mfma_f16(b, 8, 500, random_operands=True)
+    torch.cuda.synchronize()
+    assert torch.isfinite(a).all() and torch.equal(a, b)
+    assert a.abs().max() > 0
+
+
 def test_mfma_loop_random_operands_is_finite_and_deterministic():
     a = torch.empty(8 * 256, dtype=torch.float32, device="cuda:0")
     b = torch.empty_like(a)
@@ -80,5 +101,7 @@ def test_bad_arguments_are_refused():
     assert lib.synera_measure_mfma_bf16(p, 0, 1, 0, None, None) == synera.EINVAL
     assert lib.synera_measure_mfma_bf16(p, 4097, 1, 0, None, None) == synera.EINVAL
     assert lib.synera_measure_mfma_bf16(p, 1, 200001, 0, None, None) == synera.EINVAL
+    assert lib.synera_measure_mfma_f16(None, 1, 1, 0, None, None) == synera.EINVAL
+    assert lib.synera_measure_mfma_f16(p, 4097, 1, 0, None, None) == synera.EINVAL
     with pytest.raises(ValueError):
         synera.measure_mfma_bf16(buf, 8, 1)       # out too small for 8 blocks
