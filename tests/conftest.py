@@ -6,10 +6,15 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+HERE = os.path.dirname(os.path.abspath(__file__))
+if HERE not in sys.path:
+    sys.path.insert(0, HERE)
 
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    import progress                      # tests/progress.py: progress lines of the long tests bypass the capture
+    progress.set_capture_manager(config.pluginmanager.getplugin("capturemanager"))
 
 
 def pytest_collection_modifyitems(config, items):

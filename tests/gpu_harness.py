@@ -17,6 +17,7 @@ import torch
 import oracle
 import paper_2511_07423_amd as synera
 import workloads as wl
+import progress
 from helpers import oracle_model, to_np
 
 LOGIT_TOL = 2e-2          # max |delta| on logits (task statement)
@@ -121,7 +122,7 @@ def build_case(recipe, device="cuda:0", n_oracle=None, batch_size=None, oracle_d
                weights=None):
     shape = recipe.shape
     t0 = time.time()
-    say = (lambda *a: print("[case]", *a, f"(+{time.time() - t0:.1f}s)", flush=True)) if verbose else (lambda *a: None)
+    say = (lambda *a: progress.say("[case]", *a, f"(+{time.time() - t0:.1f}s)")) if verbose else (lambda *a: None)
     b = wl.draw_batch(recipe, batch_size)
     B = len(b["ctx_len"])
     rnd = wl.draw_draft_randoms(recipe, B)
@@ -194,7 +195,18 @@ def build_case(recipe, device="cuda:0", n_oracle=None, batch_size=None, oracle_d
     reqs = [{"block_table": b["block_table"][i], "ctx_len": int(L[i]), "n_draft": int(b["n_draft"][i]),
              "anchor": int(anchors[i])} for i in sampled]
     t1 = time.time()
-    dr, rows = oracle.draft_chain(model, okv, reqs, recipe.p_match, rnd["u"][sampled], rnd["tok"][sampled])
+    plain_layers, passes = model._layers, [0]
+
+    def layer_and_say(l):                     # one line per pass of the oracle over the decoder
+        if l == 0:
+            passes[0] += 1
+            say(f"oracle draft chain: forward pass {passes[0]}")
+        return plain_layers(l) if callable(plain_layers) else plain_layers[l]
+    model._layers = layer_and_say
+    try:
+        dr, rows = oracle.draft_chain(model, okv, reqs, recipe.p_match, rnd["u"][sampled], rnd["tok"][sampled])
+    finally:
+        model._layers = plain_layers
     case.timing["oracle_chain_s"] = time.time() - t1
     say("oracle draft chain done")
     drafts = [None] * B
@@ -354,7 +366,7 @@ def one_pass_parity(recipe, weights, device="cuda:0", n_requests=None, float32_t
     float32_too: also run the oracle in float32 and report how far it lands from its float64 run."""
     shape = recipe.shape
     t0 = time.time()
-    say = lambda *a: print(f"[{tag or recipe.name}]", *a, f"(+{time.time() - t0:.0f}s)", flush=True)   # noqa: E731
+    say = lambda *a: progress.say(f"[{tag or recipe.name}]", *a, f"(+{time.time() - t0:.0f}s)")   # noqa: E731
     b = wl.draw_batch(recipe)
     B = len(b["ctx_len"])
     k = b["n_draft"].astype(np.int32)
@@ -392,12 +404,12 @@ def one_pass_parity(recipe, weights, device="cuda:0", n_requests=None, float32_t
     reqs = [{"block_table": b["block_table"][i], "ctx_len": int(L[i]) - 1, "uncached": [int(rnd["last_ctx_tok"][i])],
              "drafts": drafts[i], "anchor": -1} for i in chosen]
     widen = model._layers
-    if callable(widen):
-        def widen_and_say(l):                 # a line every few layers: a pass over a 70B model takes minutes
-            if l % 8 == 0:
-                say(f"oracle at layer {l}")
-            return widen(l)
-        model._layers = widen_and_say
+
+    def layer_and_say(l):                     # a line every few layers: a pass over a 70B model takes minutes
+        if l % 8 == 0:
+            say(f"oracle at layer {l}")
+        return widen(l) if callable(widen) else widen[l]
+    model._layers = layer_and_say
     want = oracle.verify_chunks(model, okv, reqs)
     say("oracle done")
     rep = {"ok": True, "fail": [], "requests_checked": 0, "rows_checked": 0, "max_logit_err": 0.0,
