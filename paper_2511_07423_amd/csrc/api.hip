@@ -832,6 +832,8 @@ extern "C" int32_t synera_importance(synera_ctx* c, int32_t n_pages_in_pool, con
   a.Hkv = m.n_kv_heads;
   a.hd = m.head_dim;
   a.importance = d_importance;
+  a.parts = c->gparts;           // the projections' K-slice buffer is free between verifies, like qkv
+  a.parts_cap = c->gpart_elems * SY_MAX_K_SLICES;
   HIP_TRY(launch_importance(a, s));
   HIP_TRY(launch_importance_dispatch(d_importance, c->last.cu_keys, c->last.ctx_len, c->last.n_unc, c->last.cu_draft,
                                      c->last.B, i_th, theta, d_mean_importance, d_p_imp, s));

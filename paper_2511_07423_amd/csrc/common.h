@@ -157,6 +157,8 @@ struct ImportanceLaunch {
   const int32_t* items;      // device [n_items][2]: request, first key of the block's 256 keys
   int32_t n_items, max_pages, T, Hq, Hkv, hd, total_keys;
   float* importance;         // [cu_keys[B]]
+  float* parts;              // scratch: the Hkv shares of a pass's items, [Hkv][items][256]
+  size_t parts_cap;          // floats
 };
 hipError_t launch_importance(const ImportanceLaunch& a, hipStream_t s);
 // mean score of each request's draft positions and P_imp of it (Section 4.2, second equation)

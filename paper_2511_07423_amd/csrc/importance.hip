@@ -14,7 +14,8 @@
 // barrier, no per-lane address arithmetic.  Rows are walked uniformly; a key inside the chunk simply does
 // not add the rows that cannot see it.  A block covers one KV head (the grid's second dimension: with the
 // heads in one block the launch had only about one wavefront per SIMD and ran five times longer); the
-// Hkv shares of a key meet in the output through fp32 atomic adds.  Each K byte of the layer is read once.  Vector-ALU bound:
+// Hkv shares of a key are stored side by side in scratch and a second small kernel adds them in head order (no
+// atomics: the scores are bit-reproducible).  Each K byte of the layer is read once.  Vector-ALU bound:
 // 2 Hq c h FLOP per key, about 5 GFLOP on the headline batch.
 #include "common.h"
 
@@ -33,14 +34,9 @@ __global__ __launch_bounds__(256) void importance_q_kernel(const bf16_t* __restr
   reinterpret_cast<float4*>(qf)[i] = v;
 }
 
-__global__ __launch_bounds__(256) void importance_zero_kernel(float* __restrict__ p, size_t n) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) p[i] = 0.f;
-}
-
 template <int HD>
-__global__ __launch_bounds__(256) void importance_kernel(ImportanceLaunch a, float scale_log2) {
-  const SY_CONST_AS int32_t* items = reinterpret_cast<const SY_CONST_AS int32_t*>((uintptr_t)a.items);
+__global__ __launch_bounds__(256) void importance_kernel(ImportanceLaunch a, int item0, int n_batch, float scale_log2) {
+  const SY_CONST_AS int32_t* items = reinterpret_cast<const SY_CONST_AS int32_t*>((uintptr_t)a.items) + 2 * item0;
   const int req = items[2 * blockIdx.x], key0 = items[2 * blockIdx.x + 1];
   const int L = a.ctx_len[req], tok0 = a.cu_tok[req], c = a.cu_tok[req + 1] - tok0;
   const int Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
@@ -87,21 +83,38 @@ __global__ __launch_bounds__(256) void importance_kernel(ImportanceLaunch a, flo
       }
     }
   }
-  // the Hkv blocks of a key add their shares (the output was zeroed by the launch): hardware fp32 atomics,
-  // so the order of these Hkv additions, and with it the last bit of a score, can differ between runs
-  if (live) unsafeAtomicAdd(a.importance + a.cu_keys[req] + key, total / (float)Hq);
+  // this KV head's share of the block's 256 keys; importance_sum_kernel adds the Hkv shares in head order
+  a.parts[((size_t)blockIdx.y * n_batch + blockIdx.x) * 256 + threadIdx.x] = live ? total / (float)Hq : 0.f;
+}
+
+// Block = one item (256 keys of a request): score = sum of the Hkv shares, in head order.
+__global__ __launch_bounds__(256) void importance_sum_kernel(ImportanceLaunch a, int item0, int n_batch) {
+  const int req = a.items[2 * (item0 + blockIdx.x)], key0 = a.items[2 * (item0 + blockIdx.x) + 1];
+  const int n_keys = a.ctx_len[req] + a.cu_tok[req + 1] - a.cu_tok[req];
+  const int key = key0 + (int)threadIdx.x;
+  if (key >= n_keys) return;
+  float sum = 0.f;
+  for (int kh = 0; kh < a.Hkv; ++kh) sum += a.parts[((size_t)kh * n_batch + blockIdx.x) * 256 + threadIdx.x];
+  a.importance[a.cu_keys[req] + key] = sum;
 }
 
 hipError_t launch_importance(const ImportanceLaunch& a, hipStream_t s) {
   if (a.n_items <= 0) return hipSuccess;
+  if (!a.parts || a.parts_cap < (size_t)a.Hkv * 256) return hipErrorInvalidValue;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)a.hd);
   const size_t n4 = (size_t)a.T * a.Hq * a.hd / 4;
   importance_q_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, s>>>(a.q, a.q_lo, a.qf, n4);
-  importance_zero_kernel<<<(unsigned)(((size_t)a.total_keys + 255) / 256), 256, 0, s>>>(a.importance, (size_t)a.total_keys);
-  const dim3 grid(a.n_items, a.Hkv);
-  if (a.hd == 128) importance_kernel<128><<<grid, 256, 0, s>>>(a, scale_log2);
-  else if (a.hd == 64) importance_kernel<64><<<grid, 256, 0, s>>>(a, scale_log2);
-  else return hipErrorInvalidValue;
+  // as many items per pass as the scratch holds shares for (one pass on every workload measured)
+  const size_t fit = a.parts_cap / ((size_t)a.Hkv * 256);
+  const int per_pass = (int)(fit < (size_t)a.n_items ? fit : (size_t)a.n_items);
+  for (int item0 = 0; item0 < a.n_items; item0 += per_pass) {
+    const int n_batch = a.n_items - item0 < per_pass ? a.n_items - item0 : per_pass;
+    const dim3 grid(n_batch, a.Hkv);
+    if (a.hd == 128) importance_kernel<128><<<grid, 256, 0, s>>>(a, item0, n_batch, scale_log2);
+    else if (a.hd == 64) importance_kernel<64><<<grid, 256, 0, s>>>(a, item0, n_batch, scale_log2);
+    else return hipErrorInvalidValue;
+    importance_sum_kernel<<<n_batch, 256, 0, s>>>(a, item0, n_batch);
+  }
   return hipGetLastError();
 }
 

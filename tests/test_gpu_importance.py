@@ -60,6 +60,10 @@ def test_importance_scores_match_the_oracle(shape):
     i_th = 0.2
     out = ver.importance(ctx, unc, k, n_pages, kp, i_th=i_th)
     torch.cuda.synchronize()
+    # the KV-head shares of a score are added in a fixed order: a second call returns the same bits
+    again = ver.importance(ctx, unc, k, n_pages, kp, i_th=i_th)
+    torch.cuda.synchronize()
+    assert torch.equal(out["scores"], again["scores"])
     got = out["scores"].cpu().numpy().astype(np.float64)
     off = out["offsets"]
     worst = 0.0
