@@ -297,7 +297,11 @@ def main():
     res = {"metric": "verified draft tokens/sec (8B-shape bf16, batch 64) + % of HBM/MFMA roofline",
            "value": T / (ms_per_step * 1e-3), "unit": "verified draft tokens/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "vs_baseline": None, "dtype": "bf16",
+           "dtype_note": ("bf16 weights and KV cache (the metric's model type); matrix-core operands: fp16 (hi, lo) activation "
+                          "pairs against the bf16 weights widened exactly to fp16, bf16 pairs against the bf16 cache in "
+                          "attention; fp32 accumulation and residual stream"),
+           "data": "synthetic",
            "config": {"workload": w["rec"].name, "requests": B, "draft_tokens": T,
                       "context_tokens": int(b["ctx_len"].sum()), "accepted_plus_correction_tokens": accepted + B,
                       "shape": shape.name},
