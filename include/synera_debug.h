@@ -100,7 +100,8 @@ int32_t synera_measure_mfma_f16(float* d_out, int32_t blocks, int32_t iters, int
 /*
  * Tuning hook for the GEMM sweep: force the tile for every later contraction whose shape it fits
  * (-1 restores the automatic choice).  tile = rows / 16 (1 .. 17) for 256-column tiles, 100 + rows / 16
- * (rows / 16 = 1 .. 12) for 128-column tiles.  Process-wide.
+ * (rows / 16 = 1 .. 12) for 128-column tiles; + 200 for the form with two MFMA K steps per stage (256 columns:
+ * rows / 16 = 1 .. 5, 128 columns: 1 .. 9).  Process-wide.
  */
 int32_t synera_debug_set_gemm_tile(int32_t tile);
 
@@ -142,6 +143,13 @@ int32_t synera_debug_set_attention_plan(synera_ctx* ctx, int32_t attn_blocks, fl
  */
 int32_t synera_debug_gemm_plan(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices,
                                int32_t* h_tile_rows, int32_t* h_tile_cols, int32_t* h_k_slices);
+
+/*
+ * The same question for the K extent of one LDS stage of that plan: 32 (one MFMA K step per barrier) or 64 (two,
+ * the form the short tiles take).  *h_stage_k is a host pointer.  Same errors.
+ */
+int32_t synera_debug_gemm_plan_bk(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices,
+                                  int32_t* h_stage_k);
 
 /*
  * Test hook: one launch of the projection GEMM with the epilogue the decoder layers use

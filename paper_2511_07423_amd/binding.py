@@ -108,6 +108,8 @@ _lib.synera_debug_attention_plan.argtypes = [_vp, C.c_int32, C.c_int32, _i32p, _
                                              _i32p, _i32p, C.c_int64, _i32p, C.c_int64, _i32p, C.c_int64, _i32p]
 _lib.synera_debug_gemm_plan.restype = C.c_int32
 _lib.synera_debug_gemm_plan.argtypes = [C.c_int32] * 5 + [C.POINTER(C.c_int32)] * 3
+_lib.synera_debug_gemm_plan_bk.restype = C.c_int32
+_lib.synera_debug_gemm_plan_bk.argtypes = [C.c_int32] * 5 + [C.POINTER(C.c_int32)]
 _lib.synera_debug_gemm_epilogue.restype = C.c_int32
 _lib.synera_debug_gemm_epilogue.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp]
 
@@ -372,6 +374,14 @@ def debug_gemm_plan(M, N, K, epilogue=0, stored_slices=True):
     st = _lib.synera_debug_gemm_plan(M, N, K, epilogue, 1 if stored_slices else 0, C.byref(bm), C.byref(bn), C.byref(split))
     _check(st, "synera_debug_gemm_plan")
     return bm.value, bn.value, split.value
+
+
+def debug_gemm_plan_bk(M, N, K, epilogue=0, stored_slices=True):
+    """Test hook (host only): K extent of one LDS stage (32 or 64) of the plan debug_gemm_plan reports."""
+    bk = C.c_int32(0)
+    st = _lib.synera_debug_gemm_plan_bk(M, N, K, epilogue, 1 if stored_slices else 0, C.byref(bk))
+    _check(st, "synera_debug_gemm_plan_bk")
+    return bk.value
 
 
 def debug_set_gemm_tile(variant):

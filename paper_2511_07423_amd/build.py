@@ -11,10 +11,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsynera.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["gemm_nf4_high.hip", "gemm_nf4_low.hip", "gemm_nf2.hip", "api.hip", "elementwise.hip", "confidence.hip", "attention.hip",
+SOURCES = ["gemm_nf4_high.hip", "gemm_nf4_low.hip", "gemm_nf2.hip", "gemm_k64.hip", "api.hip", "elementwise.hip", "confidence.hip", "attention.hip",
            "importance.hip", "gemm.hip", "gemm_static.hip", "ceilings.hip", "scheduler.cpp"]
 # sources whose kernels issue MFMAs from inline assembly: their device assembly is kept and checked
-ASM_CHECKED = {"gemm_nf4_high.hip": "proj_kernel", "gemm_nf4_low.hip": "proj_kernel", "gemm_nf2.hip": "proj_kernel",
+ASM_CHECKED = {"gemm_nf4_high.hip": "proj_kernel", "gemm_nf4_low.hip": "proj_kernel", "gemm_nf2.hip": "proj_kernel", "gemm_k64.hip": "proj_kernel",
                "ceilings.hip": "ceiling_mfma_f16"}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

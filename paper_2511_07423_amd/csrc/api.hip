@@ -1045,26 +1045,44 @@ extern "C" int32_t synera_debug_attention_plan(const synera_model_desc* desc, in
   return st;
 }
 
+// The planner's view of a projection of M rows (host only: the pointers are only asked whether they are there).
+static int32_t plan_args(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices, GemmArgs* g) {
+  if (M < 1 || N < 1 || K < 1 || epilogue < 0 || epilogue > 2) return SYNERA_EINVAL;
+  if (N % (epilogue == GEMM_SWIGLU ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
+  *g = GemmArgs{};
+  g->a_lo = reinterpret_cast<const uint16_t*>(uintptr_t(64));
+  g->w_rows[0] = epilogue == GEMM_SWIGLU ? N / 2 : N;
+  g->w_rows[1] = epilogue == GEMM_SWIGLU ? N / 2 : 0;
+  g->M = M;
+  g->N = N;
+  g->K = K;
+  g->epilogue = epilogue;
+  g->split_k = 1;
+  g->c_parts = stored_slices && epilogue != GEMM_SWIGLU ? reinterpret_cast<float*>(uintptr_t(64)) : nullptr;
+  return SYNERA_OK;
+}
+
 extern "C" int32_t synera_debug_gemm_plan(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices,
                                           int32_t* h_tile_rows, int32_t* h_tile_cols, int32_t* h_k_slices) {
-  if (!h_tile_rows || !h_tile_cols || !h_k_slices || M < 1 || N < 1 || K < 1 || epilogue < 0 || epilogue > 2)
-    return SYNERA_EINVAL;
-  if (N % (epilogue == GEMM_SWIGLU ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
-  GemmArgs g{};
-  g.a_lo = reinterpret_cast<const uint16_t*>(uintptr_t(64));   // the planner only asks whether there is a low part
-  g.w_rows[0] = epilogue == GEMM_SWIGLU ? N / 2 : N;
-  g.w_rows[1] = epilogue == GEMM_SWIGLU ? N / 2 : 0;
-  g.M = M;
-  g.N = N;
-  g.K = K;
-  g.epilogue = epilogue;
-  g.split_k = 1;
-  g.c_parts = stored_slices && epilogue != GEMM_SWIGLU ? reinterpret_cast<float*>(uintptr_t(64)) : nullptr;   // only asked whether there
+  if (!h_tile_rows || !h_tile_cols || !h_k_slices) return SYNERA_EINVAL;
+  GemmArgs g;
+  const int32_t st = plan_args(M, N, K, epilogue, stored_slices, &g);
+  if (st != SYNERA_OK) return st;
   int bm = 0, bn = 0, split = 1;
   gemm_plan(g, &bm, &bn, &split);
   *h_tile_rows = bm;
   *h_tile_cols = bn;
   *h_k_slices = split;
+  return SYNERA_OK;
+}
+
+extern "C" int32_t synera_debug_gemm_plan_bk(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices,
+                                             int32_t* h_stage_k) {
+  if (!h_stage_k) return SYNERA_EINVAL;
+  GemmArgs g;
+  const int32_t st = plan_args(M, N, K, epilogue, stored_slices, &g);
+  if (st != SYNERA_OK) return st;
+  *h_stage_k = gemm_plan_bk(g);
   return SYNERA_OK;
 }
 

@@ -187,8 +187,10 @@ struct GemmArgs {
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 int gemm_pick_split(const GemmArgs& g);                             // K slices launch_gemm should be given (1 without c_parts)
 void gemm_plan(const GemmArgs& g, int* bm, int* bn, int* split);    // tile and K slices launch_gemm would use (host only)
-void gemm_force_variant(int v);   // tuning hook: -1 automatic, else tile rows / 16 + (128-column tile ? 100 : 0)
+void gemm_force_variant(int v);   // tuning hook: -1 automatic, else tile rows / 16 + (128-column tile ? 100 : 0) + (BK = 64 ? 200 : 0)
+int gemm_plan_bk(const GemmArgs& g);                               // K extent of a stage the plan uses (32 or 64)
 // the instantiations live in three translation units (compile time)
 hipError_t launch_proj_nf4_low(int mt, const GemmArgs& g, hipStream_t s);    // 256 columns, 16 .. 144 rows
 hipError_t launch_proj_nf4_high(int mt, const GemmArgs& g, hipStream_t s);   // 256 columns, 160 .. 272 rows
 hipError_t launch_proj_nf2(int mt, const GemmArgs& g, hipStream_t s);        // 128 columns, 16 .. 192 rows
+hipError_t launch_proj_k64(int mt, int nf, const GemmArgs& g, hipStream_t s);   // BK = 64: 128 columns x 16 .. 144 rows, 256 x 16 .. 80

@@ -16,8 +16,10 @@
 // of width 8192 at 5e-2 from the exact result.)
 //
 // Tile: BM = 16 MT rows x BN = 64 NF columns, four wavefronts (one per SIMD), each owning all BM rows of 16 NF
-// columns.  BK = 32 is exactly one MFMA K step: lane l holds row l % 16 and the 8 k values of chunk l / 16 for
-// both operands.  The weight fragment is the MFMA's first operand, so a lane ends up with 4 consecutive output
+// columns.  A stage holds BK = 32 KSUB of K: one MFMA K step (lane l holds row l % 16 and the 8 k values of chunk
+// l / 16 for both operands), or two for the short tiles (KSUB = 2: tile rows of 128 bytes, so every copy moves
+// whole cache lines, half the requests for the same bytes, and the K loop has half the barriers; small batches
+// are bound by exactly these).  The weight fragment is the MFMA's first operand, so a lane ends up with 4 consecutive output
 // columns of one row and the epilogue stores 16 bytes per lane.  Per K step a wavefront reads its NF weight
 // fragments once and streams the 2 MT activation fragments (hi, lo) through them; each activation fragment feeds
 // NF independent accumulators, which is what this 4-pass MFMA needs to issue back to back.  Accumulators 0..255
@@ -25,7 +27,7 @@
 //
 // Data movement: the rows [A_hi | A_lo | W] of K step s+2 stream straight from global memory into LDS
 // (global_load_lds_dwordx4: no staging registers, no LDS store instructions) while step s is multiplied; three
-// LDS stages.  A copy instruction of one wavefront fills 1 KB = 16 tile rows; the XOR swizzle that keeps the
+// LDS stages.  A copy instruction of one wavefront fills 1 KB = 16 (or 8) tile rows; the XOR swizzle that keeps the
 // fragment reads bank-conflict free is applied on the global side (lane i fetches the chunk that belongs at LDS
 // position i).  Per K step each wavefront waits for its own copies of the step (s_waitcnt vmcnt) and one
 // s_barrier makes every wavefront's copies visible and certifies that the stage about to be overwritten is no
@@ -59,27 +61,40 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
 __device__ __forceinline__ void glds16_at(const void* gptr, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
 }
-// Element offset of 16-byte chunk `chunk` of tile row `row` (rows of 4 chunks).  A fragment read (lane = row
-// l % 16, chunk l / 16) is served 16 lanes per cycle over the 64 banks: the chunk position varies with the
-// row's bits 1..2, which spreads the 16 rows of a fragment over all banks.
-__device__ __forceinline__ int swz16(int row, int chunk) { return (row * 4 + (chunk ^ ((row >> 1) & 3))) * 8; }
+// Element offset of 16-byte chunk `chunk` of tile row `row` (rows of CPR = 4 or 8 chunks: 64 or 128 bytes).  A
+// fragment read (lane = row l % 16, chunk 4 ks + l / 16) is served 16 lanes per cycle over the 64 banks, lanes
+// l and l + 16 together: the chunk position varies with the row's bits 1..2 (XORed into chunk bits 0..1 of a
+// 64-byte row, bits 1..2 of a 128-byte row, whose bit 0 of the row already selects the half of the bank cycle),
+// which spreads the rows of a fragment over all banks.
+template <int CPR>
+__device__ __forceinline__ int swz16(int row, int chunk) {
+  return (row * CPR + (chunk ^ (((row >> 1) & 3) << (CPR == 8 ? 1 : 0)))) * 8;
+}
 
-template <int MT, int NF, int EPI, bool LO = true>
+template <int MT, int NF, int EPI, bool LO = true, int KSUB = 1>
 __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
-  constexpr int BM = 16 * MT, BN = 64 * NF, BK = 32;
+  // KSUB MFMA K steps per stage and barrier (BK = 32 KSUB).  KSUB = 2, for the short tiles whose three stages still
+  // fit: half the barriers and full 128-byte rows per copy (half the requests to L2 for the same bytes).
+  constexpr int BM = 16 * MT, BN = 64 * NF, BK = 32 * KSUB;
+  constexpr int CPR = BK / 8, RPI = 64 / CPR;    // 16-byte chunks per tile row; tile rows per copy instruction
+  static_assert(KSUB == 1 || KSUB == 2, "one or two MFMA K steps per stage");
   static_assert(NF == 2 || NF == 4, "SwiGLU pairs the fragments (gate, up): NF must be even");
   static_assert(MT >= 1 && MT <= 17, "accumulators: 4 NF MT registers per lane, stages: 3 (2 BM + BN) x 64 B of LDS");
   constexpr int TERMS = LO ? 2 : 1;              // activation terms: (hi, lo), or hi alone (LO = false: the low part is
                                                  // neither copied nor multiplied; 11 mantissa bits, half the MFMAs)
-  constexpr int A_INS = TERMS * MT;              // copy instructions (16 tile rows each) for [A_hi | A_lo]
+  constexpr int A_INS = TERMS * BM / RPI;        // copy instructions (RPI tile rows = 1 KB each) for [A_hi | A_lo]
   constexpr int A_IPW = (A_INS + 3) / 4;         // per wavefront; a surplus one repeats the last group
-  constexpr int W_IPW = BN / 16 / 4;
+  constexpr int W_IPW = BN / RPI / 4;
   constexpr int IPW = A_IPW + W_IPW;
   constexpr int R = TERMS * BM + BN;
-  constexpr int CVT_RB = LO ? 4 : 8;             // row blocks whose MFMAs give the 16 NF conversion instructions cover
-  constexpr int C_END = MT > CVT_RB ? MT - CVT_RB : 1;   // the copies of step s+2 go out during row blocks 0 .. C_END-1
+  static_assert(3 * R * BK * 2 <= 163840, "three stages of (TERMS BM + BN) rows must fit the 160 KB of LDS");
+  // The K loop walks MV = MT KSUB "row blocks": row block i at K sub-step ks, ks fastest.
+  constexpr int MV = MT * KSUB;
+  constexpr int CVT_RB = (LO ? 4 : 8) * KSUB;    // row blocks whose MFMAs give the 16 NF KSUB conversion instructions cover
+  constexpr int C_END = MV > CVT_RB ? MV - CVT_RB : 1;   // the copies of step s+2 go out during row blocks 0 .. C_END-1
   constexpr int CPB = (IPW + C_END - 1) / C_END; // copies per row block
   constexpr int SLOTS = TERMS * NF;              // MFMAs per row block
+  constexpr int NW = KSUB * NF;                  // weight fragments of a stage per wavefront
   __shared__ __attribute__((aligned(16))) uint16_t st0[R * BK];
   __shared__ __attribute__((aligned(16))) uint16_t st1[R * BK];
   __shared__ __attribute__((aligned(16))) uint16_t st2[R * BK];
@@ -103,15 +118,15 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
   uint32_t dst[IPW];                             // byte offset of the copy's 16 rows inside a stage
 #pragma unroll
   for (int j = 0; j < IPW; ++j) {
-    int grp;                                     // 16-row group of the stage
+    int grp;                                     // group of RPI rows of the stage
     if (j < A_IPW) {
       grp = wave + 4 * j;
       grp = grp < A_INS ? grp : A_INS - 1;       // same bytes to the same place: harmless
     } else {
       grp = A_INS + wave * W_IPW + (j - A_IPW);
     }
-    const int r = grp * 16 + lane / 4;
-    const int ch = (lane % 4) ^ ((r >> 1) & 3);
+    const int r = grp * RPI + lane / CPR;
+    const int ch = (lane % CPR) ^ (((r >> 1) & 3) << (CPR == 8 ? 1 : 0));
     const uint16_t* base;
     if (r < TERMS * BM) {
       int am = m0 + (r < BM ? r : r - BM);
@@ -139,7 +154,7 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
       base = wbase + (size_t)wrow * K;
     }
     src[j] = base + (size_t)step_begin * BK + ch * 8;
-    dst[j] = grp * 16 * BK * 2;
+    dst[j] = grp * 1024;
   }
 
   f32x4 acc[MT][NF];
@@ -149,8 +164,12 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
     for (int j = 0; j < NF; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int l16 = lane & 15, kc = lane >> 4;
-  const int a_off = swz16(l16, kc);                               // + i * 16 rows; + BM rows: lo
-  const int w_off = TERMS * BM * BK + swz16(wave * 16 * NF + l16, kc);   // + j * 16 rows
+  int a_off[KSUB], w_off[KSUB];                                   // per K sub-step; + i * 16 rows (+ BM rows: lo), + j * 16 rows
+#pragma unroll
+  for (int ks = 0; ks < KSUB; ++ks) {
+    a_off[ks] = swz16<CPR>(l16, 4 * ks + kc);
+    w_off[ks] = TERMS * BM * BK + swz16<CPR>(wave * 16 * NF + l16, 4 * ks + kc);
+  }
   // bf16 pair -> fp16 pair: exponent raised on both halves at once, each half widened to fp32 (a shift, a mask),
   // and the two packed again (exact: 8 mantissa bits into 11).  A zero becomes 2^(SY_W_SHIFT - 127) in fp32 and
   // goes back to zero in the packing.
@@ -175,7 +194,7 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
 // (raise the exponents; low half to fp32; high half to fp32, in place; pack), register P % 4.  Consecutive
 // operations touch different registers: no instruction waits for the one before it.
 #define SY_CVT_OP(P_)                                                                             \
-  if ((P_) < 16 * NF) {                                                                           \
+  if ((P_) < 16 * NW) {                                                                           \
     uint32_t x_ = fwn[(P_) / 16][(P_) % 4];                                                       \
     if (((P_) % 16) / 4 == 0) asm volatile("v_add_u32 %0, %1, %0" : "+v"(x_) : "s"(exp_add));     \
     else if (((P_) % 16) / 4 == 1) asm volatile("v_lshlrev_b32 %0, 16, %1" : "=v"(tq[(P_) % 4]) : "v"(x_)); \
@@ -188,41 +207,42 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
 #define SY_NEXT_W(NEXTSTAGE)                                                                      \
   {                                                                                               \
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IPW) : "memory");                                    \
-    _Pragma("unroll") for (int j = 0; j < NF; ++j)                                                \
-        fwn[j] = *reinterpret_cast<const u32x4*>(NEXTSTAGE + w_off + j * 16 * BK);                \
+    _Pragma("unroll") for (int j = 0; j < NW; ++j)                                                \
+        fwn[j] = *reinterpret_cast<const u32x4*>(NEXTSTAGE + w_off[j / NF] + (j % NF) * 16 * BK); \
   }
 // One K step on the stage CUR with this step's weight fragments fw already converted in registers.  The copies
 // of step s+2 go out during the first row blocks; during the last four the weights of step s+1 (NEXTSTAGE) are
 // read and converted, two instructions after each MFMA, in the shadow of the matrix core.
+#define SY_AT(V_) (a_off[(V_) % KSUB] + ((V_) / KSUB) * 16 * BK)
 #define SY_MULT(STAGE, NXT, NSTEP, NEXTSTAGE)                                                     \
   {                                                                                               \
-    u32x4 fa[MT + 2], fl[MT + 2], fwn[NF];                                                        \
+    u32x4 fa[MV + 2], fl[MV + 2], fwn[NW];                                                        \
     uint32_t tq[4];                                                                               \
-    _Pragma("unroll") for (int i = 0; i < 2 && i < MT; ++i) {                                     \
-      fa[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + i * 16 * BK);                       \
-      if (LO) fl[i] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + i * 16) * BK);        \
+    _Pragma("unroll") for (int v = 0; v < 2 && v < MV; ++v) {                                     \
+      fa[v] = *reinterpret_cast<const u32x4*>(STAGE + SY_AT(v));                                  \
+      if (LO) fl[v] = *reinterpret_cast<const u32x4*>(STAGE + SY_AT(v) + BM * BK);                \
     }                                                                                             \
     __builtin_amdgcn_sched_barrier(0);                                                            \
-    _Pragma("unroll") for (int i = 0; i < MT; ++i) {                                              \
-      if (i == C_END) SY_NEXT_W(NEXTSTAGE)                                                        \
+    _Pragma("unroll") for (int v = 0; v < MV; ++v) {                                              \
+      if (v == C_END) SY_NEXT_W(NEXTSTAGE)                                                        \
       _Pragma("unroll") for (int t = 0; t < SLOTS; ++t) {                                         \
-        if (t < NF) SY_MFMA(acc[i][t], fw[t], fa[i], i)                                           \
-        else SY_MFMA(acc[i][t - NF], fw[t - NF], fl[i], i)                                        \
-        if (i >= C_END) {                                                                         \
-          SY_CVT_OP(((i - C_END) * SLOTS + t) * 2)                                                \
-          SY_CVT_OP(((i - C_END) * SLOTS + t) * 2 + 1)                                            \
+        if (t < NF) SY_MFMA(acc[v / KSUB][t], fw[(v % KSUB) * NF + t], fa[v], v / KSUB)           \
+        else SY_MFMA(acc[v / KSUB][t - NF], fw[(v % KSUB) * NF + t - NF], fl[v], v / KSUB)        \
+        if (v >= C_END) {                                                                         \
+          SY_CVT_OP(((v - C_END) * SLOTS + t) * 2)                                                \
+          SY_CVT_OP(((v - C_END) * SLOTS + t) * 2 + 1)                                            \
         }                                                                                         \
-        if (t == 0 && i + 2 < MT) fa[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (i + 2) * 16 * BK); \
-        if (LO && t == NF && i + 2 < MT)                                                          \
-          fl[i + 2] = *reinterpret_cast<const u32x4*>(STAGE + a_off + (BM + (i + 2) * 16) * BK);  \
+        if (t == 0 && v + 2 < MV) fa[v + 2] = *reinterpret_cast<const u32x4*>(STAGE + SY_AT(v + 2)); \
+        if (LO && t == NF && v + 2 < MV)                                                          \
+          fl[v + 2] = *reinterpret_cast<const u32x4*>(STAGE + SY_AT(v + 2) + BM * BK);            \
         _Pragma("unroll") for (int c = 0; c < CPB; ++c)                                           \
-            if ((c + 1) % SLOTS == t && i < C_END && i * CPB + c < IPW) SY_COPY(i * CPB + c, NXT, NSTEP) \
+            if ((c + 1) % SLOTS == t && v < C_END && v * CPB + c < IPW) SY_COPY(v * CPB + c, NXT, NSTEP) \
         __builtin_amdgcn_sched_barrier(0);                                                        \
       }                                                                                           \
     }                                                                                             \
-    if (C_END >= MT) SY_NEXT_W(NEXTSTAGE)                                                         \
-    _Pragma("unroll") for (int p = (MT > C_END ? (MT - C_END) * 2 * SLOTS : 0); p < 16 * NF; ++p) SY_CVT_OP(p) \
-    _Pragma("unroll") for (int j = 0; j < NF; ++j) fw[j] = fwn[j];                                \
+    if (C_END >= MV) SY_NEXT_W(NEXTSTAGE)                                                         \
+    _Pragma("unroll") for (int p = (MV > C_END ? (MV - C_END) * 2 * SLOTS : 0); p < 16 * NW; ++p) SY_CVT_OP(p) \
+    _Pragma("unroll") for (int j = 0; j < NW; ++j) fw[j] = fwn[j];                                \
   }
 // CUR holds step s; NXT (the stage read in step s-1) receives step s+2.  Past the end the last step is copied
 // again (never used): exactly one younger copy group is then always in flight, so the wait count is a constant
@@ -243,12 +263,12 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
     SY_ISSUE(l1, one_)
   }
   // the first step's weights: own copies of stage 0 have landed once at most the IPW younger ones are in flight
-  u32x4 fw[NF];
+  u32x4 fw[NW];
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IPW) : "memory");
 #pragma unroll
-  for (int j = 0; j < NF; ++j) fw[j] = *reinterpret_cast<const u32x4*>(st0 + w_off + j * 16 * BK);
+  for (int j = 0; j < NW; ++j) fw[j] = *reinterpret_cast<const u32x4*>(st0 + w_off[j / NF] + (j % NF) * 16 * BK);
 #pragma unroll
-  for (int j = 0; j < NF; ++j)
+  for (int j = 0; j < NW; ++j)
 #pragma unroll
     for (int q = 0; q < 4; ++q) SY_CVT1(fw[j], q)
   int s = 0;
@@ -272,6 +292,7 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
 #undef SY_CVT_OP
 #undef SY_NEXT_W
 #undef SY_MULT
+#undef SY_AT
 #undef SY_STEP
   // The surplus copies of the last steps are still in flight: let them land before the block's LDS is released;
   // MFMA results settle before they are read.  The empty statements "rewrite" each accumulator: every later read
@@ -326,20 +347,21 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
   }
 }
 
-template <int MT, int NF>
+template <int MT, int NF, int KSUB = 1>
 static hipError_t launch_proj(const GemmArgs& g, hipStream_t s) {
   constexpr int BM = 16 * MT;
   const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / (64 * NF);
   const dim3 grid(8 * ((n_tiles + 7) / 8) * m_tiles, 1, g.split_k);
+  if (g.K % (32 * KSUB) != 0) return hipErrorInvalidValue;
   if (!g.a_lo) {                                 // single-term activations: the plain store form only
     if (g.epilogue != GEMM_STORE_F32) return hipErrorInvalidValue;
-    proj_kernel<MT, NF, GEMM_STORE_F32, false><<<grid, 256, 0, s>>>(g);
+    proj_kernel<MT, NF, GEMM_STORE_F32, false, KSUB><<<grid, 256, 0, s>>>(g);
     return hipGetLastError();
   }
   switch (g.epilogue) {
-    case GEMM_STORE_F32: proj_kernel<MT, NF, GEMM_STORE_F32><<<grid, 256, 0, s>>>(g); break;
-    case GEMM_ADD_F32: proj_kernel<MT, NF, GEMM_ADD_F32><<<grid, 256, 0, s>>>(g); break;
-    case GEMM_SWIGLU: proj_kernel<MT, NF, GEMM_SWIGLU><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_STORE_F32: proj_kernel<MT, NF, GEMM_STORE_F32, true, KSUB><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_ADD_F32: proj_kernel<MT, NF, GEMM_ADD_F32, true, KSUB><<<grid, 256, 0, s>>>(g); break;
+    case GEMM_SWIGLU: proj_kernel<MT, NF, GEMM_SWIGLU, true, KSUB><<<grid, 256, 0, s>>>(g); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

@@ -17,12 +17,17 @@ def test_headline_batch_plans():
     assert synera.debug_gemm_plan(T, 2 * F, D, SWIGLU) == (272, 256, 1)
     assert synera.debug_gemm_plan(T, D, F, ADD) == (272, 256, 8)
     assert synera.debug_gemm_plan(T, VOCAB, D, STORE, stored_slices=False) == (272, 256, 1)
+    for n, k, e in ((QKV, D, STORE), (D, D, ADD), (2 * F, D, SWIGLU), (D, F, ADD)):
+        assert synera.debug_gemm_plan_bk(T, n, k, e) == 32          # the tall tiles fill the LDS with 64-byte rows
 
 
 def test_small_batches_take_the_narrow_tiles():
-    """About 140 rows: 128-column tiles double the blocks that stream the weights."""
+    """About 140 rows: 128-column tiles double the blocks that stream the weights, and those tiles are short
+    enough for two MFMA K steps per stage (half the barriers, full 128-byte rows per copy)."""
     for n, k, e in ((QKV, D, STORE), (D, D, ADD), (2 * F, D, SWIGLU), (D, F, ADD)):
         assert synera.debug_gemm_plan(144, n, k, e)[1] == 128
+        assert synera.debug_gemm_plan_bk(144, n, k, e) == 64
+        assert synera.debug_gemm_plan_bk(128, n, k, e) == 64
 
 
 def test_decode_sized_batches_use_tiles_of_their_own_height_and_never_atomics():
@@ -46,6 +51,10 @@ def test_plans_are_launchable(M, N, K, epi, stored):
     if epi == SWIGLU:
         assert split == 1
     assert split <= 8                           # SYNERA_MAX_GEMM_SLICES
+    bk = synera.debug_gemm_plan_bk(M, N, K, epi, stored)
+    assert bk in (32, 64) and K % bk == 0
+    if bk == 64:                                # three stages of (2 bm + bn) rows of 128 bytes fit the 160 KB of LDS
+        assert 3 * (2 * bm + bn) * 128 <= 163840
     if not stored:
         assert split == 1
 

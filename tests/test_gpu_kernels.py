@@ -201,7 +201,7 @@ def test_pair_carries_22_bits_and_weights_of_any_magnitude_below_256_are_exact()
     assert (c[:, 0] == 0).all()
 
 
-@pytest.mark.parametrize("tile", [-1, 1, 5, 8, 9, 12, 17, 103, 112])
+@pytest.mark.parametrize("tile", [-1, 1, 5, 8, 9, 12, 17, 103, 112, 201, 205, 301, 309])
 @pytest.mark.parametrize("M,N,K", [(1, 256, 64), (97, 512, 1024), (532, 1024, 4096), (545, 1792, 512), (272, 32000, 256)])
 def test_gemm_on_the_high_part_alone(tile, M, N, K):
     """The single-term form (the LM head's): exactly the product of the fp16 high part with the weights."""
@@ -219,8 +219,9 @@ def test_gemm_on_the_high_part_alone(tile, M, N, K):
     assert (c.double() - want).abs().max().item() < 6e-9 * K + 2e-7
 
 
-# tiles: rows / 16 (1..17) with 256 columns, 100 + rows / 16 (1..12) with 128 columns; -1 = the planner's choice
-@pytest.mark.parametrize("tile", [-1] + list(range(1, 18)) + list(range(101, 113)))
+# tiles: rows / 16 (1..17) with 256 columns, 100 + rows / 16 (1..12) with 128 columns, + 200 for two MFMA K steps
+# per stage (256 columns: 1..5, 128 columns: 1..9); -1 = the planner's choice
+@pytest.mark.parametrize("tile", [-1] + list(range(1, 18)) + list(range(101, 113)) + list(range(201, 206)) + list(range(301, 310)))
 @pytest.mark.parametrize("M,N,K", [(1, 256, 64), (97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (600, 4096, 1792),
                                    (532, 1792, 1024), (97, 1792, 320), (545, 1792, 512)])
 def test_gemm_every_tile_and_epilogue(tile, M, N, K):
@@ -260,7 +261,7 @@ def test_gemm_every_tile_and_epilogue(tile, M, N, K):
     assert ((got - glu).abs() - bound).max().item() < 0
 
 
-@pytest.mark.parametrize("tile", [-1, 4, 8, 9, 13, 17, 104, 108, 112])
+@pytest.mark.parametrize("tile", [-1, 4, 8, 9, 13, 17, 104, 108, 112, 204, 205, 304, 308, 309])
 @pytest.mark.parametrize("M,N,K", [(97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (545, 4096, 1792), (532, 1792, 2048),
                                    (24, 1792, 4096)])
 def test_gemm_stored_k_slices_sum_to_the_product(tile, M, N, K):
