@@ -55,8 +55,9 @@ def plan_fingerprint(synera, shape, b, T):
     for name, n, k, epi, stored in (("qkv", qkv, d, 0, True), ("o", d, shape.q_dim, 1, True), ("gate_up", 2 * f, d, 2, True),
                                     ("down", d, f, 1, True), ("lm_head", V, d, 0, False)):
         bm, bn, split = synera.debug_gemm_plan(T, n, k, epi, stored)
-        k64 = "k64" if synera.debug_gemm_plan_bk(T, n, k, epi, stored) == 64 else ""      # two MFMA K steps per stage
-        parts.append(f"{name}={bm}x{bn}{k64}/{split}")
+        # two MFMA K steps per stage, or one with the layers' activation pairs as one array of whole lines
+        form = "k64" if synera.debug_gemm_plan_bk(T, n, k, epi, stored) == 64 else ("pair" if stored else "")
+        parts.append(f"{name}={bm}x{bn}{form}/{split}")
     plan = synera.debug_attention_plan(shape, 512, b["ctx_len"], np.zeros(len(b["ctx_len"]), np.int32), b["n_draft"],
                                        b["block_table"])
     parts.append(f"attention={len(plan['shares'])}sh/{len(plan['prog'])}pos/{len(plan['cuts'])}cut")

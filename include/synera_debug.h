@@ -165,6 +165,17 @@ int32_t synera_debug_gemm_epilogue(const void* d_a, const void* d_a_lo, const vo
                                    void* stream);
 
 /*
+ * Test hook: synera_debug_gemm_epilogue with the activation pair in the form the decoder layers hand it over in
+ * where a stage of the kernel holds one 32-wide K block: one fp16 array d_a_pairs [M][K / 32][64], the 32 high
+ * parts of a K block followed by its 32 low parts (a copy then moves whole 128-byte lines).  Epilogues 0 and 1 as
+ * above; epilogue 2 writes its output pair in the same form into d_c (fp16 [M][N / 64][64]).  Any tile forced
+ * with synera_debug_set_gemm_tile that has 64-wide stages (variant >= 200) is ignored: the planner chooses.
+ * All pointers device.
+ */
+int32_t synera_debug_gemm_paired(const void* d_a_pairs, const void* d_w0, const void* d_w1, void* d_c, int32_t M,
+                                 int32_t N, int32_t K, int32_t epilogue, void* stream);
+
+/*
  * Test hook: the store-form projection GEMM (epilogue 0 above) in the mode the decoder layers run it in:
  * when the tile planner splits K, slice s of the product is stored to d_parts[s][M][N] (f32) for the
  * consumer kernel to add, in a fixed order and without atomics.  d_parts must hold SYNERA_MAX_GEMM_SLICES
@@ -179,7 +190,10 @@ int32_t synera_debug_gemm_slices(const void* d_a, const void* d_a_lo, const void
  * verify left it, to caller device memory.  which: 0 residual x (f32 [T][d]; when the last
  * down projection ran K-split, its slices have been added only to the rows the LM head reads), 1/2 rotated q
  * hi/lo (bf16 [T][Hq*h]), 3/4 attention output hi/lo (fp16 [T][Hq*h], scaled by 64), 5/6 SiLU*mul output
- * hi/lo (fp16 [T][f], scaled by 8).  Errors: EINVAL, ENOSPC (bytes beyond the buffer), EHIP.
+ * hi/lo (fp16 [T][f], scaled by 8).  Where the projection that reads such a pair takes it as one array
+ * (synera_debug_gemm_paired's form: its plan has 32-wide stages and no low part is switched off), buffers 3 + 4
+ * (5 + 6), which lie back to back, hold that array instead: [T][n / 32][hi 32 | lo 32], read from `which` 3 (5)
+ * on.  Errors: EINVAL, ENOSPC (bytes beyond the buffer), EHIP.
  */
 int32_t synera_debug_read_scratch(synera_ctx* ctx, int32_t which, void* d_dst, int64_t bytes, void* stream);
 

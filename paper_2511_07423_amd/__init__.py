@@ -7,7 +7,7 @@ importing the binding without the built library raises.
 """
 _EXPORTS = (
     "SyneraError", "Verifier", "confidence", "confidence_topk", "nucleus", "topp_count", "chunk_dispatch", "gemm_pair", "gemm_pair_static", "STATIC_GEMM_MAX_OUT", "split_pair", "LO_SITES",
-    "debug_set_gemm_tile", "debug_gemm_epilogue", "debug_gemm_slices", "debug_gemm_plan", "debug_gemm_plan_bk", "debug_attention_plan", "measure_hbm_copy", "measure_hbm_read", "MEASURE_READ_BLOCKS", "measure_mfma_bf16", "measure_mfma_f16",
+    "debug_set_gemm_tile", "debug_gemm_epilogue", "debug_gemm_paired", "debug_gemm_slices", "debug_gemm_plan", "debug_gemm_plan_bk", "debug_attention_plan", "measure_hbm_copy", "measure_hbm_read", "MEASURE_READ_BLOCKS", "measure_mfma_bf16", "measure_mfma_f16",
     "validate_batch", "version", "lib_path", "Scheduler", "SCHED_IDLE", "SCHED_PREFILL", "SCHED_VERIFY",
     "OK", "EINVAL", "ERANGE", "ENOSPC", "EUNSUP", "EHIP", "ENOMEM", "PAGE_SIZE", "MAX_CHUNK", "STAGES",
 )

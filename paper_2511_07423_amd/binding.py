@@ -110,6 +110,8 @@ _lib.synera_debug_gemm_plan.restype = C.c_int32
 _lib.synera_debug_gemm_plan.argtypes = [C.c_int32] * 5 + [C.POINTER(C.c_int32)] * 3
 _lib.synera_debug_gemm_plan_bk.restype = C.c_int32
 _lib.synera_debug_gemm_plan_bk.argtypes = [C.c_int32] * 5 + [C.POINTER(C.c_int32)]
+_lib.synera_debug_gemm_paired.restype = C.c_int32
+_lib.synera_debug_gemm_paired.argtypes = [_vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp]
 _lib.synera_debug_gemm_epilogue.restype = C.c_int32
 _lib.synera_debug_gemm_epilogue.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp]
 
@@ -273,6 +275,17 @@ def debug_gemm_epilogue(a, a_lo, w0, w1, c, c_lo, epilogue):
                                          _dev(w1, torch.bfloat16), c.data_ptr(), c_lo.data_ptr() if c_lo is not None else None,
                                          M, N, K, epilogue, _stream())
     _check(st, "synera_debug_gemm_epilogue")
+
+
+def debug_gemm_paired(a_pairs, w0, w1, c, epilogue):
+    """Test hook: debug_gemm_epilogue with the activation pair as one array [M][K / 32][64] (32 high parts, then
+    the 32 low parts of the same K block); epilogue 2 writes c in that form too ([M][N / 64][64])."""
+    M = a_pairs.shape[0]
+    K = a_pairs[0].numel() // 2
+    N = w0.shape[0] * (2 if epilogue == 2 else 1)
+    st = _lib.synera_debug_gemm_paired(_dev(a_pairs, torch.float16), _dev(w0, torch.bfloat16), _dev(w1, torch.bfloat16),
+                                       c.data_ptr(), M, N, K, epilogue, _stream())
+    _check(st, "synera_debug_gemm_paired")
 
 
 def topp_count(topk_prob, top_p):

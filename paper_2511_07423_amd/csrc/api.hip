@@ -249,6 +249,8 @@ extern "C" int32_t synera_create(synera_ctx** out, const synera_model_desc* desc
   const size_t qkv_dim = (size_t)(qd + 2 * kd);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+  // Each (hi, lo) pair is taken back to back: where a projection reads its pair as one array (gemm_takes_pairs),
+  // that array starts at the high part's place and spans both.
   const size_t o_x = take(T * m.d_model * 4), o_y = take(T * m.d_model * 2), o_yl = take(T * m.d_model * 2);
   const size_t o_qkv = take(T * qkv_dim * 4);
   const size_t o_q = take(T * qd * 2), o_ql = take(T * qd * 2), o_o = take(T * qd * 2), o_ol = take(T * qd * 2);
@@ -572,15 +574,43 @@ static int32_t finish_call(synera_ctx* c, const Plan& p, hipStream_t stream) {
   return SYNERA_OK;
 }
 
-// One projection.  a / a_lo: the fp16 pair of a_scale x activation.  parts / n_parts: if given, the planner may
+// The planner's view of a projection of M rows (host only: the pointers are only asked whether they are there).
+static int32_t plan_args(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices, GemmArgs* g) {
+  if (M < 1 || N < 1 || K < 1 || epilogue < 0 || epilogue > 2) return SYNERA_EINVAL;
+  if (N % (epilogue == GEMM_SWIGLU ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
+  *g = GemmArgs{};
+  g->a_lo = reinterpret_cast<const uint16_t*>(uintptr_t(64));
+  g->w_rows[0] = epilogue == GEMM_SWIGLU ? N / 2 : N;
+  g->w_rows[1] = epilogue == GEMM_SWIGLU ? N / 2 : 0;
+  g->M = M;
+  g->N = N;
+  g->K = K;
+  g->epilogue = epilogue;
+  g->split_k = 1;
+  g->c_parts = stored_slices && epilogue != GEMM_SWIGLU ? reinterpret_cast<float*>(uintptr_t(64)) : nullptr;
+  return SYNERA_OK;
+}
+
+// Whether a two-term projection of M rows takes its activations as one paired array ([M][K / 32][hi | lo]: whole
+// 128-byte lines per copy): where its plan has one MFMA K step per stage.  The producer kernel is told the same.
+static bool gemm_takes_pairs(int M, int N, int K, int epi, bool stored) {
+  GemmArgs g;
+  return plan_args(M, N, K, epi, stored, &g) == SYNERA_OK && gemm_plan_bk(g) == 32;
+}
+
+// One projection.  a / a_lo: the fp16 pair of a_scale x activation; a_paired: both in the one array a
+// ([M][K / 32][hi 32 | lo 32]); c_paired (SwiGLU): the output pair in that form in cbuf.  parts / n_parts: if given, the planner may
 // split K; the slices are then stored to `parts` ([n][M][N], *n_parts = n) for the consumer kernel to add, and
 // cbuf is left alone; otherwise *n_parts = 0 and cbuf holds the result.
 static int32_t run_gemm(const uint16_t* a, const uint16_t* a_lo, float a_scale, const void* w0, int r0, const void* w1,
                         int r1, const void* w2, int r2, void* cbuf, void* cbuf_lo, int M, int N, int K, int epi,
-                        hipStream_t s, float* parts = nullptr, int* n_parts = nullptr) {
+                        hipStream_t s, float* parts = nullptr, int* n_parts = nullptr, bool a_paired = false,
+                        bool c_paired = false) {
   GemmArgs g;
   g.a = a;
-  g.a_lo = a_lo;
+  g.a_lo = a_paired ? nullptr : a_lo;
+  g.a_paired = a_paired;
+  g.c_paired = c_paired;
   g.c_lo = cbuf_lo;
   g.w[0] = static_cast<const bf16_t*>(w0);
   g.w[1] = static_cast<const bf16_t*>(w1);
@@ -642,6 +672,14 @@ static int32_t verify_launches(synera_ctx* c, const Plan& p, int32_t B, const in
   al.Hkv = Hkv;
   al.hd = hd;
 
+  // Which projections read their activation pair as one paired array (the producer writes it that way then).  The
+  // ablation of low parts works on separate arrays: any of its bits keeps them.
+  const bool pair_qkv = !lo_off && gemm_takes_pairs(T, qd + 2 * kd, d, GEMM_STORE_F32, true);
+  const bool pair_o = !lo_off && gemm_takes_pairs(T, d, qd, GEMM_ADD_F32, true);
+  const bool pair_gu = !lo_off && gemm_takes_pairs(T, 2 * m.d_ffn, d, GEMM_SWIGLU, true);
+  const bool pair_down = !lo_off && gemm_takes_pairs(T, d, m.d_ffn, GEMM_ADD_F32, true);
+  al.o_paired = pair_o;
+
   // K-split projections leave their slices in c->gparts; the kernel that reads the result next adds them
   // (RMSNorm for the two residual projections, RoPE for QKV).  pend = slices waiting to be added to x.
   int pend = 0;
@@ -653,14 +691,14 @@ static int32_t verify_launches(synera_ctx* c, const Plan& p, int32_t B, const in
     {
       StageTimer t(c, SYNERA_STAGE_NORM, s);
       HIP_TRY(launch_rmsnorm(c->x, c->gparts, pend, x_stride, static_cast<const bf16_t*>(w.attn_norm), nullptr, c->y,
-                             c->y_lo, T, d, m.rms_eps, (lo_off & LO_QKV_IN) != 0, s));
+                             c->y_lo, T, d, m.rms_eps, (lo_off & LO_QKV_IN) != 0, pair_qkv, s));
       pend = 0;
     }
     int qkv_parts = 0;
     {
       StageTimer t(c, SYNERA_STAGE_QKV, s);
       if ((st = run_gemm(c->y, c->y_lo, SY_Y_SCALE, w.wq, qd, w.wk, kd, w.wv, kd, c->qkv, nullptr, T, qd + 2 * kd, d,
-                         GEMM_STORE_F32, s, c->gparts, &qkv_parts)))
+                         GEMM_STORE_F32, s, c->gparts, &qkv_parts, pair_qkv)))
         return st;
     }
     {
@@ -678,26 +716,26 @@ static int32_t verify_launches(synera_ctx* c, const Plan& p, int32_t B, const in
     {
       StageTimer t(c, SYNERA_STAGE_O, s);
       if ((st = run_gemm(c->o, c->o_lo, SY_O_SCALE, w.wo, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d, qd,
-                         GEMM_ADD_F32, s, c->gparts, &pend)))
+                         GEMM_ADD_F32, s, c->gparts, &pend, pair_o)))
         return st;
     }
     {
       StageTimer t(c, SYNERA_STAGE_NORM, s);
       HIP_TRY(launch_rmsnorm(c->x, c->gparts, pend, x_stride, static_cast<const bf16_t*>(w.mlp_norm), nullptr, c->y,
-                             c->y_lo, T, d, m.rms_eps, (lo_off & LO_GATE_UP_IN) != 0, s));
+                             c->y_lo, T, d, m.rms_eps, (lo_off & LO_GATE_UP_IN) != 0, pair_gu, s));
       pend = 0;
     }
     {
       StageTimer t(c, SYNERA_STAGE_GATE_UP, s);
       if ((st = run_gemm(c->y, c->y_lo, SY_Y_SCALE, w.w_gate, 0, w.w_up, 0, nullptr, 0, c->act,
-                         c->act_lo, T, 2 * m.d_ffn, d, GEMM_SWIGLU, s)))
+                         c->act_lo, T, 2 * m.d_ffn, d, GEMM_SWIGLU, s, nullptr, nullptr, pair_gu, pair_down)))
         return st;
     }
     if (lo_off & LO_DOWN_IN) HIP_TRY(launch_fill_zero(reinterpret_cast<float*>(c->act_lo), (size_t)T * m.d_ffn / 2, s));
     {
       StageTimer t(c, SYNERA_STAGE_DOWN, s);
       if ((st = run_gemm(c->act, c->act_lo, SY_ACT_SCALE, w.w_down, d, nullptr, 0, nullptr, 0, c->x, nullptr, T, d,
-                         m.d_ffn, GEMM_ADD_F32, s, c->gparts, &pend)))
+                         m.d_ffn, GEMM_ADD_F32, s, c->gparts, &pend, pair_down)))
         return st;
     }
   }
@@ -706,7 +744,7 @@ static int32_t verify_launches(synera_ctx* c, const Plan& p, int32_t B, const in
   const bool extra = p.R_all > p.R;
   // (the last down projection's slices are added here, for the selected rows only)
   HIP_TRY(launch_rmsnorm(c->x, c->gparts, pend, x_stride, static_cast<const bf16_t*>(c->final_norm), p.meta.sel_rows,
-                         c->ysel, c->ysel_lo, p.R_all, d, m.rms_eps, (lo_off & LO_LM_HEAD_IN) != 0, s));
+                         c->ysel, c->ysel_lo, p.R_all, d, m.rms_eps, (lo_off & LO_LM_HEAD_IN) != 0, false, s));
   float* logits = (d_logits && !extra) ? d_logits : c->logits;
   {
     StageTimer t(c, SYNERA_STAGE_LM_HEAD, s);
@@ -973,7 +1011,7 @@ extern "C" int32_t synera_debug_read_scratch(synera_ctx* c, int32_t which, void*
     case 6: src = c->act_lo; cap = T * (int64_t)m.d_ffn * 2; break;
     default: return SYNERA_EINVAL;
   }
-  if (bytes > cap) return SYNERA_ENOSPC;
+  if (bytes > cap && !((which == 3 || which == 5) && bytes <= 2 * cap)) return SYNERA_ENOSPC;
   HIP_TRY(hipMemcpyAsync(d_dst, src, (size_t)bytes, hipMemcpyDeviceToDevice, static_cast<hipStream_t>(stream)));
   return SYNERA_OK;
 }
@@ -1045,23 +1083,6 @@ extern "C" int32_t synera_debug_attention_plan(const synera_model_desc* desc, in
   return st;
 }
 
-// The planner's view of a projection of M rows (host only: the pointers are only asked whether they are there).
-static int32_t plan_args(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices, GemmArgs* g) {
-  if (M < 1 || N < 1 || K < 1 || epilogue < 0 || epilogue > 2) return SYNERA_EINVAL;
-  if (N % (epilogue == GEMM_SWIGLU ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
-  *g = GemmArgs{};
-  g->a_lo = reinterpret_cast<const uint16_t*>(uintptr_t(64));
-  g->w_rows[0] = epilogue == GEMM_SWIGLU ? N / 2 : N;
-  g->w_rows[1] = epilogue == GEMM_SWIGLU ? N / 2 : 0;
-  g->M = M;
-  g->N = N;
-  g->K = K;
-  g->epilogue = epilogue;
-  g->split_k = 1;
-  g->c_parts = stored_slices && epilogue != GEMM_SWIGLU ? reinterpret_cast<float*>(uintptr_t(64)) : nullptr;
-  return SYNERA_OK;
-}
-
 extern "C" int32_t synera_debug_gemm_plan(int32_t M, int32_t N, int32_t K, int32_t epilogue, int32_t stored_slices,
                                           int32_t* h_tile_rows, int32_t* h_tile_cols, int32_t* h_k_slices) {
   if (!h_tile_rows || !h_tile_cols || !h_k_slices) return SYNERA_EINVAL;
@@ -1096,6 +1117,17 @@ extern "C" int32_t synera_debug_gemm_epilogue(const void* d_a, const void* d_a_l
   return run_gemm(static_cast<const uint16_t*>(d_a), static_cast<const uint16_t*>(d_a_lo), 1.0f, d_w0, glu ? N / 2 : N,
                   glu ? d_w1 : nullptr, glu ? N / 2 : 0, nullptr, 0, d_c, d_c_lo, M, N, K, epilogue,
                   static_cast<hipStream_t>(stream));
+}
+
+extern "C" int32_t synera_debug_gemm_paired(const void* d_a_pairs, const void* d_w0, const void* d_w1, void* d_c,
+                                            int32_t M, int32_t N, int32_t K, int32_t epilogue, void* stream) {
+  if (!d_a_pairs || !d_w0 || !d_c || M < 1 || N < 1 || K < 1 || epilogue < 0 || epilogue > 2) return SYNERA_EINVAL;
+  if (epilogue == GEMM_SWIGLU && !d_w1) return SYNERA_EINVAL;
+  if (N % (epilogue == GEMM_SWIGLU ? 256 : 128) != 0 || K % 64 != 0) return SYNERA_EUNSUP;
+  const bool glu = epilogue == GEMM_SWIGLU;
+  return run_gemm(static_cast<const uint16_t*>(d_a_pairs), nullptr, 1.0f, d_w0, glu ? N / 2 : N, glu ? d_w1 : nullptr,
+                  glu ? N / 2 : 0, nullptr, 0, d_c, nullptr, M, N, K, epilogue, static_cast<hipStream_t>(stream),
+                  nullptr, nullptr, true, glu);
 }
 
 static_assert(SYNERA_MAX_GEMM_SLICES == SY_MAX_K_SLICES, "header and planner disagree on the slice limit");

@@ -63,6 +63,18 @@ __device__ __forceinline__ void store_pair(uint16_t* hi, uint16_t* lo, float a, 
   *reinterpret_cast<uint2*>(lo) = lo_off ? make_uint2(0u, 0u) : l;
 }
 
+// Four consecutive outputs of token row `tok`, columns col .. col + 3 of its Hq x hd values: to the two arrays of
+// the pair, or (o_paired) to the one array [T][Hq hd / 32][hi 32 | lo 32] the output projection then reads.
+__device__ __forceinline__ void store_o(const AttnLaunch& a, size_t tok, int col, float v0, float v1, float v2, float v3) {
+  const size_t width = (size_t)a.Hq * a.hd;
+  if (a.o_paired) {
+    uint16_t* at = a.o + tok * 2 * width + pair_col(col);
+    store_pair(at, at + 32, v0, v1, v2, v3, (a.lo_off & 2) != 0);
+  } else {
+    store_pair(a.o + tok * width + col, a.o_lo + tok * width + col, v0, v1, v2, v3, (a.lo_off & 2) != 0);
+  }
+}
+
 // Asynchronous 16-byte-per-lane copy global -> LDS; lane i lands at lds_addr + 16 i (m0 carries the
 // wavefront-uniform LDS address).
 __device__ __forceinline__ void copy_to_lds(const void* gptr, uint32_t lds_addr) {
@@ -416,11 +428,11 @@ __device__ __forceinline__ void attn_body(const AttnLaunch& a, const int pos_beg
     if (kp == 0 && row < u_nrows) {
       if (u_part < 0) {
         const float inv = 1.0f / l_run;
-        const size_t at = ((size_t)(u_tok0 + row / G) * Hq + u_kh * G + row % G) * HD + 4 * g;
+        const size_t tok = (size_t)(u_tok0 + row / G);
+        const int col = (u_kh * G + row % G) * HD + 4 * g;
 #pragma unroll
         for (int db = 0; db < DB; ++db)
-          store_pair(a.o + at + db * 16, a.o_lo + at + db * 16, acc[db][0] * inv, acc[db][1] * inv,
-                     acc[db][2] * inv, acc[db][3] * inv, (a.lo_off & 2) != 0);
+          store_o(a, tok, col + db * 16, acc[db][0] * inv, acc[db][1] * inv, acc[db][2] * inv, acc[db][3] * inv);
         if (a.row_ml && g == 0)
           a.row_ml[(size_t)(u_tok0 + row / G) * Hq + u_kh * G + row % G] = make_float2(m_fin, l_run);
       } else {
@@ -462,8 +474,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnLaunch a) {
       l += w * ml.y;
     }
     const float inv = 1.0f / l;
-    const size_t at = ((size_t)(c.tok0 + row / G) * Hq + c.kh * G + row % G) * HD + d4;
-    store_pair(a.o + at, a.o_lo + at, sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv, (a.lo_off & 2) != 0);
+    store_o(a, (size_t)(c.tok0 + row / G), (c.kh * G + row % G) * HD + d4, sum.x * inv, sum.y * inv, sum.z * inv, sum.w * inv);
     if (a.row_ml && d4 == 0) a.row_ml[(size_t)(c.tok0 + row / G) * Hq + c.kh * G + row % G] = make_float2(M, l);
   }
 }

@@ -58,10 +58,11 @@ hipError_t launch_embed(const bf16_t* embed, const int32_t* tokens, float* x, in
                         hipStream_t s);
 // parts / n_parts: pending K-split slices [n_parts][T][d] of the projection that feeds the residual; the
 // kernel adds them to x first (and writes x back), so the GEMM needs no atomics.  n_parts = 0: none.
-// y_hi / y_lo: the normalised rows as an fp16 pair scaled by SY_Y_SCALE (lo_off: the low part is written as zeros).
+// y_hi / y_lo: the normalised rows as an fp16 pair scaled by SY_Y_SCALE (lo_off: the low part is written as zeros);
+// paired: the pair goes to y_hi as one array [rows][d / 32][hi 32 | lo 32] (y_lo unused).
 hipError_t launch_rmsnorm(float* x, const float* parts, int n_parts, size_t part_stride, const bf16_t* gain,
                           const int32_t* rows, uint16_t* y_hi, uint16_t* y_lo, int n_rows, int d, float eps,
-                          bool lo_off, hipStream_t s);
+                          bool lo_off, bool paired, hipStream_t s);
 hipError_t launch_rope_table(const BatchMeta& m, float2* cs, int T, int head_dim, float base, hipStream_t s);
 // n_parts > 0: qkv points at K-split slices [n_parts][T][(Hq+2Hkv) hd] whose sum is the projection.
 hipError_t launch_rope_append(const float* qkv, int n_parts, size_t part_stride, const float2* cs, const BatchMeta& m,
@@ -135,6 +136,7 @@ struct AttnLaunch {
   float* part_ml;            // [slots][64][2]
   uint16_t* o;               // [T][Hq][hd], high part of the output's fp16 pair (scaled by SY_O_SCALE)
   uint16_t* o_lo;            // low part
+  bool o_paired;             // write the pair to o as one array [T][Hq hd / 32][hi 32 | lo 32] instead (o_lo unused)
   int32_t lo_off;            // ablation: bit 0 drops the low part of the probabilities, bit 1 writes o_lo as zeros
   float2* row_ml;            // optional [T][Hq]: per query row the softmax reference m (exponent-2 domain) and
                              // the sum l of 2^(s - m) over its keys, i.e. p(key) = 2^(s scale log2e - m) / l
@@ -169,8 +171,9 @@ hipError_t launch_importance_dispatch(const float* importance, const int32_t* cu
 // ---------------------------------------------------------------- gemm.hip
 enum GemmEpilogue { GEMM_STORE_F32 = 0, GEMM_ADD_F32 = 1, GEMM_SWIGLU = 2 };
 struct GemmArgs {
-  const uint16_t* a;     // [M][K], high part of the activation's fp16 pair
-  const uint16_t* a_lo;  // [M][K], low part; nullptr (STORE only): the high part alone is multiplied
+  const uint16_t* a;     // [M][K], high part of the activation's fp16 pair -- or, with a_paired, the whole pair as
+                         // [M][K / 32][hi 32 | lo 32] (a_lo unused)
+  const uint16_t* a_lo;  // [M][K], low part; nullptr without a_paired (STORE only): the high part alone is multiplied
   const bf16_t* w[3];    // up to three row segments of the bf16 weight (each [rows][K])
   int32_t w_rows[3];     // rows per segment (multiples of the N tile); unused = 0
   void* c;               // f32 [M][N] (STORE/ADD) or the high part of an fp16 pair [M][N/2] (SWIGLU: w[0] = gate, w[1] = up)
@@ -182,7 +185,11 @@ struct GemmArgs {
   float* c_parts;        // [split_k][M][N] fp32, or nullptr (then the planner never splits K)
   float out_scale;       // accumulators x this = the product: 2^-SY_W_SHIFT / (the activation pair's scale)
   float c_scale;         // SWIGLU only: scale of the output pair (SY_ACT_SCALE)
+  bool a_paired;         // the activations are one paired array (see a); only with tiles of one K step per stage
+  bool c_paired;         // SWIGLU only: write the output pair as one paired array [M][N/2 / 32][hi 32 | lo 32] to c
 };
+// Element offset of column `col` inside a row of a paired array (row pitch: 2 x columns); the low part is 32 on.
+__host__ __device__ __forceinline__ size_t pair_col(int col) { return (size_t)(col >> 5) * 64 + (col & 31); }
 #define SY_MAX_K_SLICES 8
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t s);
 int gemm_pick_split(const GemmArgs& g);                             // K slices launch_gemm should be given (1 without c_parts)

@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
                                                       const bf16_t* __restrict__ gain,
                                                       const int32_t* __restrict__ rows,
                                                       uint16_t* __restrict__ y, uint16_t* __restrict__ y_lo, int d,
-                                                      float eps, bool lo_off) {
+                                                      float eps, bool lo_off, bool paired) {
   const int r = blockIdx.x;
   const size_t row_at = (size_t)(rows ? rows[r] : r) * d;
   float* src = x + row_at;
@@ -63,8 +63,9 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
   const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps) * SY_Y_SCALE;
-  uint16_t* dst = y + (size_t)r * d;
-  uint16_t* dst_lo = y_lo + (size_t)r * d;
+  // the pair as two arrays [rows][d], or (paired) as one array [rows][d / 32][hi 32 | lo 32]
+  uint16_t* dst = y + (size_t)r * d * (paired ? 2 : 1);
+  uint16_t* dst_lo = paired ? dst + 32 : y_lo + (size_t)r * d;
   for (int c = threadIdx.x * 4; c < d; c += 256 * 4) {
     float4 v = *reinterpret_cast<const float4*>(src + c);
     uint2 g = *reinterpret_cast<const uint2*>(gain + c);
@@ -73,8 +74,9 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float* __restrict__ x, con
     uint2 hi, lo;
     split_f16x2(o0, o1, hi.x, lo.x);
     split_f16x2(o2, o3, hi.y, lo.y);
-    *reinterpret_cast<uint2*>(dst + c) = hi;
-    *reinterpret_cast<uint2*>(dst_lo + c) = lo_off ? make_uint2(0u, 0u) : lo;
+    const size_t at = paired ? pair_col(c) : (size_t)c;
+    *reinterpret_cast<uint2*>(dst + at) = hi;
+    *reinterpret_cast<uint2*>(dst_lo + at) = lo_off ? make_uint2(0u, 0u) : lo;
   }
 }
 
@@ -86,7 +88,7 @@ template <int IT>
 __global__ __launch_bounds__(256) void rmsnorm_row_in_registers_kernel(
     float* __restrict__ x, const float* __restrict__ parts, int n_parts, size_t part_stride,
     const bf16_t* __restrict__ gain, const int32_t* __restrict__ rows, uint16_t* __restrict__ y,
-    uint16_t* __restrict__ y_lo, int d, float eps, bool lo_off) {
+    uint16_t* __restrict__ y_lo, int d, float eps, bool lo_off, bool paired) {
   const int r = blockIdx.x;
   const size_t row_at = (size_t)(rows ? rows[r] : r) * d;
   float* src = x + row_at;
@@ -127,8 +129,9 @@ __global__ __launch_bounds__(256) void rmsnorm_row_in_registers_kernel(
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
   const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) / (float)d + eps) * SY_Y_SCALE;
-  uint16_t* dst = y + (size_t)r * d;
-  uint16_t* dst_lo = y_lo + (size_t)r * d;
+  // the pair as two arrays [rows][d], or (paired) as one array [rows][d / 32][hi 32 | lo 32]
+  uint16_t* dst = y + (size_t)r * d * (paired ? 2 : 1);
+  uint16_t* dst_lo = paired ? dst + 32 : y_lo + (size_t)r * d;
 #pragma unroll
   for (int k = 0; k < IT; ++k) {
     const int c = threadIdx.x * 4 + k * 1024;
@@ -139,21 +142,22 @@ __global__ __launch_bounds__(256) void rmsnorm_row_in_registers_kernel(
     uint2 hi, lo;
     split_f16x2(o0, o1, hi.x, lo.x);
     split_f16x2(o2, o3, hi.y, lo.y);
-    *reinterpret_cast<uint2*>(dst + c) = hi;
-    *reinterpret_cast<uint2*>(dst_lo + c) = lo_off ? make_uint2(0u, 0u) : lo;
+    const size_t at = paired ? pair_col(c) : (size_t)c;
+    *reinterpret_cast<uint2*>(dst + at) = hi;
+    *reinterpret_cast<uint2*>(dst_lo + at) = lo_off ? make_uint2(0u, 0u) : lo;
   }
 }
 
 hipError_t launch_rmsnorm(float* x, const float* parts, int n_parts, size_t part_stride, const bf16_t* gain,
                           const int32_t* rows, uint16_t* y_hi, uint16_t* y_lo, int n_rows, int d, float eps,
-                          bool lo_off, hipStream_t s) {
+                          bool lo_off, bool paired, hipStream_t s) {
   if (n_rows <= 0) return hipSuccess;
   if (d <= 4096)
-    rmsnorm_row_in_registers_kernel<4><<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps, lo_off);
+    rmsnorm_row_in_registers_kernel<4><<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps, lo_off, paired);
   else if (d <= 8192)
-    rmsnorm_row_in_registers_kernel<8><<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps, lo_off);
+    rmsnorm_row_in_registers_kernel<8><<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps, lo_off, paired);
   else
-    rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps, lo_off);
+    rmsnorm_kernel<<<n_rows, 256, 0, s>>>(x, parts, n_parts, part_stride, gain, rows, y_hi, y_lo, d, eps, lo_off, paired);
   return hipGetLastError();
 }
 

@@ -12,6 +12,7 @@ void gemm_force_variant(int v) { g_forced = v; }
 
 static bool tile_fits(const GemmArgs& g, int mt, int nf, int ksub) {
   if (mt < 1 || (nf == 4 ? mt > 17 : mt > 12)) return false;
+  if (g.a_paired && ksub != 1) return false;                       // the paired activation array: one K step per stage
   if (ksub == 2 && (nf == 4 ? mt > 5 : mt > 9)) return false;      // three stages of 128-byte rows must fit the LDS
   if (g.K % (32 * ksub) != 0) return false;
   const int bn = 64 * nf;
@@ -49,7 +50,7 @@ static double plan_cost(const GemmArgs& g, int mt, int nf, int ksub, int split) 
   const long rounds = (tiles * split + 255) / 256;
   const double steps = (double)(g.K / (32 * ksub)) / split;
   const double merge = split > 1 ? 2.4 * split * ((double)g.M * g.N / 2.2e6) : 0.0;
-  return rounds * steps * step_us(mt, nf, g.a_lo != nullptr, ksub) + merge;
+  return rounds * steps * step_us(mt, nf, g.a_lo != nullptr || g.a_paired, ksub) + merge;
 }
 
 static void pick(const GemmArgs& g, int* mt_out, int* nf_out, int* ksub_out, int* split_out) {
@@ -117,9 +118,11 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
   pick(g, &mt, &nf, &ksub, &split);
   if (mt < 0 || g.split_k > g.K / 32 || g.split_k > SY_MAX_K_SLICES) return hipErrorInvalidValue;
   if (g.split_k > 1 && (!g.c_parts || g.epilogue == GEMM_SWIGLU)) return hipErrorInvalidValue;
-  if (!g.a_lo && g.epilogue != GEMM_STORE_F32) return hipErrorInvalidValue;
+  if (!g.a_lo && !g.a_paired && g.epilogue != GEMM_STORE_F32) return hipErrorInvalidValue;
+  if (g.a_paired && ksub != 1) return hipErrorInvalidValue;
+  if (g.c_paired && g.epilogue != GEMM_SWIGLU) return hipErrorInvalidValue;
   if (g.epilogue == GEMM_SWIGLU) {
-    if (!g.c_lo || !g.w[1]) return hipErrorInvalidValue;
+    if ((!g.c_lo && !g.c_paired) || !g.w[1]) return hipErrorInvalidValue;
   } else {
     long rows = 0;
     for (int i = 0; i < 3; ++i) rows += g.w_rows[i];

@@ -71,8 +71,13 @@ __device__ __forceinline__ int swz16(int row, int chunk) {
   return (row * CPR + (chunk ^ (((row >> 1) & 3) << (CPR == 8 ? 1 : 0)))) * 8;
 }
 
-template <int MT, int NF, int EPI, bool LO = true, int KSUB = 1>
+template <int MT, int NF, int EPI, bool LO = true, int KSUB = 1, bool PAIRED = false>
 __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
+  // PAIRED: the activations come as one array [M][K / 32][hi 32 | lo 32] (GemmArgs::a, a_lo unused): the 64 bytes of
+  // a row's high part and the 64 of its low part for one K step are one 128-byte line, so an activation copy moves
+  // 8 whole lines instead of 16 half lines (the tall tiles run into the rate at which L2 takes requests).  In LDS an
+  // activation row is then those 128 bytes (chunks 0..3 high, 4..7 low); the weight rows keep their 64.
+  static_assert(!PAIRED || (LO && KSUB == 1), "paired activations: two terms, one MFMA K step per stage");
   // KSUB MFMA K steps per stage and barrier (BK = 32 KSUB).  KSUB = 2, for the short tiles whose three stages still
   // fit: half the barriers and full 128-byte rows per copy (half the requests to L2 for the same bytes).
   constexpr int BM = 16 * MT, BN = 64 * NF, BK = 32 * KSUB;
@@ -128,6 +133,14 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
     const int r = grp * RPI + lane / CPR;
     const int ch = (lane % CPR) ^ (((r >> 1) & 3) << (CPR == 8 ? 1 : 0));
     const uint16_t* base;
+    if (PAIRED && grp < A_INS) {                 // 8 activation rows of 128 bytes
+      const int r8 = grp * 8 + lane / 8;
+      int am = m0 + r8;
+      am = am < M ? am : M - 1;                  // rows past M are copied (clamped) and never stored
+      src[j] = g.a + (size_t)am * 2 * K + (size_t)step_begin * 64 + (((lane % 8) ^ (((r8 >> 1) & 3) << 1)) * 8);
+      dst[j] = grp * 1024;
+      continue;
+    }
     if (r < TERMS * BM) {
       int am = m0 + (r < BM ? r : r - BM);
       am = am < M ? am : M - 1;                  // rows past M are copied (clamped) and never stored
@@ -164,6 +177,7 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
     for (int j = 0; j < NF; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int l16 = lane & 15, kc = lane >> 4;
+  const int a_pair[2] = {swz16<8>(l16, kc), swz16<8>(l16, 4 + kc)};   // PAIRED: high and low fragment of a 128-byte row
   int a_off[KSUB], w_off[KSUB];                                   // per K sub-step; + i * 16 rows (+ BM rows: lo), + j * 16 rows
 #pragma unroll
   for (int ks = 0; ks < KSUB; ++ks) {
@@ -174,7 +188,7 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
   // and the two packed again (exact: 8 mantissa bits into 11).  A zero becomes 2^(SY_W_SHIFT - 127) in fp32 and
   // goes back to zero in the packing.
   const uint32_t exp_add = ((uint32_t)SY_W_SHIFT << 7) * 0x00010001u, hi_mask = 0xFFFF0000u;
-#define SY_COPY(J_, NXT, STEP) glds16_at(src[J_] + (size_t)(STEP) * BK, NXT + dst[J_]);
+#define SY_COPY(J_, NXT, STEP) glds16_at(src[J_] + (size_t)(STEP) * (PAIRED && (J_) < A_IPW ? 64 : BK), NXT + dst[J_]);
 #define SY_ISSUE(NXT, STEP) _Pragma("unroll") for (int j = 0; j < IPW; ++j) SY_COPY(j, NXT, STEP)
 #define SY_MFMA(ACC, FW, FA, I_)                                                                  \
   {                                                                                               \
@@ -213,14 +227,15 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
 // One K step on the stage CUR with this step's weight fragments fw already converted in registers.  The copies
 // of step s+2 go out during the first row blocks; during the last four the weights of step s+1 (NEXTSTAGE) are
 // read and converted, two instructions after each MFMA, in the shadow of the matrix core.
-#define SY_AT(V_) (a_off[(V_) % KSUB] + ((V_) / KSUB) * 16 * BK)
+#define SY_AT(V_) (PAIRED ? a_pair[0] + (V_) * 16 * 64 : a_off[(V_) % KSUB] + ((V_) / KSUB) * 16 * BK)
+#define SY_AT_LO(V_) (PAIRED ? a_pair[1] + (V_) * 16 * 64 : a_off[(V_) % KSUB] + ((V_) / KSUB) * 16 * BK + BM * BK)
 #define SY_MULT(STAGE, NXT, NSTEP, NEXTSTAGE)                                                     \
   {                                                                                               \
     u32x4 fa[MV + 2], fl[MV + 2], fwn[NW];                                                        \
     uint32_t tq[4];                                                                               \
     _Pragma("unroll") for (int v = 0; v < 2 && v < MV; ++v) {                                     \
       fa[v] = *reinterpret_cast<const u32x4*>(STAGE + SY_AT(v));                                  \
-      if (LO) fl[v] = *reinterpret_cast<const u32x4*>(STAGE + SY_AT(v) + BM * BK);                \
+      if (LO) fl[v] = *reinterpret_cast<const u32x4*>(STAGE + SY_AT_LO(v));                       \
     }                                                                                             \
     __builtin_amdgcn_sched_barrier(0);                                                            \
     _Pragma("unroll") for (int v = 0; v < MV; ++v) {                                              \
@@ -234,7 +249,7 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
         }                                                                                         \
         if (t == 0 && v + 2 < MV) fa[v + 2] = *reinterpret_cast<const u32x4*>(STAGE + SY_AT(v + 2)); \
         if (LO && t == NF && v + 2 < MV)                                                          \
-          fl[v + 2] = *reinterpret_cast<const u32x4*>(STAGE + SY_AT(v + 2) + BM * BK);            \
+          fl[v + 2] = *reinterpret_cast<const u32x4*>(STAGE + SY_AT_LO(v + 2));                   \
         _Pragma("unroll") for (int c = 0; c < CPB; ++c)                                           \
             if ((c + 1) % SLOTS == t && v < C_END && v * CPB + c < IPW) SY_COPY(v * CPB + c, NXT, NSTEP) \
         __builtin_amdgcn_sched_barrier(0);                                                        \
@@ -293,6 +308,7 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
 #undef SY_NEXT_W
 #undef SY_MULT
 #undef SY_AT
+#undef SY_AT_LO
 #undef SY_STEP
   // The surplus copies of the last steps are still in flight: let them land before the block's LDS is released;
   // MFMA results settle before they are read.  The empty statements "rewrite" each accumulator: every later read
@@ -324,9 +340,16 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
         uint32_t h0, l0_, h1, l1_;
         split_f16x2(v[0], v[1], h0, l0_);
         split_f16x2(v[2], v[3], h1, l1_);
-        const size_t at = (size_t)m * (g.N >> 1) + (n0 >> 1) + (wave * (NF / 2) + (j >> 1)) * 16 + nq;
-        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c) + at) = make_uint2(h0, h1);
-        *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c_lo) + at) = make_uint2(l0_, l1_);
+        const int col = (n0 >> 1) + (wave * (NF / 2) + (j >> 1)) * 16 + nq;
+        if (g.c_paired) {
+          uint16_t* at = reinterpret_cast<uint16_t*>(g.c) + (size_t)m * g.N + pair_col(col);
+          *reinterpret_cast<uint2*>(at) = make_uint2(h0, h1);
+          *reinterpret_cast<uint2*>(at + 32) = make_uint2(l0_, l1_);
+        } else {
+          const size_t at = (size_t)m * (g.N >> 1) + col;
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c) + at) = make_uint2(h0, h1);
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.c_lo) + at) = make_uint2(l0_, l1_);
+        }
       }
     } else {
       float* c = (g.split_k > 1 ? g.c_parts + (size_t)blockIdx.z * M * g.N : reinterpret_cast<float*>(g.c)) +
@@ -353,10 +376,23 @@ static hipError_t launch_proj(const GemmArgs& g, hipStream_t s) {
   const int m_tiles = (g.M + BM - 1) / BM, n_tiles = g.N / (64 * NF);
   const dim3 grid(8 * ((n_tiles + 7) / 8) * m_tiles, 1, g.split_k);
   if (g.K % (32 * KSUB) != 0) return hipErrorInvalidValue;
-  if (!g.a_lo) {                                 // single-term activations: the plain store form only
+  if (!g.a_lo && !g.a_paired) {                  // single-term activations: the plain store form only
     if (g.epilogue != GEMM_STORE_F32) return hipErrorInvalidValue;
     proj_kernel<MT, NF, GEMM_STORE_F32, false, KSUB><<<grid, 256, 0, s>>>(g);
     return hipGetLastError();
+  }
+  if (g.a_paired) {                              // one array [M][K / 32][hi | lo]: the forms with one K step per stage
+    if constexpr (KSUB == 1) {
+      switch (g.epilogue) {
+        case GEMM_STORE_F32: proj_kernel<MT, NF, GEMM_STORE_F32, true, 1, true><<<grid, 256, 0, s>>>(g); break;
+        case GEMM_ADD_F32: proj_kernel<MT, NF, GEMM_ADD_F32, true, 1, true><<<grid, 256, 0, s>>>(g); break;
+        case GEMM_SWIGLU: proj_kernel<MT, NF, GEMM_SWIGLU, true, 1, true><<<grid, 256, 0, s>>>(g); break;
+        default: return hipErrorInvalidValue;
+      }
+      return hipGetLastError();
+    } else {
+      return hipErrorInvalidValue;
+    }
   }
   switch (g.epilogue) {
     case GEMM_STORE_F32: proj_kernel<MT, NF, GEMM_STORE_F32, true, KSUB><<<grid, 256, 0, s>>>(g); break;

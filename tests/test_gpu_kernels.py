@@ -261,6 +261,59 @@ def test_gemm_every_tile_and_epilogue(tile, M, N, K):
     assert ((got - glu).abs() - bound).max().item() < 0
 
 
+def _pairs(hi, lo):
+    """[M][K] high and low parts -> [M][K / 32][hi 32 | lo 32], the form the decoder layers hand activations over in."""
+    M, K = hi.shape
+    return torch.stack([hi.view(M, K // 32, 32), lo.view(M, K // 32, 32)], dim=2).contiguous()
+
+
+@pytest.mark.parametrize("tile", [-1] + list(range(1, 18)) + list(range(101, 113)))
+@pytest.mark.parametrize("M,N,K", [(1, 256, 64), (97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (600, 4096, 1792),
+                                   (545, 1792, 512)])
+def test_gemm_paired_activation_layout(tile, M, N, K):
+    """The activation pair as one array of whole 128-byte lines (hi and lo of a K block side by side): same MFMAs in
+    the same order as the two-array form, so a forced tile must give the same bits; the planner's own choice
+    (tile -1, which may differ between the forms) is held to the float64 product."""
+    synera = _synera()
+    g = torch.Generator(device=DEV).manual_seed(77 * M + N + K)
+    x = torch.randn((M, K), generator=g, device=DEV)
+    a, al = synera.split_pair(x)
+    ap = _pairs(a, al)
+    w = wl.draw_normal_bf16((N, K), 0.02, 23 * N + K, DEV)
+    half = N // 2
+    w0, w1 = w[:half].contiguous(), w[half:].contiguous()
+    base = torch.randn((M, N), generator=g, device=DEV)
+    synera.debug_set_gemm_tile(tile)
+    try:
+        c = torch.full((M, N), float("nan"), device=DEV)
+        synera.debug_gemm_epilogue(a, al, w, None, c, None, 0)
+        c_add = base.clone()
+        synera.debug_gemm_epilogue(a, al, w, None, c_add, None, 1)
+        act_hi = torch.empty((M, half), dtype=torch.float16, device=DEV)
+        act_lo = torch.empty_like(act_hi)
+        synera.debug_gemm_epilogue(a, al, w0, w1, act_hi, act_lo, 2)
+        cp = torch.full((M, N), float("nan"), device=DEV)
+        synera.debug_gemm_paired(ap, w, None, cp, 0)
+        cp_add = base.clone()
+        synera.debug_gemm_paired(ap, w, None, cp_add, 1)
+        actp = torch.full((M, half // 32, 2, 32), float("nan"), dtype=torch.float16, device=DEV)
+        synera.debug_gemm_paired(ap, w0, w1, actp, 2)
+        torch.cuda.synchronize()
+    finally:
+        synera.debug_set_gemm_tile(-1)
+    want = (a.double() + al.double()) @ w.double().T
+    tol = 6e-9 * K + 2e-7
+    assert (cp.double() - want).abs().max().item() < tol
+    if tile > 0:
+        assert torch.equal(cp, c) and torch.equal(cp_add, c_add)
+        assert torch.equal(actp[:, :, 0].reshape(M, half), act_hi) and torch.equal(actp[:, :, 1].reshape(M, half), act_lo)
+    else:
+        assert (cp_add.double() - (base.double() + want)).abs().max().item() < tol + 1e-6
+        got = (actp[:, :, 0].double() + actp[:, :, 1].double()).reshape(M, half)
+        ref = act_hi.double() + act_lo.double()
+        assert (got - ref).abs().max().item() <= 8 * tol * 4 + 2.0 ** -20 * ref.abs().max().item()
+
+
 @pytest.mark.parametrize("tile", [-1, 4, 8, 9, 13, 17, 104, 108, 112, 204, 205, 304, 308, 309])
 @pytest.mark.parametrize("M,N,K", [(97, 512, 1024), (289, 768, 320), (532, 1024, 4096), (545, 4096, 1792), (532, 1792, 2048),
                                    (24, 1792, 4096)])
