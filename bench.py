@@ -36,13 +36,14 @@ HBM_PEAK_GBS = 8000.0
 # workload as they were when the counters were read; if the planners of the library being timed answer
 # differently, the traffic fields are null.
 PROFILED_WORKLOAD = "c3_8b_b64_ragged"
-PROFILED_PLAN = "qkv=272x256/5;o=144x256/4;gate_up=272x256/1;down=272x256/8;lm_head=272x256/1;attention=512sh/21270pos/258cut"
+PROFILED_PLAN = "qkv=272x256pair/5;o=144x256pair/4;gate_up=272x256pair/1;down=272x256pair/8;lm_head=272x256/1;attention=512sh/21270pos/258cut"
 MEASURED_TRAFFIC_BYTES = {          # read + written, per launch
-    "gate_up": 390.0e6 + 30.5e6,        # 305 - 580 MB read from launch to launch; mean of two profiled runs
+    "gate_up": 341.0e6 + 30.5e6,        # 305 - 456 MB read from launch to launch
     "down": 361.9e6 + 69.7e6,
-    "qkv": 124.2e6 + 65.4e6,
+    "qkv": 122.0e6 + 65.4e6,
     "o": 103.6e6 + 34.9e6,
-    "attention": 332.8e6 + 15.7e6,
+    "attention": 333.0e6 + 15.7e6,
+    "lm_head": 302.0e6 + 68.1e6,
 }
 
 
