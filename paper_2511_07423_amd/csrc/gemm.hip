@@ -125,7 +125,10 @@ hipError_t launch_gemm(const GemmArgs& g, hipStream_t s) {
     if ((!g.c_lo && !g.c_paired) || !g.w[1]) return hipErrorInvalidValue;
   } else {
     long rows = 0;
-    for (int i = 0; i < 3; ++i) rows += g.w_rows[i];
+    for (int i = 0; i < 3; ++i) {
+      rows += g.w_rows[i];
+      if (g.w_rows[i] % 16 != 0) return hipErrorInvalidValue;   // a copy's 16 tile rows come from one array
+    }
     if (rows != g.N) return hipErrorInvalidValue;
   }
   if (ksub == 2) return launch_proj_k64(mt, nf, g, s);

@@ -58,8 +58,10 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
 // Asynchronous 16-byte-per-lane copy global -> LDS; m0 carries the wavefront-uniform LDS address, lane i lands
 // at that address + 16 i.  (Through the compiler builtin every later LDS read is preceded by a wait for ALL
 // copies in flight, which would serialise the pipeline.)
-__device__ __forceinline__ void glds16_at(const void* gptr, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+// The global address is a wavefront-uniform base (a scalar register pair, advanced along K with scalar adds) plus a
+// 32-bit byte offset per lane that never changes: no vector arithmetic per copy, half the address registers.
+__device__ __forceinline__ void glds16_at(const void* base, uint32_t lane_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(lane_off), "s"(base) : "memory", "m0");
 }
 // Element offset of 16-byte chunk `chunk` of tile row `row` (rows of CPR = 4 or 8 chunks: 64 or 128 bytes).  A
 // fragment read (lane = row l % 16, chunk 4 ks + l / 16) is served 16 lanes per cycle over the 64 banks, lanes
@@ -119,7 +121,8 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
   const int n_steps = (int)((long)(blockIdx.z + 1) * total_steps / g.split_k) - step_begin;
   if (n_steps <= 0) return;
 
-  const uint16_t* src[IPW];
+  const uint16_t* src[IPW];                      // wavefront-uniform part of the copy's global address
+  uint32_t off[IPW];                             // this lane's byte offset from it (constant along K)
   uint32_t dst[IPW];                             // byte offset of the copy's 16 rows inside a stage
 #pragma unroll
   for (int j = 0; j < IPW; ++j) {
@@ -132,21 +135,23 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
     }
     const int r = grp * RPI + lane / CPR;
     const int ch = (lane % CPR) ^ (((r >> 1) & 3) << (CPR == 8 ? 1 : 0));
-    const uint16_t* base;
+    dst[j] = grp * 1024;
     if (PAIRED && grp < A_INS) {                 // 8 activation rows of 128 bytes
       const int r8 = grp * 8 + lane / 8;
       int am = m0 + r8;
       am = am < M ? am : M - 1;                  // rows past M are copied (clamped) and never stored
-      src[j] = g.a + (size_t)am * 2 * K + (size_t)step_begin * 64 + (((lane % 8) ^ (((r8 >> 1) & 3) << 1)) * 8);
-      dst[j] = grp * 1024;
+      src[j] = g.a + (size_t)m0 * 2 * K + (size_t)step_begin * 64;
+      off[j] = (uint32_t)(am - m0) * (uint32_t)(4 * K) + (((lane % 8) ^ (((r8 >> 1) & 3) << 1)) * 16);
       continue;
     }
-    if (r < TERMS * BM) {
+    if (grp * RPI < TERMS * BM) {                // a group lies in one array: BM is a multiple of RPI
+      const int first = grp * RPI;
       int am = m0 + (r < BM ? r : r - BM);
       am = am < M ? am : M - 1;                  // rows past M are copied (clamped) and never stored
-      base = (r < BM ? g.a : g.a_lo) + (size_t)am * K;
+      src[j] = (first < BM ? g.a : g.a_lo) + (size_t)m0 * K + (size_t)step_begin * BK;
+      off[j] = (uint32_t)(am - m0) * (uint32_t)(2 * K) + ch * 16;
     } else {
-      const int col = r - TERMS * BM;
+      const int col = grp * RPI - TERMS * BM;    // the group's first column: all its rows are in one weight array
       int wrow;
       const bf16_t* wbase;
       if (EPI == GEMM_SWIGLU) {                  // 16-column groups alternate gate, up
@@ -164,10 +169,9 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
           }
         }
       }
-      base = wbase + (size_t)wrow * K;
+      src[j] = wbase + (size_t)wrow * K + (size_t)step_begin * BK;
+      off[j] = (uint32_t)(lane / CPR) * (uint32_t)(2 * K) + ch * 16;
     }
-    src[j] = base + (size_t)step_begin * BK + ch * 8;
-    dst[j] = grp * 1024;
   }
 
   f32x4 acc[MT][NF];
@@ -188,7 +192,7 @@ __global__ __launch_bounds__(256) void proj_kernel(GemmArgs g) {
   // and the two packed again (exact: 8 mantissa bits into 11).  A zero becomes 2^(SY_W_SHIFT - 127) in fp32 and
   // goes back to zero in the packing.
   const uint32_t exp_add = ((uint32_t)SY_W_SHIFT << 7) * 0x00010001u, hi_mask = 0xFFFF0000u;
-#define SY_COPY(J_, NXT, STEP) glds16_at(src[J_] + (size_t)(STEP) * (PAIRED && (J_) < A_IPW ? 64 : BK), NXT + dst[J_]);
+#define SY_COPY(J_, NXT, STEP) glds16_at(src[J_] + (size_t)(STEP) * (PAIRED && (J_) < A_IPW ? 64 : BK), off[J_], NXT + dst[J_]);
 #define SY_ISSUE(NXT, STEP) _Pragma("unroll") for (int j = 0; j < IPW; ++j) SY_COPY(j, NXT, STEP)
 #define SY_MFMA(ACC, FW, FA, I_)                                                                  \
   {                                                                                               \
