@@ -252,3 +252,67 @@ def test_a_request_with_nan_in_its_cache_leaves_the_others_untouched(monkeypatch
         assert np.array_equal(clean[name][cu[1]:], dirty[name][cu[1]:]), name
     for name in ("accept_len", "correction"):
         assert np.array_equal(clean[name][1:], dirty[name][1:]), name
+
+
+def test_both_forms_of_the_activation_pair_give_the_same_bits():
+    """A projection whose stage holds one 32-wide K block reads its (hi, lo) activations as one array of whole
+    128-byte lines, written that way by RMSNorm, by the attention's normalising store and by the SwiGLU epilogue;
+    otherwise as two arrays.  Same tile, same MFMAs in the same order: with the tile forced, the verify must give
+    the same bits in both forms (the two-array form is kept by the low-part switch of the LM head's input, which
+    changes no arithmetic: the LM head runs on the high part either way), and the planner's own choice for this
+    small shape (64-wide stages, two arrays) must agree to rounding."""
+    import paper_2511_07423_amd as synera
+    shape = wl.ModelShape("pairs", 2, 512, 8, 2, 64, 1024, 512)
+    head = wl.draw_head_weights(shape, 61, DEV)
+    layers = [wl.draw_layer_weights(shape, 61, l, DEV) for l in range(shape.n_layers)]
+    g = torch.Generator(device=DEV).manual_seed(62)
+    rng = np.random.default_rng(63)
+    B = 20
+    ctx = rng.integers(0, 400, B).astype(np.int32)
+    k = rng.integers(1, 33, B).astype(np.int32)
+    k[0], k[1] = 32, 1
+    T = int(k.sum())
+    assert T > 144
+    need = (ctx + k + 15) // 16
+    n_pages, max_pages = int(need.sum()), int(need.max())
+    bt = np.full((B, max_pages), -1, np.int32)
+    perm, at = rng.permutation(n_pages), 0
+    for i in range(B):
+        bt[i, :need[i]] = perm[at:at + need[i]]
+        at += int(need[i])
+    pool = (shape.n_layers, n_pages, shape.n_kv_heads)
+    k_pool = torch.randn(pool + (wl.PAGE_SIZE, shape.head_dim), generator=g, device=DEV).to(torch.bfloat16)
+    v_pool = torch.randn(pool + (shape.head_dim, wl.PAGE_SIZE), generator=g, device=DEV).to(torch.bfloat16)
+    toks = torch.from_numpy(rng.integers(0, shape.vocab, T).astype(np.int32)).to(DEV)
+    anchor = torch.from_numpy(rng.integers(0, shape.vocab, B).astype(np.int32)).to(DEV)
+    ver = synera.Verifier(shape, head, layers, max_batch=B, max_tokens=T, max_pages=max_pages)
+    zeros = np.zeros(B, np.int32)
+    qkv_n = (shape.n_q_heads + 2 * shape.n_kv_heads) * shape.head_dim
+
+    def run(tile, lo_off):
+        synera.debug_set_gemm_tile(tile)
+        ver.debug_set_lo_off(lo_off)
+        try:
+            stage_k = [synera.debug_gemm_plan_bk(T, n, kk, epi, 1) for n, kk, epi in
+                       ((qkv_n, shape.d_model, 0), (shape.d_model, shape.n_q_heads * shape.head_dim, 1),
+                        (2 * shape.d_ffn, shape.d_model, 2), (shape.d_model, shape.d_ffn, 1))]
+            kp, vp = k_pool.clone(), v_pool.clone()
+            out = ver.verify(ctx, zeros, k, toks, anchor, bt, n_pages, kp, vp, want_logits=True)
+            torch.cuda.synchronize()
+        finally:
+            synera.debug_set_gemm_tile(-1)
+            ver.debug_set_lo_off(0)
+        res = {n: v.cpu().numpy() for n, v in out.items() if v is not None}
+        res["k_pool"], res["v_pool"] = kp.view(torch.int16).cpu().numpy(), vp.view(torch.int16).cpu().numpy()
+        return res, stage_k
+
+    planned, sk0 = run(-1, [])
+    paired, sk1 = run(108, [])                     # 128 x 128 tiles, one 32-wide K block per stage: one paired array
+    two, sk2 = run(108, ["lm_head_in"])            # the same tiles on two arrays
+    ver.close()
+    assert sk1 == [32, 32, 32, 32] and sk2 == [32, 32, 32, 32], (sk1, sk2)
+    assert all(np.isfinite(v).all() for n, v in paired.items() if n not in ("k_pool", "v_pool"))
+    for name in paired:
+        assert np.array_equal(paired[name], two[name]), name
+    assert np.abs(paired["logits"] - planned["logits"]).max() < 1e-4, sk0
+    assert np.array_equal(paired["accept_len"], planned["accept_len"])
