@@ -158,7 +158,7 @@ int32_t synera_validate_batch(int32_t B, const int32_t* h_ctx_len, const int32_t
  *                           only for requests with u_i == 0 (otherwise the row of
  *                           the last uncached token supplies q(x|prefix))
  *   h_block_table host [B][max_pages]
- *   d_k_pool, d_v_pool   dev, layout above, n_pages_in_pool pages per layer
+ *   d_k_pool, d_v_pool   dev, layout above, n_pages_in_pool pages per layer, 16-byte aligned
  * Outputs (device).  R = sum k_i rows, request-major, one per draft position:
  *   d_logits    f32 [R][vocab]   may be NULL
  *   d_argmax    i32 [R]          greedy token AFTER draft j (lowest id on ties)
@@ -169,7 +169,7 @@ int32_t synera_validate_batch(int32_t B, const int32_t* h_ctx_len, const int32_t
  *                          and a_j the argmax of draft j-1's row
  *   d_correction  i32 [B]  a_{n_i} (for n_i == k_i the token after the last draft)
  * Errors: as synera_validate_batch (limits from synera_create), EINVAL for null
- * required pointers, EHIP.
+ * required pointers and for pools that are not 16-byte aligned, EHIP.
  */
 int32_t synera_verify(synera_ctx* ctx, int32_t B, const int32_t* h_ctx_len,
                       const int32_t* h_n_uncached, const int32_t* h_n_draft,

@@ -781,6 +781,8 @@ extern "C" int32_t synera_verify(synera_ctx* c, int32_t B, const int32_t* h_ctx_
   if (!c || !h_n_uncached || !d_tokens || !d_anchor || !d_k_pool || !d_v_pool || !d_argmax || !d_accept_len ||
       !d_correction)
     return SYNERA_EINVAL;
+  // the attention kernel copies 16 bytes per lane out of the pools
+  if (((reinterpret_cast<uintptr_t>(d_k_pool) | reinterpret_cast<uintptr_t>(d_v_pool)) & 15) != 0) return SYNERA_EINVAL;
   if (max_pages > c->max_pages) return SYNERA_ENOSPC;
   int32_t st = synera_validate_batch(B, h_ctx_len, h_n_draft, h_n_uncached, h_block_table, max_pages,
                                      n_pages_in_pool, c->max_batch, c->max_tokens, SYNERA_MAX_CHUNK);

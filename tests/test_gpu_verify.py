@@ -316,3 +316,31 @@ def test_both_forms_of_the_activation_pair_give_the_same_bits():
         assert np.array_equal(paired[name], two[name]), name
     assert np.abs(paired["logits"] - planned["logits"]).max() < 1e-4, sk0
     assert np.array_equal(paired["accept_len"], planned["accept_len"])
+
+
+def test_pools_that_are_not_16_byte_aligned_are_refused():
+    """The attention kernel copies 16 bytes per lane straight out of the pools: a pool pointer off that alignment is
+    an argument error, raised before anything is launched."""
+    import paper_2511_07423_amd as synera
+    shape = _mini_shape()
+    head = wl.draw_head_weights(shape, 71, DEV)
+    layers = [wl.draw_layer_weights(shape, 71, l, DEV) for l in range(shape.n_layers)]
+    ctx, k = np.array([20], np.int32), np.array([4], np.int32)
+    bt = np.array([[0, 1]], np.int32)
+    n = shape.n_layers * 2 * shape.n_kv_heads * wl.PAGE_SIZE * shape.head_dim
+    flat_k = torch.zeros(n + 8, dtype=torch.bfloat16, device=DEV)
+    flat_v = torch.zeros(n + 8, dtype=torch.bfloat16, device=DEV)
+    shp_k = (shape.n_layers, 2, shape.n_kv_heads, wl.PAGE_SIZE, shape.head_dim)
+    shp_v = (shape.n_layers, 2, shape.n_kv_heads, shape.head_dim, wl.PAGE_SIZE)
+    toks = torch.zeros(4, dtype=torch.int32, device=DEV)
+    anchor = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ver = synera.Verifier(shape, head, layers, max_batch=1, max_tokens=4, max_pages=2)
+    zeros = np.zeros(1, np.int32)
+    good = ver.verify(ctx, zeros, k, toks, anchor, bt, 2, flat_k[:n].view(shp_k), flat_v[:n].view(shp_v))
+    torch.cuda.synchronize()
+    assert good["argmax"].shape[0] == 4
+    for kp, vp in ((flat_k[1:n + 1].view(shp_k), flat_v[:n].view(shp_v)), (flat_k[:n].view(shp_k), flat_v[4:n + 4].view(shp_v))):
+        with pytest.raises(synera.SyneraError) as e:
+            ver.verify(ctx, zeros, k, toks, anchor, bt, 2, kp, vp)
+        assert e.value.status == synera.EINVAL
+    ver.close()
